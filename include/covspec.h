@@ -1,0 +1,132 @@
+/*
+ * covspec.h -- C ABI of the MI355X (gfx950) visual-token-reduction library.
+ *
+ * The library implements the training-free visual token selection of CoVSpec
+ * (paper Section III-A, "Visual Token Selection"): score every visual token on
+ * query relevance and token activity, fuse the two scores, pre-select the M
+ * best, measure each pre-selected token's energy in the top-r singular
+ * subspace, keep the B_vis = k tokens with the largest energy and gather their
+ * feature rows.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every data pointer is DEVICE memory owned by the caller.  The library
+ *    never allocates or frees memory; scratch space comes from `workspace`.
+ *  - All tensors are dense row-major.  B images are independent.
+ *  - `dtype` (0 = fp32, 1 = bf16) is the storage type of X, hidden, Q, Wq, Wk
+ *    and of the gathered tokens.  Scores are fp32, indices are int32.
+ *  - Work is enqueued on `stream`; calls return without synchronising.  Outputs
+ *    are valid once the caller has synchronised the stream.
+ *  - Arguments are validated on the host before anything is launched.  Return
+ *    value: COVSPEC_OK or one of the codes below; no exception crosses the ABI.
+ *  - The library keeps no global state; concurrent calls are safe when they use
+ *    distinct workspaces.
+ *  - Ties in every ranking go to the lower index.  Ranking decisions are taken
+ *    on the fp32 score values that the library returns.
+ */
+#ifndef COVSPEC_H
+#define COVSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Opaque stream handle: pass a hipStream_t (NULL = the default stream). */
+typedef void* covspec_stream_t;
+
+enum {
+  COVSPEC_OK = 0,
+  COVSPEC_INVALID_ARG = 1,         /* NULL required pointer, bad size / mode / lambda ...        */
+  COVSPEC_WORKSPACE_TOO_SMALL = 2, /* workspace_bytes < covspec_workspace_size(params)            */
+  COVSPEC_UNSUPPORTED = 3,         /* valid request outside the kernels' limits (see below)       */
+  COVSPEC_HIP_ERROR = 4            /* a launch failed; hipGetLastError() still holds the cause    */
+};
+
+enum { COVSPEC_FP32 = 0, COVSPEC_BF16 = 1 };
+
+/* Query-relevance definition.
+ *   COSINE_MAX   : S^query_i = max_j cos(e(v_i), e(q_j))  (paper Sec. III-A.1, query-aware score).
+ *   ATTN_SOFTMAX : variant that is NOT in the paper: per head, softmax over the visual tokens of
+ *                  e(q_j)_h . e(v_i)_h / sqrt(d/H), averaged over heads and query tokens.        */
+enum { COVSPEC_REL_COSINE_MAX = 0, COVSPEC_REL_ATTN_SOFTMAX = 1 };
+
+/* Low-rank stage.
+ *   ENERGY_TOPK     : rank-r truncated SVD of the pre-selected tokens, c_i = ||(V_r Sigma_r)_i||^2,
+ *                     keep the k largest (paper Sec. III-A.3).
+ *   GREEDY_RESIDUAL : variant that is NOT in the paper: k greedy picks, each the token with the
+ *                     largest residual after projecting out the tokens already picked
+ *                     (pivoted Cholesky of the token Gram matrix).                               */
+enum { COVSPEC_LR_ENERGY_TOPK = 0, COVSPEC_LR_GREEDY_RESIDUAL = 1 };
+
+typedef struct covspec_params {
+  int32_t batch;        /* B >= 1 images                                                          */
+  int32_t n_tokens;     /* N visual tokens per image, 1 <= N <= 16384                              */
+  int32_t d_model;      /* d feature width; multiple of 8 (bf16) or 4 (fp32)                      */
+  int32_t n_query;      /* T >= 1 query-keyword embeddings per image (no padding mask)            */
+  int32_t n_heads;      /* H; used by ATTN_SOFTMAX only, which needs d / H == 128                 */
+  int32_t n_act_layers; /* K in [0, 8]; hidden holds K+1 slices; K = 0 drops the activity term    */
+  int32_t dtype;        /* COVSPEC_FP32 / COVSPEC_BF16                                            */
+  int32_t rel_mode;     /* COVSPEC_REL_*                                                          */
+  int32_t lr_mode;      /* COVSPEC_LR_*                                                           */
+  int32_t preselect_m;  /* M; 0 => min(N, 2k).  k <= M <= N, M <= 4096                            */
+  int32_t rank_r;       /* r; 0 => max(1, k/2).  1 <= r < min(M, d) (ENERGY_TOPK only)            */
+  int32_t keep_k;       /* k; 0 => floor(keep_ratio*N + 0.5) clamped to [1, M]                    */
+  float keep_ratio;     /* used only when keep_k == 0; must then be in (0, 1]                     */
+  float lambda;         /* fusion weight of the query score, in [0, 1] (paper fusion equation)    */
+} covspec_params;
+
+/* Bytes of device scratch that any of the three entry points needs for `p` (0 if `p` is invalid
+ * or unsupported).  The workspace must be 256-byte aligned. */
+size_t covspec_workspace_size(const covspec_params* p);
+
+/* Resolve the defaults of `p` (k, M, r) exactly as the entry points do.  Returns a status code. */
+int covspec_resolve(const covspec_params* p, int32_t* keep_k, int32_t* preselect_m, int32_t* rank_r);
+
+/*
+ * Scores (paper Sec. III-A.1 and III-A.2, fusion equation).
+ *   X      [B, N, d]      visual token features (also the representation z_i of the low-rank stage)
+ *   hidden [B, K+1, N, d] hidden states of the K+1 last layers, oldest first; NULL (or K = 0) drops
+ *                         the activity term and makes s_fused the normalised query score
+ *   Q      [B, T, d]      query-keyword features
+ *   Wq, Wk [d, d]         embedding maps, [d_in, d_out]: e(q) = q Wq, e(v) = v Wk; NULL = identity
+ *   s_query, s_act, s_fused [B, N] fp32 outputs; each may be NULL (s_act is untouched when the
+ *                         activity term is dropped)
+ * Both scores are min-max normalised per image before fusion; a constant score normalises to 0.
+ */
+int covspec_score(const covspec_params* p, const void* X, const void* hidden, const void* Q,
+                  const void* Wq, const void* Wk, float* s_query, float* s_act, float* s_fused,
+                  void* workspace, size_t workspace_bytes, covspec_stream_t stream);
+
+/*
+ * Selection from caller-supplied fused scores (paper Sec. III-A.3).
+ *   X        [B, N, d]   features; s_fused [B, N] fp32
+ *   idx_out  [B, k]      kept token positions in [0, N), ascending              (required)
+ *   c_out    [B, M]      ENERGY_TOPK: subspace energy of the pre-selected tokens, in idx_m order;
+ *                        GREEDY_RESIDUAL: untouched                              (or NULL)
+ *   idx_m_out[B, M]      pre-selected positions, ascending                       (or NULL)
+ *   pick_order_out [B,k] GREEDY_RESIDUAL: token positions in pick order          (or NULL)
+ *   resid_out [B, k]     GREEDY_RESIDUAL: residual squared norm at each pick     (or NULL)
+ */
+int covspec_select(const covspec_params* p, const void* X, const float* s_fused, int32_t* idx_out,
+                   float* c_out, int32_t* idx_m_out, int32_t* pick_order_out, float* resid_out,
+                   void* workspace, size_t workspace_bytes, covspec_stream_t stream);
+
+/*
+ * Whole path: score, fuse, select, gather (paper Sec. III-A).
+ *   idx_out    [B, k]     kept positions, ascending                              (required)
+ *   tokens_out [B, k, d]  bit copies of X[b, idx_out[b, j], :], same dtype as X  (required)
+ */
+int covspec_reduce(const covspec_params* p, const void* X, const void* hidden, const void* Q,
+                   const void* Wq, const void* Wk, int32_t* idx_out, void* tokens_out,
+                   void* workspace, size_t workspace_bytes, covspec_stream_t stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* covspec_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COVSPEC_H */

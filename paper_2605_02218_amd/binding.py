@@ -1,0 +1,204 @@
+"""ctypes binding of libcovspec.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+include/covspec.h; this module converts torch tensors to device pointers,
+supplies the current HIP stream and allocates outputs / workspace.  There is
+no CPU fallback: a missing library raises at import of the symbols.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcovspec.so")
+
+FP32, BF16 = 0, 1
+REL_COSINE_MAX, REL_ATTN_SOFTMAX = 0, 1
+LR_ENERGY_TOPK, LR_GREEDY_RESIDUAL = 0, 1
+OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
+
+EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
+           "covspec_reduce", "covspec_status_string")
+
+
+class CovspecParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "n_tokens", "d_model", "n_query", "n_heads", "n_act_layers", "dtype",
+        "rel_mode", "lr_mode", "preselect_m", "rank_r", "keep_k")] + [
+        ("keep_ratio", ctypes.c_float), ("lambda_", ctypes.c_float)]
+
+
+class CovspecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libcovspec.so (built by paper_2605_02218_amd.build); fail loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s not found: run `python -m paper_2605_02218_amd.build` (or __graft_entry__.build()) first"
+                          % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, pp = ctypes.c_void_p, ctypes.POINTER(CovspecParams)
+    lib.covspec_workspace_size.restype = ctypes.c_size_t
+    lib.covspec_workspace_size.argtypes = [pp]
+    lib.covspec_resolve.restype = ctypes.c_int
+    lib.covspec_resolve.argtypes = [pp] + [ctypes.POINTER(ctypes.c_int32)] * 3
+    lib.covspec_score.restype = ctypes.c_int
+    lib.covspec_score.argtypes = [pp] + [vp] * 8 + [vp, ctypes.c_size_t, vp]
+    lib.covspec_select.restype = ctypes.c_int
+    lib.covspec_select.argtypes = [pp] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
+    lib.covspec_reduce.restype = ctypes.c_int
+    lib.covspec_reduce.argtypes = [pp] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
+    lib.covspec_status_string.restype = ctypes.c_char_p
+    lib.covspec_status_string.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().covspec_status_string(int(status)).decode()
+
+
+@dataclass
+class Params:
+    batch: int
+    n_tokens: int
+    d_model: int
+    n_query: int
+    n_heads: int = 1
+    n_act_layers: int = 0
+    dtype: int = BF16
+    rel_mode: int = REL_COSINE_MAX
+    lr_mode: int = LR_ENERGY_TOPK
+    preselect_m: int = 0
+    rank_r: int = 0
+    keep_k: int = 0
+    keep_ratio: float = 0.25
+    lam: float = 0.5
+
+    def c_struct(self) -> CovspecParams:
+        return CovspecParams(self.batch, self.n_tokens, self.d_model, self.n_query, self.n_heads,
+                             self.n_act_layers, self.dtype, self.rel_mode, self.lr_mode, self.preselect_m,
+                             self.rank_r, self.keep_k, self.keep_ratio, self.lam)
+
+
+def workspace_size(p: Params) -> int:
+    cs = p.c_struct()
+    return int(load_library().covspec_workspace_size(ctypes.byref(cs)))
+
+
+def resolve(p: Params):
+    """(k, M, r) after the library's defaults; raises CovspecError on invalid params."""
+    cs = p.c_struct()
+    k, m, r = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    st = load_library().covspec_resolve(ctypes.byref(cs), ctypes.byref(k), ctypes.byref(m), ctypes.byref(r))
+    if st != OK:
+        raise CovspecError(st, "covspec_resolve")
+    return k.value, m.value, r.value
+
+
+# ---------------------------------------------------------------- torch-facing helpers
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _torch_dtype(dtype: int):
+    import torch
+    return torch.bfloat16 if dtype == BF16 else torch.float32
+
+
+def alloc_workspace(p: Params, device="cuda"):
+    import torch
+    n = workspace_size(p)
+    if n == 0:
+        cs = p.c_struct()
+        st = load_library().covspec_resolve(ctypes.byref(cs), None, None, None)
+        raise CovspecError(st if st != OK else INVALID_ARG, "covspec_workspace_size")
+    return torch.empty(n + 256, dtype=torch.uint8, device=device)
+
+
+def _ws_args(ws):
+    base = ws.data_ptr()
+    aligned = (base + 255) // 256 * 256
+    return aligned, ws.numel() - (aligned - base)
+
+
+def score(p: Params, X, hidden, Q, Wq, Wk, workspace=None):
+    """covspec_score: returns (s_query, s_act or None, s_fused), each [B, N] fp32."""
+    import torch
+    ws = workspace if workspace is not None else alloc_workspace(p, X.device)
+    B, N = p.batch, p.n_tokens
+    sq = torch.empty(B, N, dtype=torch.float32, device=X.device)
+    sf = torch.empty_like(sq)
+    has_act = hidden is not None and p.n_act_layers > 0
+    sa = torch.empty_like(sq) if has_act else None
+    wp, wb = _ws_args(ws)
+    cs = p.c_struct()
+    st = load_library().covspec_score(ctypes.byref(cs), _ptr(X), _ptr(hidden), _ptr(Q), _ptr(Wq), _ptr(Wk),
+                                      _ptr(sq), _ptr(sa), _ptr(sf), wp, wb, _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_score")
+    return sq, sa, sf
+
+
+def select(p: Params, X, s_fused, workspace=None):
+    """covspec_select: dict with idx [B,k], idx_m [B,M] and c [B,M] (energy) or pick_order/resid [B,k] (greedy)."""
+    import torch
+    ws = workspace if workspace is not None else alloc_workspace(p, X.device)
+    k, M, _ = resolve(p)
+    B = p.batch
+    dev = X.device
+    idx = torch.empty(B, k, dtype=torch.int32, device=dev)
+    idx_m = torch.empty(B, M, dtype=torch.int32, device=dev)
+    out = {"idx": idx, "idx_m": idx_m}
+    c = pick = resid = None
+    if p.lr_mode == LR_ENERGY_TOPK:
+        c = torch.empty(B, M, dtype=torch.float32, device=dev)
+        out["c"] = c
+    else:
+        pick = torch.empty(B, k, dtype=torch.int32, device=dev)
+        resid = torch.empty(B, k, dtype=torch.float32, device=dev)
+        out["pick_order"], out["resid"] = pick, resid
+    wp, wb = _ws_args(ws)
+    cs = p.c_struct()
+    st = load_library().covspec_select(ctypes.byref(cs), _ptr(X), _ptr(s_fused), _ptr(idx), _ptr(c), _ptr(idx_m),
+                                       _ptr(pick), _ptr(resid), wp, wb, _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_select")
+    return out
+
+
+def reduce(p: Params, X, hidden, Q, Wq, Wk, workspace=None, idx_out=None, tokens_out=None):
+    """covspec_reduce: returns (idx [B,k] int32, tokens [B,k,d] in X's dtype)."""
+    import torch
+    ws = workspace if workspace is not None else alloc_workspace(p, X.device)
+    k, _, _ = resolve(p)
+    idx = idx_out if idx_out is not None else torch.empty(p.batch, k, dtype=torch.int32, device=X.device)
+    tok = tokens_out if tokens_out is not None else torch.empty(p.batch, k, p.d_model, dtype=X.dtype, device=X.device)
+    wp, wb = _ws_args(ws)
+    cs = p.c_struct()
+    st = load_library().covspec_reduce(ctypes.byref(cs), _ptr(X), _ptr(hidden), _ptr(Q), _ptr(Wq), _ptr(Wk),
+                                       _ptr(idx), _ptr(tok), wp, wb, _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_reduce")
+    return idx, tok

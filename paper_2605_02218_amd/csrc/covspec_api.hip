@@ -1,0 +1,326 @@
+// C ABI of the visual-token-reduction library: argument validation, workspace
+// carving and the launch sequence of paper Sec. III-A (score, fuse, pre-select,
+// low-rank energy, keep, gather).  No allocation, no synchronisation, no global state.
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include "../../include/covspec.h"
+#include "kernels.h"
+
+using namespace covspec;
+
+namespace {
+
+constexpr int kMaxTokens = 16384;
+constexpr int kMaxPreselect = 4096;
+constexpr int kMaxActLayers = 8;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Plan {
+  int B, N, d, T, H, K, dtype, rel, lr, M, r, k;
+  float lambda;
+  int esz;        // bytes per stored element
+  int planes;     // bf16: 3 split planes of the folded query matrix, fp32: 1
+  int nparts;     // per-token partial sums of |e(v)|^2 written by the projection GEMM
+  int nP;         // Gram pitch, multiple of 16
+  // workspace offsets (bytes)
+  size_t wqT, wkT, Eq, qn2, Eq3, G3raw, G3, vn2p, logits, Ev, S, stats, sq, sa, sf;
+  size_t idxm, Awork, ctl, lam, c, Lt, order, resid;
+  size_t total;
+};
+
+int resolve(const covspec_params* p, int* k_, int* M_, int* r_) {
+  if (!p) return COVSPEC_INVALID_ARG;
+  if (p->n_tokens < 1 || p->keep_k < 0 || p->preselect_m < 0 || p->rank_r < 0) return COVSPEC_INVALID_ARG;
+  const long N = p->n_tokens;
+  long k = p->keep_k;
+  if (k == 0) {
+    if (!(p->keep_ratio > 0.f) || !(p->keep_ratio <= 1.f)) return COVSPEC_INVALID_ARG;
+    k = (long)floor((double)p->keep_ratio * (double)N + 0.5);
+    if (k < 1) k = 1;
+    if (k > N) k = N;
+  }
+  long M = p->preselect_m > 0 ? p->preselect_m : (2 * k < N ? 2 * k : N);
+  if (p->keep_k == 0 && k > M) k = M;
+  long r = p->rank_r > 0 ? p->rank_r : (k / 2 > 1 ? k / 2 : 1);
+  if (M > N || k > M || k < 1) return COVSPEC_INVALID_ARG;
+  *k_ = (int)k; *M_ = (int)M; *r_ = (int)r;
+  return COVSPEC_OK;
+}
+
+int make_plan(const covspec_params* p, Plan* pl) {
+  if (!p) return COVSPEC_INVALID_ARG;
+  if (p->batch < 1 || p->n_tokens < 1 || p->d_model < 1 || p->n_query < 1 || p->n_heads < 1) return COVSPEC_INVALID_ARG;
+  if (p->d_model % p->n_heads != 0) return COVSPEC_INVALID_ARG;
+  if (p->n_act_layers < 0) return COVSPEC_INVALID_ARG;
+  if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16) return COVSPEC_INVALID_ARG;
+  if (p->rel_mode != COVSPEC_REL_COSINE_MAX && p->rel_mode != COVSPEC_REL_ATTN_SOFTMAX) return COVSPEC_INVALID_ARG;
+  if (p->lr_mode != COVSPEC_LR_ENERGY_TOPK && p->lr_mode != COVSPEC_LR_GREEDY_RESIDUAL) return COVSPEC_INVALID_ARG;
+  if (!(p->lambda >= 0.f) || !(p->lambda <= 1.f)) return COVSPEC_INVALID_ARG;
+  int k, M, r;
+  int st = resolve(p, &k, &M, &r);
+  if (st != COVSPEC_OK) return st;
+  const int mind = M < p->d_model ? M : p->d_model;
+  if (p->lr_mode == COVSPEC_LR_ENERGY_TOPK && (r < 1 || r >= mind)) return COVSPEC_INVALID_ARG;
+  // limits of the kernels
+  if (p->n_tokens > kMaxTokens || M > kMaxPreselect || p->n_act_layers > kMaxActLayers) return COVSPEC_UNSUPPORTED;
+  if (p->d_model % (p->dtype == COVSPEC_BF16 ? 8 : 4) != 0) return COVSPEC_UNSUPPORTED;
+  if (p->rel_mode == COVSPEC_REL_ATTN_SOFTMAX && (p->d_model / p->n_heads) % 4 != 0) return COVSPEC_UNSUPPORTED;
+  if ((long)p->batch * p->n_tokens > 0x3fffffffL || (long)p->batch * p->n_query > 0x3fffffffL) return COVSPEC_UNSUPPORTED;
+
+  Plan& q = *pl;
+  q.B = p->batch; q.N = p->n_tokens; q.d = p->d_model; q.T = p->n_query; q.H = p->n_heads; q.K = p->n_act_layers;
+  q.dtype = p->dtype; q.rel = p->rel_mode; q.lr = p->lr_mode; q.M = M; q.r = r; q.k = k; q.lambda = p->lambda;
+  q.esz = p->dtype == COVSPEC_BF16 ? 2 : 4;
+  q.planes = p->dtype == COVSPEC_BF16 ? 3 : 1;
+  q.nparts = gemm_tiles_n(q.d);
+  q.nP = (M + 15) / 16 * 16;
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  const size_t B = q.B, N = q.N, d = q.d, T = q.T, BT = B * T, BN = B * N;
+  q.wqT = take(d * d * q.esz);
+  q.wkT = take(d * d * q.esz);
+  q.Eq = take(BT * d * 4);
+  q.qn2 = take(BT * 4);
+  q.Eq3 = q.G3raw = q.G3 = q.vn2p = q.logits = q.Ev = q.S = q.stats = 0;
+  if (q.rel == COVSPEC_REL_COSINE_MAX) {
+    if (q.dtype == COVSPEC_BF16) q.Eq3 = take(3 * BT * d * 2);
+    q.G3raw = take((size_t)q.planes * BT * d * 4);
+    if (q.dtype == COVSPEC_BF16) q.G3 = take(3 * BT * d * 2);
+    q.vn2p = take(BN * q.nparts * 4);
+    q.logits = take(BN * q.planes * T * 4);
+  } else {
+    q.Ev = take(BN * d * 4);
+    q.S = take(B * q.H * T * N * 4);
+    q.stats = take(B * q.H * T * 8);
+  }
+  q.sq = take(BN * 4);
+  q.sa = take(BN * 4);
+  q.sf = take(BN * 4);
+  q.idxm = take(B * M * 4);
+  q.Awork = take(B * (size_t)q.nP * q.nP * 8);
+  q.ctl = take(jacobi_ctl_bytes(q.B));
+  q.lam = take(B * q.nP * 8);
+  q.c = take(B * M * 4);
+  q.Lt = q.order = q.resid = 0;
+  if (q.lr == COVSPEC_LR_GREEDY_RESIDUAL) {
+    q.Lt = take(B * (size_t)k * q.nP * 8);
+    q.order = take(B * k * 4);
+    q.resid = take(B * k * 4);
+  }
+  q.total = off;
+  return COVSPEC_OK;
+}
+
+#define HIPCHK(expr)                                \
+  do {                                              \
+    hipError_t e__ = (expr);                        \
+    if (e__ != hipSuccess) return COVSPEC_HIP_ERROR; \
+  } while (0)
+
+template <typename T>
+inline T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
+
+int check_ws(const Plan& pl, void* ws, size_t bytes) {
+  if (!ws || ((uintptr_t)ws & 255u)) return COVSPEC_INVALID_ARG;
+  if (bytes < pl.total) return COVSPEC_WORKSPACE_TOO_SMALL;
+  return COVSPEC_OK;
+}
+
+// ---- scores: paper Sec. III-A.1 (query-aware), III-A.2 (activity), fusion equation
+int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, const void* Wq, const void* Wk,
+              float* s_query, float* s_act, float* s_fused, void* ws, hipStream_t st) {
+  const long B = q.B, N = q.N, d = q.d, T = q.T, BT = B * T, BN = B * N;
+  float* Eq = at<float>(ws, q.Eq);
+  float* qn2 = at<float>(ws, q.qn2);
+  float* sq = s_query ? s_query : at<float>(ws, q.sq);
+  float* sf = s_fused ? s_fused : at<float>(ws, q.sf);
+  const bool has_act = hidden != nullptr && q.K > 0;
+  float* sa = has_act ? (s_act ? s_act : at<float>(ws, q.sa)) : nullptr;
+
+  // e(q) = q Wq, kept in fp32
+  if (Wq) {
+    HIPCHK(launch_transpose(Wq, at<void>(ws, q.wqT), q.d, q.d, q.dtype, st));
+    GemmArgs g;
+    g.A = Q; g.B = at<void>(ws, q.wqT); g.C = Eq; g.M = (int)BT; g.N = q.d; g.K = q.d; g.lda = d; g.ldb = d; g.ldc = d;
+    HIPCHK(launch_gemm_nt(g, q.dtype, st));
+  } else {
+    HIPCHK(launch_to_f32(Q, Eq, BT * d, q.dtype, st));
+  }
+  if (Wk) HIPCHK(launch_transpose(Wk, at<void>(ws, q.wkT), q.d, q.d, q.dtype, st));
+
+  if (q.rel == COVSPEC_REL_COSINE_MAX) {
+    HIPCHK(launch_row_norm2(Eq, qn2, BT, q.d, DT_F32, st));
+    // fold Wk into the query side: <x Wk, e(q)> = <x, Wk e(q)^T>; the token side then only needs |x Wk|^2
+    const void* Gq;  // per image [planes*T, d] in the storage dtype of X
+    float* vn2 = at<float>(ws, q.vn2p);
+    int nparts;
+    if (Wk) {
+      float* Graw = at<float>(ws, q.G3raw);
+      GemmArgs g;
+      g.B = Wk; g.C = Graw; g.N = q.d; g.K = q.d; g.lda = d; g.ldb = d; g.ldc = d;
+      if (q.dtype == COVSPEC_BF16) {
+        HIPCHK(launch_sum_split3(Eq, 1, 0, BT, q.d, BT, at<unsigned short>(ws, q.Eq3), st));
+        g.A = at<void>(ws, q.Eq3); g.M = (int)(3 * BT);
+        HIPCHK(launch_gemm_nt(g, DT_BF16, st));
+        HIPCHK(launch_sum_split3(Graw, 3, BT * d, BT, q.d, T, at<unsigned short>(ws, q.G3), st));
+        Gq = at<void>(ws, q.G3);
+      } else {
+        g.A = Eq; g.M = (int)BT;
+        HIPCHK(launch_gemm_nt(g, DT_F32, st));
+        Gq = Graw;
+      }
+      GemmArgs n;
+      n.A = X; n.B = at<void>(ws, q.wkT); n.C = vn2; n.M = (int)BN; n.N = q.d; n.K = q.d; n.lda = d; n.ldb = d;
+      n.ldc = q.nparts; n.epilogue = EPI_ROWNORM2;
+      HIPCHK(launch_gemm_nt(n, q.dtype, st));
+      nparts = q.nparts;
+    } else {
+      if (q.dtype == COVSPEC_BF16) {
+        HIPCHK(launch_sum_split3(Eq, 1, 0, BT, q.d, T, at<unsigned short>(ws, q.G3), st));
+        Gq = at<void>(ws, q.G3);
+      } else {
+        Gq = Eq;
+      }
+      HIPCHK(launch_row_norm2(X, vn2, BN, q.d, q.dtype, st));
+      nparts = 1;
+    }
+    float* logits = at<float>(ws, q.logits);
+    GemmArgs l;
+    l.A = X; l.B = Gq; l.C = logits; l.M = q.N; l.N = q.planes * q.T; l.K = q.d; l.lda = d; l.ldb = d; l.ldc = q.planes * T;
+    l.batch = q.B; l.strideA = N * d; l.strideB = (long)q.planes * T * d; l.strideC = N * q.planes * T;
+    HIPCHK(launch_gemm_nt(l, q.dtype, st));
+    HIPCHK(launch_cosine_max(logits, q.planes, vn2, nparts, qn2, sq, q.B, q.N, q.T, st));
+  } else {
+    // variant: e(v) materialised in fp32, per-head logits with the fp32 MFMA, softmax over the visual tokens
+    float* Ev = at<float>(ws, q.Ev);
+    if (Wk) {
+      GemmArgs g;
+      g.A = X; g.B = at<void>(ws, q.wkT); g.C = Ev; g.M = (int)BN; g.N = q.d; g.K = q.d; g.lda = d; g.ldb = d; g.ldc = d;
+      HIPCHK(launch_gemm_nt(g, q.dtype, st));
+    } else {
+      HIPCHK(launch_to_f32(X, Ev, BN * d, q.dtype, st));
+    }
+    const int dh = q.d / q.H;
+    float* S = at<float>(ws, q.S);
+    GemmArgs g;
+    g.A = Eq; g.B = Ev; g.C = S; g.M = q.T; g.N = q.N; g.K = dh; g.lda = d; g.ldb = d; g.ldc = N;
+    g.batch = q.B * q.H; g.batch_inner = q.H;
+    g.strideA = T * d; g.strideA2 = dh; g.strideB = N * d; g.strideB2 = dh; g.strideC = (long)q.H * T * N; g.strideC2 = T * N;
+    HIPCHK(launch_gemm_nt(g, DT_F32, st));
+    const float scale = (float)(1.0 / sqrt((double)dh));
+    float2* stats = at<float2>(ws, q.stats);
+    HIPCHK(launch_softmax_stats(S, stats, B * q.H * T, q.N, scale, st));
+    HIPCHK(launch_softmax_mean(S, stats, sq, q.B, q.H * q.T, q.N, scale, st));
+  }
+
+  if (has_act) HIPCHK(launch_activity(hidden, sa, q.B, q.N, q.d, q.K, q.dtype, st));
+  HIPCHK(launch_fuse(sq, sa, sf, q.B, q.N, q.lambda, st));
+  return COVSPEC_OK;
+}
+
+// ---- selection: paper Sec. III-A.3
+int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_out, float* c_out, int32_t* idx_m_out,
+               int32_t* pick_order_out, float* resid_out, void* ws, hipStream_t st) {
+  const long N = q.N, d = q.d;
+  int32_t* idxm = idx_m_out ? idx_m_out : at<int32_t>(ws, q.idxm);
+  HIPCHK(launch_select_top(s_fused, q.B, q.N, q.M, nullptr, idxm, st));
+
+  // token Gram matrix of the pre-selected rows, fp64, zero-padded to the pitch
+  double* A = at<double>(ws, q.Awork);
+  HIPCHK(launch_fill_zero(A, (size_t)q.B * q.nP * q.nP * 8, st));
+  GemmArgs g;
+  g.A = X; g.B = X; g.C = A; g.M = q.M; g.N = q.M; g.K = q.d; g.lda = d; g.ldb = d; g.ldc = q.nP;
+  g.batch = q.B; g.strideA = N * d; g.strideB = N * d; g.strideC = (long)q.nP * q.nP;
+  g.gatherA = idxm; g.gatherB = idxm; g.gstrideA = q.M; g.gstrideB = q.M;
+  g.epilogue = EPI_STORE_F64;
+  HIPCHK(launch_gemm_nt(g, q.dtype, st));
+
+  if (q.lr == COVSPEC_LR_ENERGY_TOPK) {
+    float* c = c_out ? c_out : at<float>(ws, q.c);
+    HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, at<void>(ws, q.ctl), st));
+    HIPCHK(launch_subspace_energy(A, q.B, q.M, q.nP, q.r, at<double>(ws, q.lam), c, st));
+    HIPCHK(launch_select_top(c, q.B, q.M, q.k, idxm, idx_out, st));
+  } else {
+    int32_t* order = at<int32_t>(ws, q.order);
+    float* resid = resid_out ? resid_out : at<float>(ws, q.resid);
+    HIPCHK(launch_greedy(A, q.B, q.M, q.nP, q.k, at<double>(ws, q.Lt), order, resid, st));
+    HIPCHK(launch_greedy_finish(order, idxm, q.B, q.M, q.k, idx_out, pick_order_out, st));
+  }
+  return COVSPEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t covspec_workspace_size(const covspec_params* p) {
+  Plan pl;
+  if (make_plan(p, &pl) != COVSPEC_OK) return 0;
+  return pl.total;
+}
+
+int covspec_resolve(const covspec_params* p, int32_t* keep_k, int32_t* preselect_m, int32_t* rank_r) {
+  Plan pl;
+  int st = make_plan(p, &pl);
+  if (st != COVSPEC_OK) return st;
+  if (keep_k) *keep_k = pl.k;
+  if (preselect_m) *preselect_m = pl.M;
+  if (rank_r) *rank_r = pl.r;
+  return COVSPEC_OK;
+}
+
+int covspec_score(const covspec_params* p, const void* X, const void* hidden, const void* Q, const void* Wq,
+                  const void* Wk, float* s_query, float* s_act, float* s_fused, void* workspace, size_t workspace_bytes,
+                  covspec_stream_t stream) {
+  Plan pl;
+  int st = make_plan(p, &pl);
+  if (st != COVSPEC_OK) return st;
+  if (!X || !Q) return COVSPEC_INVALID_ARG;
+  if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
+  return run_score(pl, X, hidden, Q, Wq, Wk, s_query, s_act, s_fused, workspace, (hipStream_t)stream);
+}
+
+int covspec_select(const covspec_params* p, const void* X, const float* s_fused, int32_t* idx_out, float* c_out,
+                   int32_t* idx_m_out, int32_t* pick_order_out, float* resid_out, void* workspace,
+                   size_t workspace_bytes, covspec_stream_t stream) {
+  Plan pl;
+  int st = make_plan(p, &pl);
+  if (st != COVSPEC_OK) return st;
+  if (!X || !s_fused || !idx_out) return COVSPEC_INVALID_ARG;
+  if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
+  return run_select(pl, X, s_fused, idx_out, c_out, idx_m_out, pick_order_out, resid_out, workspace, (hipStream_t)stream);
+}
+
+int covspec_reduce(const covspec_params* p, const void* X, const void* hidden, const void* Q, const void* Wq,
+                   const void* Wk, int32_t* idx_out, void* tokens_out, void* workspace, size_t workspace_bytes,
+                   covspec_stream_t stream) {
+  Plan pl;
+  int st = make_plan(p, &pl);
+  if (st != COVSPEC_OK) return st;
+  if (!X || !Q || !idx_out || !tokens_out) return COVSPEC_INVALID_ARG;
+  if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  float* sf = at<float>(workspace, pl.sf);
+  st = run_score(pl, X, hidden, Q, Wq, Wk, nullptr, nullptr, sf, workspace, s);
+  if (st != COVSPEC_OK) return st;
+  st = run_select(pl, X, sf, idx_out, nullptr, nullptr, nullptr, nullptr, workspace, s);
+  if (st != COVSPEC_OK) return st;
+  HIPCHK(launch_gather_rows(X, idx_out, tokens_out, pl.B, pl.N, pl.k, (long)pl.d * pl.esz, s));
+  return COVSPEC_OK;
+}
+
+const char* covspec_status_string(int status) {
+  switch (status) {
+    case COVSPEC_OK: return "ok";
+    case COVSPEC_INVALID_ARG: return "invalid argument";
+    case COVSPEC_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case COVSPEC_UNSUPPORTED: return "shape or mode outside the kernels' limits";
+    case COVSPEC_HIP_ERROR: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,349 @@
+// HBM-bound and small per-token kernels of the token-selection path:
+// activity score, row norms, format conversion and splitting, the cosine-max
+// and softmax epilogues, min-max fusion, gather.
+#include "common.h"
+#include "kernels.h"
+
+namespace covspec {
+
+namespace {
+
+// ---------------------------------------------------------------- 16-byte element loads
+template <int DT> struct Vec;
+template <> struct Vec<DT_BF16> {
+  static constexpr int N = 8;
+  __device__ static __forceinline__ void load(const void* base, long elem, float (&v)[8]) {
+    u32x4_t r = *(const u32x4_t*)((const bf16_t*)base + elem);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo_to_f32(r[i]); v[2 * i + 1] = bf16hi_to_f32(r[i]); }
+  }
+  __device__ static __forceinline__ float load1(const void* base, long elem) { return bf16_to_f32(((const bf16_t*)base)[elem]); }
+};
+template <> struct Vec<DT_F32> {
+  static constexpr int N = 4;
+  __device__ static __forceinline__ void load(const void* base, long elem, float (&v)[4]) {
+    f32x4_t r = *(const f32x4_t*)((const float*)base + elem);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = r[i];
+  }
+  __device__ static __forceinline__ float load1(const void* base, long elem) { return ((const float*)base)[elem]; }
+};
+
+// ---------------------------------------------------------------- activity (paper Sec. III-A.2)
+// One wave per token.  The wave walks the row in 16-byte-per-lane chunks and reads the K+1 slices of a
+// chunk back to back, keeping the previous slice in registers, so every hidden element is read from
+// HBM exactly once.  Squared differences accumulate in fp32 per (layer, lane) and are wave-reduced in a
+// fixed order, so equal rows give bit-equal scores.
+template <int DT, int K>
+__global__ __launch_bounds__(256) void activity_kernel(const void* __restrict__ hidden, float* __restrict__ s_act,
+                                                        long tokens, int N, int d) {
+  constexpr int V = Vec<DT>::N;
+  const int lane = threadIdx.x & 63;
+  const long token = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (token >= tokens) return;
+  const long b = token / N, i = token - b * N;
+  const long slice = (long)N * d;
+  const long base = (b * (K + 1) * N + i) * (long)d;
+  float acc[K];
+#pragma unroll
+  for (int l = 0; l < K; ++l) acc[l] = 0.f;
+  for (int c = lane * V; c < d; c += 64 * V) {
+    float prev[V], cur[V];
+    Vec<DT>::load(hidden, base + c, prev);
+#pragma unroll
+    for (int l = 1; l <= K; ++l) {
+      Vec<DT>::load(hidden, base + l * slice + c, cur);
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        float df = cur[e] - prev[e];
+        acc[l - 1] = fmaf(df, df, acc[l - 1]);
+        prev[e] = cur[e];
+      }
+    }
+  }
+  double total = 0.0;
+#pragma unroll
+  for (int l = 0; l < K; ++l) total += sqrt((double)wave_sum(acc[l]));
+  if (lane == 0) s_act[token] = (float)(total / K);
+}
+
+template <int DT>
+hipError_t activity_dispatch(const void* hidden, float* s_act, long tokens, int N, int d, int K, hipStream_t st) {
+  dim3 grid((unsigned)((tokens + 3) / 4)), block(256);
+#define COVSPEC_ACT_CASE(KK) \
+  case KK: hipLaunchKernelGGL((activity_kernel<DT, KK>), grid, block, 0, st, hidden, s_act, tokens, N, d); break;
+  switch (K) {
+    COVSPEC_ACT_CASE(1) COVSPEC_ACT_CASE(2) COVSPEC_ACT_CASE(3) COVSPEC_ACT_CASE(4)
+    COVSPEC_ACT_CASE(5) COVSPEC_ACT_CASE(6) COVSPEC_ACT_CASE(7) COVSPEC_ACT_CASE(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef COVSPEC_ACT_CASE
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- row norms
+template <int DT>
+__global__ __launch_bounds__(256) void row_norm2_kernel(const void* __restrict__ x, float* __restrict__ out, long rows, int d) {
+  constexpr int V = Vec<DT>::N;
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  float acc = 0.f;
+  for (int c = lane * V; c < d; c += 64 * V) {
+    float v[V];
+    Vec<DT>::load(x, row * d + c, v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc = fmaf(v[e], v[e], acc);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) out[row] = acc;
+}
+
+// ---------------------------------------------------------------- transpose
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in, T* __restrict__ out, int rows, int cols) {
+  __shared__ T tile[64][65];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int r = ty; r < 64; r += 4)
+    if (r0 + r < rows && c0 + tx < cols) tile[r][tx] = in[(long)(r0 + r) * cols + c0 + tx];
+  __syncthreads();
+  for (int c = ty; c < 64; c += 4)
+    if (c0 + c < cols && r0 + tx < rows) out[(long)(c0 + c) * rows + r0 + tx] = tile[tx][c];
+}
+
+// ---------------------------------------------------------------- conversion / splitting
+template <int DT>
+__global__ void to_f32_kernel(const void* __restrict__ src, float* __restrict__ dst, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = Vec<DT>::load1(src, i);
+}
+
+__device__ __forceinline__ float sum_planes(const float* src, int planes, long plane_stride, long i) {
+  float v = src[i];
+  for (int p = 1; p < planes; ++p) v += src[p * plane_stride + i];
+  return v;
+}
+
+__global__ void sum_split3_kernel(const float* __restrict__ src, int planes, long plane_stride, long rows, int d,
+                                  long rpg, bf16_t* __restrict__ out) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * d) return;
+  long r = i / d;
+  int c = (int)(i - r * d);
+  float v = sum_planes(src, planes, plane_stride, i);
+  bf16_t hi = f32_to_bf16_rne(v);
+  float r1 = v - bf16_to_f32(hi);  // exact
+  bf16_t mid = f32_to_bf16_rne(r1);
+  float r2 = r1 - bf16_to_f32(mid);  // exact
+  bf16_t lo = f32_to_bf16_rne(r2);
+  long g = r / rpg, j = r - g * rpg;
+  out[((g * 3 + 0) * rpg + j) * d + c] = hi;
+  out[((g * 3 + 1) * rpg + j) * d + c] = mid;
+  out[((g * 3 + 2) * rpg + j) * d + c] = lo;
+}
+
+__global__ void sum_planes_kernel(const float* __restrict__ src, int planes, long plane_stride, long n, float* __restrict__ out) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = sum_planes(src, planes, plane_stride, i);
+}
+
+// ---------------------------------------------------------------- cosine-max epilogue (paper Sec. III-A.1)
+// One wave per token; lanes stride over the query keywords.  The scalar arithmetic is fp64 so that the only
+// error left in the score is that of the fp32-accumulated contractions feeding it.
+__global__ __launch_bounds__(256) void cosine_max_kernel(const float* __restrict__ logits, int planes,
+                                                          const float* __restrict__ vnorm2, int nparts,
+                                                          const float* __restrict__ qnorm2, float* __restrict__ s_query,
+                                                          long tokens, int N, int T) {
+  const int lane = threadIdx.x & 63;
+  const long token = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (token >= tokens) return;
+  const long b = token / N;
+  double n2 = 0.0;
+  for (int t = 0; t < nparts; ++t) n2 += (double)vnorm2[token * nparts + t];
+  const double nv = sqrt(n2);
+  const float* L = logits + token * (long)planes * T;
+  double best = -INFINITY;
+  for (int j = lane; j < T; j += 64) {
+    double dot = (double)L[j];
+    for (int s = 1; s < planes; ++s) dot += (double)L[s * T + j];
+    double den = nv * sqrt((double)qnorm2[b * T + j]);
+    double c = dot / fmax(den, 1e-30);
+    best = fmax(best, c);
+  }
+  best = wave_max(best);
+  if (lane == 0) s_query[token] = (float)best;
+}
+
+// ---------------------------------------------------------------- softmax relevance (variant)
+// stats[row] = (max_i scale*S[row,i], sum_i exp(scale*S[row,i] - max)); one wave per row.
+__global__ __launch_bounds__(256) void softmax_stats_kernel(const float* __restrict__ S, float2* __restrict__ stats,
+                                                             long rows, int N, float scale) {
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float* p = S + row * (long)N;
+  float m = -INFINITY;
+  for (int i = lane; i < N; i += 64) m = fmaxf(m, p[i] * scale);
+  m = wave_max(m);
+  double z = 0.0;
+  for (int i = lane; i < N; i += 64) z += (double)expf(p[i] * scale - m);
+  z = wave_sum(z);
+  if (lane == 0) stats[row] = make_float2(m, (float)z);
+}
+
+// s_query[b,i] = (1/HT) sum_{row < HT} exp(scale*S[b,row,i] - max_row) / Z_row, rows added in order.
+__global__ __launch_bounds__(256) void softmax_mean_kernel(const float* __restrict__ S, const float2* __restrict__ stats,
+                                                            float* __restrict__ s_query, int HT, int N, float scale) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int b = blockIdx.y;
+  if (i >= N) return;
+  const float* p = S + (long)b * HT * N + i;
+  const float2* st = stats + (long)b * HT;
+  double acc = 0.0;
+  for (int r = 0; r < HT; ++r) {
+    float2 mz = st[r];
+    acc += (double)expf(p[(long)r * N] * scale - mz.x) / (double)mz.y;
+  }
+  s_query[(long)b * N + i] = (float)(acc / HT);
+}
+
+// ---------------------------------------------------------------- min-max + fuse (paper fusion equation)
+__device__ __forceinline__ void block_minmax(float& lo, float& hi, float* red) {
+  lo = wave_min(lo);
+  hi = wave_max(hi);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { red[w] = lo; red[32 + w] = hi; }
+  __syncthreads();
+  lo = red[0]; hi = red[32];
+  for (int k = 1; k < nw; ++k) { lo = fminf(lo, red[k]); hi = fmaxf(hi, red[32 + k]); }
+}
+
+__global__ __launch_bounds__(1024) void fuse_kernel(const float* __restrict__ s_query, const float* __restrict__ s_act,
+                                                     float* __restrict__ s_fused, int N, float lambda) {
+  __shared__ float red[64];
+  const long off = (long)blockIdx.x * N;
+  float qlo = INFINITY, qhi = -INFINITY, alo = INFINITY, ahi = -INFINITY;
+  for (int i = threadIdx.x; i < N; i += blockDim.x) {
+    float q = s_query[off + i];
+    qlo = fminf(qlo, q); qhi = fmaxf(qhi, q);
+    if (s_act) { float a = s_act[off + i]; alo = fminf(alo, a); ahi = fmaxf(ahi, a); }
+  }
+  block_minmax(qlo, qhi, red);
+  if (s_act) block_minmax(alo, ahi, red);
+  const double lam = (double)lambda;
+  for (int i = threadIdx.x; i < N; i += blockDim.x) {
+    double q = (qhi == qlo) ? 0.0 : ((double)s_query[off + i] - (double)qlo) / ((double)qhi - (double)qlo);
+    double f = q;
+    if (s_act) {
+      double a = (ahi == alo) ? 0.0 : ((double)s_act[off + i] - (double)alo) / ((double)ahi - (double)alo);
+      f = lam * q + (1.0 - lam) * a;
+    }
+    s_fused[off + i] = (float)f;
+  }
+}
+
+// ---------------------------------------------------------------- gather
+__global__ __launch_bounds__(256) void gather_rows_kernel(const unsigned char* __restrict__ X, const int32_t* __restrict__ idx,
+                                                           unsigned char* __restrict__ out, int N, int k, long row_bytes) {
+  const long row = blockIdx.x;  // b*k + j
+  const long b = row / k;
+  const long src = (b * N + idx[row]) * row_bytes;
+  const long dst = row * row_bytes;
+  for (long o = (long)threadIdx.x * 16; o < row_bytes; o += 256 * 16)
+    *(u32x4_t*)(out + dst + o) = *(const u32x4_t*)(X + src + o);
+}
+
+__global__ void fill_zero_kernel(u32x4_t* p, long n16) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const u32x4_t z = {0u, 0u, 0u, 0u};
+  for (; i < n16; i += (long)gridDim.x * blockDim.x) p[i] = z;
+}
+
+inline unsigned blocks_for(long n, int per) { return (unsigned)((n + per - 1) / per); }
+
+}  // namespace
+
+hipError_t launch_transpose(const void* in, void* out, int rows, int cols, int dtype, hipStream_t st) {
+  dim3 grid((cols + 63) / 64, (rows + 63) / 64), block(256);
+  if (dtype == DT_BF16) hipLaunchKernelGGL((transpose_kernel<bf16_t>), grid, block, 0, st, (const bf16_t*)in, (bf16_t*)out, rows, cols);
+  else hipLaunchKernelGGL((transpose_kernel<float>), grid, block, 0, st, (const float*)in, (float*)out, rows, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_activity(const void* hidden, float* s_act, int B, int N, int d, int K, int dtype, hipStream_t st) {
+  long tokens = (long)B * N;
+  return dtype == DT_BF16 ? activity_dispatch<DT_BF16>(hidden, s_act, tokens, N, d, K, st)
+                          : activity_dispatch<DT_F32>(hidden, s_act, tokens, N, d, K, st);
+}
+
+hipError_t launch_row_norm2(const void* x, float* out, long rows, int d, int dtype, hipStream_t st) {
+  dim3 grid(blocks_for(rows, 4)), block(256);
+  if (dtype == DT_BF16) hipLaunchKernelGGL((row_norm2_kernel<DT_BF16>), grid, block, 0, st, x, out, rows, d);
+  else hipLaunchKernelGGL((row_norm2_kernel<DT_F32>), grid, block, 0, st, x, out, rows, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_to_f32(const void* src, float* dst, long n, int dtype, hipStream_t st) {
+  dim3 grid(blocks_for(n, 256)), block(256);
+  if (dtype == DT_BF16) hipLaunchKernelGGL((to_f32_kernel<DT_BF16>), grid, block, 0, st, src, dst, n);
+  else hipLaunchKernelGGL((to_f32_kernel<DT_F32>), grid, block, 0, st, src, dst, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_sum_split3(const float* src, int planes, long plane_stride, long rows, int d, long rows_per_group,
+                             unsigned short* out, hipStream_t st) {
+  dim3 grid(blocks_for(rows * d, 256)), block(256);
+  hipLaunchKernelGGL(sum_split3_kernel, grid, block, 0, st, src, planes, plane_stride, rows, d, rows_per_group, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_sum_planes(const float* src, int planes, long plane_stride, long n, float* out, hipStream_t st) {
+  dim3 grid(blocks_for(n, 256)), block(256);
+  hipLaunchKernelGGL(sum_planes_kernel, grid, block, 0, st, src, planes, plane_stride, n, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_cosine_max(const float* logits, int planes, const float* vnorm2, int nparts, const float* qnorm2,
+                             float* s_query, int B, int N, int T, hipStream_t st) {
+  long tokens = (long)B * N;
+  dim3 grid(blocks_for(tokens, 4)), block(256);
+  hipLaunchKernelGGL(cosine_max_kernel, grid, block, 0, st, logits, planes, vnorm2, nparts, qnorm2, s_query, tokens, N, T);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_stats(const float* S, float2* stats, long rows, int N, float scale, hipStream_t st) {
+  dim3 grid(blocks_for(rows, 4)), block(256);
+  hipLaunchKernelGGL(softmax_stats_kernel, grid, block, 0, st, S, stats, rows, N, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_mean(const float* S, const float2* stats, float* s_query, int B, int HT, int N, float scale,
+                               hipStream_t st) {
+  dim3 grid((N + 255) / 256, B), block(256);
+  hipLaunchKernelGGL(softmax_mean_kernel, grid, block, 0, st, S, stats, s_query, HT, N, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_fuse(const float* s_query, const float* s_act, float* s_fused, int B, int N, float lambda, hipStream_t st) {
+  hipLaunchKernelGGL(fuse_kernel, dim3(B), dim3(1024), 0, st, s_query, s_act, s_fused, N, lambda);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const void* X, const int32_t* idx, void* out, int B, int N, int k, long row_bytes, hipStream_t st) {
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((long)B * k)), dim3(256), 0, st, (const unsigned char*)X, idx,
+                     (unsigned char*)out, N, k, row_bytes);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+  long n16 = (long)(bytes / 16);
+  if (n16 == 0) return hipSuccess;
+  unsigned blocks = (unsigned)((n16 + 255) / 256);
+  if (blocks > 65536u) blocks = 65536u;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, (u32x4_t*)p, n16);
+  return hipGetLastError();
+}
+
+}  // namespace covspec

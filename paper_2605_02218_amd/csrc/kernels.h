@@ -1,0 +1,107 @@
+// Host-side launch interface of the gfx950 kernels.  Every launcher enqueues on
+// `stream` and returns the launch status; none allocates or synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace covspec {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+// ---------------------------------------------------------------- gemm.hip
+// C[M,N] = A[M,K] * B[N,K]^T  (both operands K-contiguous), fp32 accumulation on MFMA.
+enum GemmEpilogue {
+  EPI_STORE_F32 = 0,  // C fp32 [M,N]
+  EPI_ROWNORM2 = 1,   // C fp32 [M, tiles_n]: per-tile sums over columns of C^2 (C itself is not stored)
+  EPI_STORE_F64 = 2,  // C fp64 [M,N]; the fp32 accumulators are flushed into fp64 every 256 k
+};
+
+struct GemmArgs {
+  const void* A = nullptr;
+  const void* B = nullptr;
+  void* C = nullptr;
+  int M = 0, N = 0, K = 0;
+  long lda = 0, ldb = 0, ldc = 0;              // row pitches, in elements
+  int batch = 1;                               // total batch count = outer * batch_inner
+  int batch_inner = 1;                         // batch id -> (outer = id / inner, in = id % inner)
+  long strideA = 0, strideB = 0, strideC = 0;  // outer batch strides, in elements
+  long strideA2 = 0, strideB2 = 0, strideC2 = 0;  // inner batch strides, in elements
+  const int32_t* gatherA = nullptr;            // optional [outer batch, M] / [outer batch, N] row lists
+  const int32_t* gatherB = nullptr;
+  long gstrideA = 0, gstrideB = 0;
+  int epilogue = EPI_STORE_F32;
+};
+int gemm_tiles_n(int N);
+hipError_t launch_gemm_nt(const GemmArgs& g, int dtype, hipStream_t stream);
+
+// ---------------------------------------------------------------- elementwise.hip
+// out[c][r] = in[r][c] for a rows x cols matrix of bf16 or fp32 elements.
+hipError_t launch_transpose(const void* in, void* out, int rows, int cols, int dtype, hipStream_t stream);
+
+// Token activity (paper Sec. III-A.2): s_act[b,i] = (1/K) sum_l ||hidden[b,l,i,:] - hidden[b,l-1,i,:]||_2.
+hipError_t launch_activity(const void* hidden, float* s_act, int B, int N, int d, int K, int dtype, hipStream_t stream);
+
+// out[row] = sum_c x[row,c]^2 (fp32 result, fp64 when out64 != nullptr) for rows x d.
+hipError_t launch_row_norm2(const void* x, float* out, long rows, int d, int dtype, hipStream_t stream);
+
+// dst fp32 = convert(src), n elements.
+hipError_t launch_to_f32(const void* src, float* dst, long n, int dtype, hipStream_t stream);
+
+// v[r,c] = sum_{p < planes} src[p*plane_stride + r*d + c] (added in plane order), then split into three
+// bf16 planes hi/mid/lo with hi+mid+lo == v to ~2^-25 relative.  Output row of (r, s):
+// ((r / rows_per_group) * 3 + s) * rows_per_group + r % rows_per_group.
+hipError_t launch_sum_split3(const float* src, int planes, long plane_stride, long rows, int d, long rows_per_group,
+                             unsigned short* out, hipStream_t stream);
+// v as above, stored as fp32 (the fp32 path needs no split).
+hipError_t launch_sum_planes(const float* src, int planes, long plane_stride, long n, float* out, hipStream_t stream);
+
+// Query-aware score (paper Sec. III-A.1): s_query[b,i] = max_j L[b,i,j] / max(|e(v_i)| |e(q_j)|, 1e-30) with
+// L[b,i,j] = sum_{s<planes} logits[b,i,s*T+j], |e(v_i)|^2 = sum_{t<nparts} vnorm2[(b*N+i)*nparts + t],
+// |e(q_j)|^2 = qnorm2[b*T+j].
+hipError_t launch_cosine_max(const float* logits, int planes, const float* vnorm2, int nparts, const float* qnorm2,
+                             float* s_query, int B, int N, int T, hipStream_t stream);
+
+// Attention-softmax relevance (variant): S is [B,H,T,N] fp32 logits (unscaled).  Pass 1 writes per (b,h,j)
+// the row maximum and the sum of exponentials of scale*S; pass 2 averages the probabilities over (h,j).
+hipError_t launch_softmax_stats(const float* S, float2* stats, long rows, int N, float scale, hipStream_t stream);
+hipError_t launch_softmax_mean(const float* S, const float2* stats, float* s_query, int B, int HT, int N, float scale,
+                               hipStream_t stream);
+
+// Per-image min-max normalisation and fusion (paper fusion equation):
+// s_fused = lambda*minmax(s_query) + (1-lambda)*minmax(s_act);  s_act == nullptr => s_fused = minmax(s_query).
+hipError_t launch_fuse(const float* s_query, const float* s_act, float* s_fused, int B, int N, float lambda,
+                       hipStream_t stream);
+
+// out[b,j,:] = X[b, idx[b,j], :]  (bit copy; row_bytes multiple of 16).
+hipError_t launch_gather_rows(const void* X, const int32_t* idx, void* out, int B, int N, int k, long row_bytes,
+                              hipStream_t stream);
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
+
+// ---------------------------------------------------------------- select.hip
+// Per image: positions of the m largest of scores[b, 0..n) (ties -> lower position), ascending.
+// out[b,j] = map ? map[b*n + pos] : pos.   n <= 16384.
+hipError_t launch_select_top(const float* scores, int B, int n, int m, const int32_t* map, int32_t* out,
+                             hipStream_t stream);
+
+// ---------------------------------------------------------------- eigen.hip
+// One-sided block Jacobi on the rows of the symmetric PSD matrices A[b] (fp64, pitch nP, nP % 16 == 0,
+// rows/cols >= n zero).  On return row k of A[b] is lambda_k v_k^T.  `ctl` is scratch of jacobi_ctl_bytes(B).
+size_t jacobi_ctl_bytes(int B);
+hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, void* ctl, hipStream_t stream);
+// Subspace energy (paper energy equation) from the converged rows: c[b,i] = sum over the r rows with the
+// largest norm of A[k][i]^2 / |row k|.   `lam` is scratch of B*nP doubles.
+hipError_t launch_subspace_energy(const double* A, int B, int n, int nP, int r, double* lam, float* c,
+                                  hipStream_t stream);
+
+// ---------------------------------------------------------------- greedy.hip
+// Greedy residual picks (variant): pivoted Cholesky of G[b] (fp64, pitch nP).  Lt is scratch [B][k][nP] fp64.
+// order[b,t] = local position picked at step t, resid[b,t] = residual squared norm at that pick.
+hipError_t launch_greedy(const double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid,
+                         hipStream_t stream);
+// idx_out[b,:] = sort ascending of idx_m[b, order[b,:]];  pick_out[b,t] = idx_m[b, order[b,t]] (optional).
+hipError_t launch_greedy_finish(const int32_t* order, const int32_t* idx_m, int B, int M, int k, int32_t* idx_out,
+                                int32_t* pick_out, hipStream_t stream);
+
+}  // namespace covspec

@@ -1,0 +1,92 @@
+"""Host-side checks of the C ABI: symbols, defaults, argument validation (no GPU work is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_02218_amd as C
+from paper_2605_02218_amd import binding as Bd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "covspec.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(covspec_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = C.load_library()
+    names = _declared_functions()
+    assert set(names) == set(Bd.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_params_struct_layout_matches_header():
+    assert ctypes.sizeof(Bd.CovspecParams) == 14 * 4
+
+
+def _p(**kw):
+    base = dict(batch=2, n_tokens=576, d_model=1024, n_query=16, n_heads=8, n_act_layers=4, dtype=C.FP32,
+                keep_k=64, preselect_m=128, rank_r=32)
+    base.update(kw)
+    return C.Params(**base)
+
+
+def test_resolve_defaults():
+    assert C.resolve(_p()) == (64, 128, 32)
+    assert C.resolve(_p(preselect_m=0, rank_r=0)) == (64, 128, 32)
+    assert C.resolve(_p(n_tokens=8192, d_model=1536, keep_k=0, keep_ratio=0.1, preselect_m=0, rank_r=128)) == (819, 1638, 128)
+    assert C.resolve(_p(keep_k=0, keep_ratio=1.0, preselect_m=0, rank_r=3)) == (576, 576, 3)
+    assert C.workspace_size(_p()) > 0
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(batch=0), Bd.INVALID_ARG), (dict(n_query=0), Bd.INVALID_ARG), (dict(n_heads=3), Bd.INVALID_ARG),
+    (dict(dtype=2), Bd.INVALID_ARG), (dict(rel_mode=2), Bd.INVALID_ARG), (dict(lr_mode=-1), Bd.INVALID_ARG),
+    (dict(lam=1.5), Bd.INVALID_ARG), (dict(lam=float("nan")), Bd.INVALID_ARG),
+    (dict(keep_k=200), Bd.INVALID_ARG),                       # k > M
+    (dict(preselect_m=600), Bd.INVALID_ARG),                  # M > N
+    (dict(rank_r=128), Bd.INVALID_ARG),                       # r >= min(M, d)
+    (dict(keep_k=0, keep_ratio=0.0), Bd.INVALID_ARG),
+    (dict(n_act_layers=-1), Bd.INVALID_ARG),
+    (dict(n_tokens=20000), Bd.UNSUPPORTED), (dict(n_act_layers=9), Bd.UNSUPPORTED),
+    (dict(d_model=1028, n_heads=1), Bd.OK), (dict(d_model=1026, n_heads=1), Bd.UNSUPPORTED),
+    (dict(n_tokens=16384, keep_k=4097, preselect_m=8194, rank_r=8), Bd.UNSUPPORTED),
+])
+def test_invalid_params_are_rejected_on_the_host(kw, status):
+    p = _p(**kw)
+    cs = p.c_struct()
+    lib = C.load_library()
+    assert lib.covspec_resolve(ctypes.byref(cs), None, None, None) == status
+    assert (C.workspace_size(p) > 0) == (status == Bd.OK)
+    if status != Bd.OK:
+        with pytest.raises(C.CovspecError):
+            C.resolve(p)
+
+
+def test_greedy_mode_does_not_need_a_rank():
+    assert C.workspace_size(_p(lr_mode=C.LR_GREEDY_RESIDUAL, rank_r=128)) > 0
+
+
+def test_entry_points_reject_null_pointers_and_small_workspaces_before_any_launch():
+    lib = C.load_library()
+    p = _p()
+    cs = p.c_struct()
+    fake = 4096  # never dereferenced: validation fails first
+    assert lib.covspec_score(ctypes.byref(cs), None, None, fake, None, None, None, None, None, fake, 1 << 40, None) == Bd.INVALID_ARG
+    assert lib.covspec_select(ctypes.byref(cs), fake, fake, None, None, None, None, None, fake, 1 << 40, None) == Bd.INVALID_ARG
+    assert lib.covspec_reduce(ctypes.byref(cs), fake, None, fake, None, None, fake, None, fake, 1 << 40, None) == Bd.INVALID_ARG
+    assert lib.covspec_reduce(ctypes.byref(cs), fake, None, fake, None, None, fake, fake, fake, 16, None) == Bd.WORKSPACE_TOO_SMALL
+    assert lib.covspec_reduce(ctypes.byref(cs), fake, None, fake, None, None, fake, fake, None, 1 << 40, None) == Bd.INVALID_ARG
+    assert lib.covspec_reduce(ctypes.byref(cs), fake, None, fake, None, None, fake, fake, fake + 8, 1 << 40, None) == Bd.INVALID_ARG
+    assert lib.covspec_score(None, fake, None, fake, None, None, None, None, None, fake, 1 << 40, None) == Bd.INVALID_ARG
+
+
+def test_status_strings():
+    assert C.status_string(0) == "ok"
+    assert "workspace" in C.status_string(2)
+    assert C.status_string(99) == "unknown status"

@@ -1,0 +1,142 @@
+"""GPU parity: the HIP path behind the C ABI against the CPU oracle, element by element.
+
+Bars: indices bit-exact (ties -> lower index); scores within 1e-5 relative for fp32
+inputs and 2e-2 for bf16 inputs (denominator floored at 1e-3 of the largest reference
+magnitude).  Inputs are seeded and synthetic (covspec_inputs); expected values come
+from the oracle only.
+"""
+import numpy as np
+import pytest
+
+import covspec_inputs as I
+from oracle import covspec_oracle as O
+from tests import util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def C():
+    import paper_2605_02218_amd as C
+    C.load_library()
+    return C
+
+
+SMALL = {
+    "fp32-ragged": I.small_workload(cid=11, name="s-fp32", batch=2, n_tokens=300, d_model=192, dtype=I.FP32,
+                                    n_query=5, n_heads=3, keep_k=20, preselect_m=50, rank_r=8, factor_rank=32,
+                                    n_act_layers=3),
+    "bf16-ragged": I.small_workload(cid=12, name="s-bf16", batch=3, n_tokens=333, d_model=256, dtype=I.BF16,
+                                    n_query=7, n_heads=2, keep_k=24, preselect_m=56, rank_r=10, factor_rank=48,
+                                    n_act_layers=4, structure="dups+outliers"),
+    "bf16-tiles": I.small_workload(cid=13, name="m-bf16", batch=2, n_tokens=700, d_model=512, dtype=I.BF16,
+                                   n_query=33, n_heads=4, keep_k=150, preselect_m=300, rank_r=40, factor_rank=96,
+                                   n_act_layers=2, structure="neardups"),
+}
+
+
+def _cpu(t):
+    return t.detach().cpu().numpy()
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("rel_mode", [0, 1])
+def test_score_matches_oracle(C, name, rel_mode):
+    w = SMALL[name]
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    p = U.lib_params(C, w, w.batch, rel_mode=rel_mode)
+    sq, sa, sf = C.score(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    sq, sa, sf = _cpu(sq), _cpu(sa), _cpu(sf)
+    for b in range(w.batch):
+        ref = U.oracle_image(w, batch, b, U.oracle_params(w, rel_mode=rel_mode))
+        U.assert_scores_close(sq[b], ref["s_query"], w.dtype, "%s s_query[%d]" % (name, b))
+        U.assert_scores_close(sa[b], ref["s_act"], w.dtype, "%s s_act[%d]" % (name, b))
+        U.assert_scores_close(sf[b], ref["s_fused"], w.dtype, "%s s_fused[%d]" % (name, b))
+        if rel_mode == 1:
+            assert abs(float(sq[b].astype(np.float64).sum()) - 1.0) < 1e-4
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_score_without_weights_or_hidden(C, name):
+    w = SMALL[name]
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    p = U.lib_params(C, w, w.batch, n_act_layers=0)
+    sq, sa, sf = C.score(p, dev["X"], None, dev["Q"], None, None)
+    assert sa is None
+    for b in range(w.batch):
+        ref = U.oracle_image(w, batch, b, U.oracle_params(w), use_hidden=False, use_wq=False, use_wk=False)
+        U.assert_scores_close(_cpu(sq)[b], ref["s_query"], w.dtype, "s_query identity")
+        U.assert_scores_close(_cpu(sf)[b], ref["s_fused"], w.dtype, "s_fused identity")
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("lr_mode", [0, 1])
+def test_select_matches_oracle(C, name, lr_mode):
+    import torch
+    w = SMALL[name]
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    op = U.oracle_params(w, lr_mode=lr_mode)
+    refs = [U.oracle_image(w, batch, b, op) for b in range(w.batch)]
+    sf32 = np.stack([O.decision_values(r["s_fused"]) for r in refs])      # oracle scores in, HIP selection out
+    p = U.lib_params(C, w, w.batch, lr_mode=lr_mode)
+    out = C.select(p, dev["X"], torch.from_numpy(sf32).cuda())
+    for b, ref in enumerate(refs):
+        np.testing.assert_array_equal(_cpu(out["idx_m"])[b], ref["idx_m"])
+        if lr_mode == 0:
+            U.assert_scores_close(_cpu(out["c"])[b], ref["c"], w.dtype, "%s c[%d]" % (name, b),
+                                  tol=1e-5 if w.dtype == I.FP32 else 1e-4)
+        else:
+            np.testing.assert_array_equal(_cpu(out["pick_order"])[b], ref["pick_order"])
+            U.assert_scores_close(_cpu(out["resid"])[b], ref["resid"], w.dtype, "%s resid[%d]" % (name, b),
+                                  tol=1e-5 if w.dtype == I.FP32 else 1e-4)
+        np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"],
+                                      err_msg="margin_topk=%r" % ref.get("margin_topk"))
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("modes", [(0, 0), (1, 1)])
+def test_reduce_matches_oracle(C, name, modes):
+    w = SMALL[name]
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    p = U.lib_params(C, w, w.batch, rel_mode=modes[0], lr_mode=modes[1])
+    idx, tok = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    idx2, tok2 = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    assert bool((idx == idx2).all()) and bool((tok.view(dev["X"].dtype) == tok2).all())   # deterministic
+    idx, tok = _cpu(idx), tok.view({I.BF16: __import__("torch").int16, I.FP32: __import__("torch").float32}[w.dtype]).cpu().numpy()
+    X = batch["X"].view(np.int16) if w.dtype == I.BF16 else batch["X"]
+    for b in range(w.batch):
+        ref = U.oracle_image(w, batch, b, U.oracle_params(w, rel_mode=modes[0], lr_mode=modes[1]))
+        np.testing.assert_array_equal(idx[b], ref["idx"], err_msg="margins topm=%r topk=%r" % (
+            ref["margin_topm"], ref.get("margin_topk")))
+        assert len(set(idx[b].tolist())) == w.keep_k and np.all(np.diff(idx[b]) > 0)
+        np.testing.assert_array_equal(tok[b], X[b][idx[b]])                  # bit copy of the stored rows
+
+
+def test_keep_everything_is_identity(C):
+    w = SMALL["bf16-ragged"]
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    for lr in (0, 1):
+        p = U.lib_params(C, w, w.batch, lr_mode=lr, keep_k=w.n_tokens, preselect_m=w.n_tokens, rank_r=5)
+        idx, _ = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+        np.testing.assert_array_equal(_cpu(idx), np.tile(np.arange(w.n_tokens, dtype=np.int32), (w.batch, 1)))
+
+
+def test_select_ties_and_exact_duplicates(C):
+    import torch
+    # constant fused scores: every cut is a tie -> the first M positions; duplicates tie in the energy ranking
+    w = SMALL["bf16-ragged"]
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    sf = torch.zeros(w.batch, w.n_tokens, dtype=torch.float32, device="cuda")
+    sf[:, 100:] = -1.0
+    p = U.lib_params(C, w, w.batch)
+    out = C.select(p, dev["X"], sf)
+    np.testing.assert_array_equal(_cpu(out["idx_m"]), np.tile(np.arange(w.preselect_m, dtype=np.int32), (w.batch, 1)))
+    for b in range(w.batch):
+        ref = O.select(I.as_f64(batch["X"][b], w.dtype), _cpu(sf)[b], U.oracle_params(w))
+        np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"])
