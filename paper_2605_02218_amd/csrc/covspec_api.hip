@@ -74,7 +74,8 @@ int make_plan(const covspec_params* p, Plan* pl) {
   q.dtype = p->dtype; q.rel = p->rel_mode; q.lr = p->lr_mode; q.M = M; q.r = r; q.k = k; q.lambda = p->lambda;
   q.esz = p->dtype == COVSPEC_BF16 ? 2 : 4;
   q.planes = p->dtype == COVSPEC_BF16 ? 3 : 1;
-  q.nparts = gemm_tiles_n(q.d);
+  q.nparts = p->dtype == COVSPEC_BF16 ? gemm_tiles_n(q.d) : gemm64_tiles_n(q.d);
+  const size_t fsz = p->dtype == COVSPEC_BF16 ? 4 : 8;  // bytes per intermediate value
   q.nP = (M + 15) / 16 * 16;
 
   size_t off = 0;
@@ -82,19 +83,19 @@ int make_plan(const covspec_params* p, Plan* pl) {
   const size_t B = q.B, N = q.N, d = q.d, T = q.T, BT = B * T, BN = B * N;
   q.wqT = take(d * d * q.esz);
   q.wkT = take(d * d * q.esz);
-  q.Eq = take(BT * d * 4);
-  q.qn2 = take(BT * 4);
+  q.Eq = take(BT * d * fsz);
+  q.qn2 = take(BT * fsz);
   q.Eq3 = q.G3raw = q.G3 = q.vn2p = q.logits = q.Ev = q.S = q.stats = 0;
   if (q.rel == COVSPEC_REL_COSINE_MAX) {
     if (q.dtype == COVSPEC_BF16) q.Eq3 = take(3 * BT * d * 2);
-    q.G3raw = take((size_t)q.planes * BT * d * 4);
+    q.G3raw = take((size_t)q.planes * BT * d * fsz);
     if (q.dtype == COVSPEC_BF16) q.G3 = take(3 * BT * d * 2);
-    q.vn2p = take(BN * q.nparts * 4);
-    q.logits = take(BN * q.planes * T * 4);
+    q.vn2p = take(BN * q.nparts * fsz);
+    q.logits = take(BN * q.planes * T * fsz);
   } else {
-    q.Ev = take(BN * d * 4);
-    q.S = take(B * q.H * T * N * 4);
-    q.stats = take(B * q.H * T * 8);
+    q.Ev = take(BN * d * fsz);
+    q.S = take(B * q.H * T * N * fsz);
+    q.stats = take(B * q.H * T * 16);
   }
   q.sq = take(BN * 4);
   q.sa = take(BN * 4);
@@ -130,90 +131,104 @@ int check_ws(const Plan& pl, void* ws, size_t bytes) {
 }
 
 // ---- scores: paper Sec. III-A.1 (query-aware), III-A.2 (activity), fusion equation
+//
+// bf16 storage: contractions on the bf16 MFMA with fp32 accumulation, fp32 intermediates.
+// fp32 storage: every contraction and intermediate in fp64 (see gemm64.hip).
 int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, const void* Wq, const void* Wk,
               float* s_query, float* s_act, float* s_fused, void* ws, hipStream_t st) {
   const long B = q.B, N = q.N, d = q.d, T = q.T, BT = B * T, BN = B * N;
-  float* Eq = at<float>(ws, q.Eq);
-  float* qn2 = at<float>(ws, q.qn2);
+  const bool f64 = q.dtype == COVSPEC_FP32;
+  const int in_x = f64 ? IN_F32 : IN_BF16;      // storage type of X, Q, W
+  const int in_mid = f64 ? IN_F64 : IN_F32;     // type of the intermediates
+  void* Eq = at<void>(ws, q.Eq);
+  void* qn2 = at<void>(ws, q.qn2);
   float* sq = s_query ? s_query : at<float>(ws, q.sq);
   float* sf = s_fused ? s_fused : at<float>(ws, q.sf);
   const bool has_act = hidden != nullptr && q.K > 0;
   float* sa = has_act ? (s_act ? s_act : at<float>(ws, q.sa)) : nullptr;
+  auto gemm = [&](const GemmArgs& g, bool a_mid, bool b_mid) -> hipError_t {
+    // a_mid / b_mid: operand is an intermediate (fp64 on the fp64 path) rather than a stored input
+    return f64 ? launch_gemm64_nt(g, a_mid, b_mid, st) : launch_gemm_nt(g, DT_BF16, st);
+  };
 
-  // e(q) = q Wq, kept in fp32
+  // e(q) = q Wq
   if (Wq) {
     HIPCHK(launch_transpose(Wq, at<void>(ws, q.wqT), q.d, q.d, q.dtype, st));
     GemmArgs g;
     g.A = Q; g.B = at<void>(ws, q.wqT); g.C = Eq; g.M = (int)BT; g.N = q.d; g.K = q.d; g.lda = d; g.ldb = d; g.ldc = d;
-    HIPCHK(launch_gemm_nt(g, q.dtype, st));
+    g.epilogue = f64 ? EPI_STORE_F64 : EPI_STORE_F32;
+    HIPCHK(gemm(g, false, false));
   } else {
-    HIPCHK(launch_to_f32(Q, Eq, BT * d, q.dtype, st));
+    HIPCHK(launch_convert(Q, in_x, Eq, f64, BT * d, st));
   }
   if (Wk) HIPCHK(launch_transpose(Wk, at<void>(ws, q.wkT), q.d, q.d, q.dtype, st));
 
   if (q.rel == COVSPEC_REL_COSINE_MAX) {
-    HIPCHK(launch_row_norm2(Eq, qn2, BT, q.d, DT_F32, st));
+    HIPCHK(launch_row_norm2(Eq, in_mid, qn2, f64, BT, q.d, st));
     // fold Wk into the query side: <x Wk, e(q)> = <x, Wk e(q)^T>; the token side then only needs |x Wk|^2
-    const void* Gq;  // per image [planes*T, d] in the storage dtype of X
-    float* vn2 = at<float>(ws, q.vn2p);
+    const void* Gq;  // per image [planes*T, d]
+    void* vn2 = at<void>(ws, q.vn2p);
     int nparts;
     if (Wk) {
-      float* Graw = at<float>(ws, q.G3raw);
+      void* Graw = at<void>(ws, q.G3raw);
       GemmArgs g;
       g.B = Wk; g.C = Graw; g.N = q.d; g.K = q.d; g.lda = d; g.ldb = d; g.ldc = d;
-      if (q.dtype == COVSPEC_BF16) {
-        HIPCHK(launch_sum_split3(Eq, 1, 0, BT, q.d, BT, at<unsigned short>(ws, q.Eq3), st));
+      if (!f64) {
+        HIPCHK(launch_sum_split3((const float*)Eq, 1, 0, BT, q.d, BT, at<unsigned short>(ws, q.Eq3), st));
         g.A = at<void>(ws, q.Eq3); g.M = (int)(3 * BT);
         HIPCHK(launch_gemm_nt(g, DT_BF16, st));
-        HIPCHK(launch_sum_split3(Graw, 3, BT * d, BT, q.d, T, at<unsigned short>(ws, q.G3), st));
+        HIPCHK(launch_sum_split3((const float*)Graw, 3, BT * d, BT, q.d, T, at<unsigned short>(ws, q.G3), st));
         Gq = at<void>(ws, q.G3);
       } else {
-        g.A = Eq; g.M = (int)BT;
-        HIPCHK(launch_gemm_nt(g, DT_F32, st));
+        g.A = Eq; g.M = (int)BT; g.epilogue = EPI_STORE_F64;
+        HIPCHK(launch_gemm64_nt(g, true, false, st));
         Gq = Graw;
       }
       GemmArgs n;
       n.A = X; n.B = at<void>(ws, q.wkT); n.C = vn2; n.M = (int)BN; n.N = q.d; n.K = q.d; n.lda = d; n.ldb = d;
       n.ldc = q.nparts; n.epilogue = EPI_ROWNORM2;
-      HIPCHK(launch_gemm_nt(n, q.dtype, st));
+      HIPCHK(gemm(n, false, false));
       nparts = q.nparts;
     } else {
-      if (q.dtype == COVSPEC_BF16) {
-        HIPCHK(launch_sum_split3(Eq, 1, 0, BT, q.d, T, at<unsigned short>(ws, q.G3), st));
+      if (!f64) {
+        HIPCHK(launch_sum_split3((const float*)Eq, 1, 0, BT, q.d, T, at<unsigned short>(ws, q.G3), st));
         Gq = at<void>(ws, q.G3);
       } else {
         Gq = Eq;
       }
-      HIPCHK(launch_row_norm2(X, vn2, BN, q.d, q.dtype, st));
+      HIPCHK(launch_row_norm2(X, in_x, vn2, f64, BN, q.d, st));
       nparts = 1;
     }
-    float* logits = at<float>(ws, q.logits);
+    void* logits = at<void>(ws, q.logits);
     GemmArgs l;
     l.A = X; l.B = Gq; l.C = logits; l.M = q.N; l.N = q.planes * q.T; l.K = q.d; l.lda = d; l.ldb = d; l.ldc = q.planes * T;
     l.batch = q.B; l.strideA = N * d; l.strideB = (long)q.planes * T * d; l.strideC = N * q.planes * T;
-    HIPCHK(launch_gemm_nt(l, q.dtype, st));
-    HIPCHK(launch_cosine_max(logits, q.planes, vn2, nparts, qn2, sq, q.B, q.N, q.T, st));
+    l.epilogue = f64 ? EPI_STORE_F64 : EPI_STORE_F32;
+    HIPCHK(gemm(l, false, true));
+    HIPCHK(launch_cosine_max(logits, q.planes, vn2, nparts, qn2, f64, sq, q.B, q.N, q.T, st));
   } else {
-    // variant: e(v) materialised in fp32, per-head logits with the fp32 MFMA, softmax over the visual tokens
-    float* Ev = at<float>(ws, q.Ev);
+    // variant: e(v) materialised, per-head logits, softmax over the visual tokens
+    void* Ev = at<void>(ws, q.Ev);
     if (Wk) {
       GemmArgs g;
       g.A = X; g.B = at<void>(ws, q.wkT); g.C = Ev; g.M = (int)BN; g.N = q.d; g.K = q.d; g.lda = d; g.ldb = d; g.ldc = d;
-      HIPCHK(launch_gemm_nt(g, q.dtype, st));
+      g.epilogue = f64 ? EPI_STORE_F64 : EPI_STORE_F32;
+      HIPCHK(gemm(g, false, false));
     } else {
-      HIPCHK(launch_to_f32(X, Ev, BN * d, q.dtype, st));
+      HIPCHK(launch_convert(X, in_x, Ev, f64, BN * d, st));
     }
     const int dh = q.d / q.H;
-    float* S = at<float>(ws, q.S);
+    void* S = at<void>(ws, q.S);
     GemmArgs g;
     g.A = Eq; g.B = Ev; g.C = S; g.M = q.T; g.N = q.N; g.K = dh; g.lda = d; g.ldb = d; g.ldc = N;
     g.batch = q.B * q.H; g.batch_inner = q.H;
     g.strideA = T * d; g.strideA2 = dh; g.strideB = N * d; g.strideB2 = dh; g.strideC = (long)q.H * T * N; g.strideC2 = T * N;
-    HIPCHK(launch_gemm_nt(g, DT_F32, st));
-    const float scale = (float)(1.0 / sqrt((double)dh));
-    float2* stats = at<float2>(ws, q.stats);
-    HIPCHK(launch_softmax_stats(S, stats, B * q.H * T, q.N, scale, st));
-    HIPCHK(launch_softmax_mean(S, stats, sq, q.B, q.H * q.T, q.N, scale, st));
+    g.epilogue = f64 ? EPI_STORE_F64 : EPI_STORE_F32;
+    HIPCHK(f64 ? launch_gemm64_nt(g, true, true, st) : launch_gemm_nt(g, DT_F32, st));
+    const double scale = 1.0 / sqrt((double)dh);
+    void* stats = at<void>(ws, q.stats);
+    HIPCHK(launch_softmax_stats(S, f64, stats, B * q.H * T, q.N, scale, st));
+    HIPCHK(launch_softmax_mean(S, f64, stats, sq, q.B, q.H * q.T, q.N, scale, st));
   }
 
   if (has_act) HIPCHK(launch_activity(hidden, sa, q.B, q.N, q.d, q.K, q.dtype, st));
@@ -236,7 +251,12 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
   g.batch = q.B; g.strideA = N * d; g.strideB = N * d; g.strideC = (long)q.nP * q.nP;
   g.gatherA = idxm; g.gatherB = idxm; g.gstrideA = q.M; g.gstrideB = q.M;
   g.epilogue = EPI_STORE_F64;
-  HIPCHK(launch_gemm_nt(g, q.dtype, st));
+  // The greedy variant ranks residuals, i.e. differences of Gram entries that shrink far below the
+  // entries themselves, so its Gram matrix is accumulated in fp64; the energy ranking is not a
+  // cancellation and takes the bf16 MFMA with fp32 partial sums flushed into fp64.
+  if (q.dtype == COVSPEC_FP32) HIPCHK(launch_gemm64_nt(g, false, false, st));
+  else if (q.lr == COVSPEC_LR_GREEDY_RESIDUAL) HIPCHK(launch_gemm64_bf16(g, st));
+  else HIPCHK(launch_gemm_nt(g, DT_BF16, st));
 
   if (q.lr == COVSPEC_LR_ENERGY_TOPK) {
     float* c = c_out ? c_out : at<float>(ws, q.c);

@@ -1,6 +1,8 @@
 // HBM-bound and small per-token kernels of the token-selection path:
 // activity score, row norms, format conversion and splitting, the cosine-max
 // and softmax epilogues, min-max fusion, gather.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -33,8 +35,9 @@ template <> struct Vec<DT_F32> {
 // One wave per token.  The wave walks the row in 16-byte-per-lane chunks and reads the K+1 slices of a
 // chunk back to back, keeping the previous slice in registers, so every hidden element is read from
 // HBM exactly once.  Squared differences accumulate in fp32 per (layer, lane) and are wave-reduced in a
-// fixed order, so equal rows give bit-equal scores.
-template <int DT, int K>
+// fixed order, so equal rows give bit-equal scores.  fp32 inputs accumulate in fp64, bf16 inputs in fp32
+// (a difference of two bf16 values is exact in fp32).
+template <int DT, int K, typename Acc>
 __global__ __launch_bounds__(256) void activity_kernel(const void* __restrict__ hidden, float* __restrict__ s_act,
                                                         long tokens, int N, int d) {
   constexpr int V = Vec<DT>::N;
@@ -44,9 +47,9 @@ __global__ __launch_bounds__(256) void activity_kernel(const void* __restrict__ 
   const long b = token / N, i = token - b * N;
   const long slice = (long)N * d;
   const long base = (b * (K + 1) * N + i) * (long)d;
-  float acc[K];
+  Acc acc[K];
 #pragma unroll
-  for (int l = 0; l < K; ++l) acc[l] = 0.f;
+  for (int l = 0; l < K; ++l) acc[l] = (Acc)0;
   for (int c = lane * V; c < d; c += 64 * V) {
     float prev[V], cur[V];
     Vec<DT>::load(hidden, base + c, prev);
@@ -55,8 +58,8 @@ __global__ __launch_bounds__(256) void activity_kernel(const void* __restrict__ 
       Vec<DT>::load(hidden, base + l * slice + c, cur);
 #pragma unroll
       for (int e = 0; e < V; ++e) {
-        float df = cur[e] - prev[e];
-        acc[l - 1] = fmaf(df, df, acc[l - 1]);
+        const Acc df = (Acc)cur[e] - (Acc)prev[e];
+        acc[l - 1] += df * df;
         prev[e] = cur[e];
       }
     }
@@ -71,7 +74,7 @@ template <int DT>
 hipError_t activity_dispatch(const void* hidden, float* s_act, long tokens, int N, int d, int K, hipStream_t st) {
   dim3 grid((unsigned)((tokens + 3) / 4)), block(256);
 #define COVSPEC_ACT_CASE(KK) \
-  case KK: hipLaunchKernelGGL((activity_kernel<DT, KK>), grid, block, 0, st, hidden, s_act, tokens, N, d); break;
+  case KK: hipLaunchKernelGGL((activity_kernel<DT, KK, typename std::conditional<DT == DT_F32, double, float>::type>), grid, block, 0, st, hidden, s_act, tokens, N, d); break;
   switch (K) {
     COVSPEC_ACT_CASE(1) COVSPEC_ACT_CASE(2) COVSPEC_ACT_CASE(3) COVSPEC_ACT_CASE(4)
     COVSPEC_ACT_CASE(5) COVSPEC_ACT_CASE(6) COVSPEC_ACT_CASE(7) COVSPEC_ACT_CASE(8)
@@ -82,18 +85,21 @@ hipError_t activity_dispatch(const void* hidden, float* s_act, long tokens, int 
 }
 
 // ---------------------------------------------------------------- row norms
-template <int DT>
-__global__ __launch_bounds__(256) void row_norm2_kernel(const void* __restrict__ x, float* __restrict__ out, long rows, int d) {
-  constexpr int V = Vec<DT>::N;
+template <typename In> __device__ __forceinline__ double load_as_f64(const In* p, long i);
+template <> __device__ __forceinline__ double load_as_f64<bf16_t>(const bf16_t* p, long i) { return (double)bf16_to_f32(p[i]); }
+template <> __device__ __forceinline__ double load_as_f64<float>(const float* p, long i) { return (double)p[i]; }
+template <> __device__ __forceinline__ double load_as_f64<double>(const double* p, long i) { return p[i]; }
+
+// one wave per row; Out = float accumulates in fp32, Out = double in fp64
+template <typename In, typename Out>
+__global__ __launch_bounds__(256) void row_norm2_kernel(const In* __restrict__ x, Out* __restrict__ out, long rows, int d) {
   const int lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  float acc = 0.f;
-  for (int c = lane * V; c < d; c += 64 * V) {
-    float v[V];
-    Vec<DT>::load(x, row * d + c, v);
-#pragma unroll
-    for (int e = 0; e < V; ++e) acc = fmaf(v[e], v[e], acc);
+  Out acc = (Out)0;
+  for (int c = lane; c < d; c += 64) {
+    const Out v = (Out)load_as_f64<In>(x, row * d + c);
+    acc += v * v;
   }
   acc = wave_sum(acc);
   if (lane == 0) out[row] = acc;
@@ -113,10 +119,10 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
 }
 
 // ---------------------------------------------------------------- conversion / splitting
-template <int DT>
-__global__ void to_f32_kernel(const void* __restrict__ src, float* __restrict__ dst, long n) {
+template <typename In, typename Out>
+__global__ void convert_kernel(const In* __restrict__ src, Out* __restrict__ dst, long n) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dst[i] = Vec<DT>::load1(src, i);
+  if (i < n) dst[i] = (Out)load_as_f64<In>(src, i);
 }
 
 __device__ __forceinline__ float sum_planes(const float* src, int planes, long plane_stride, long i) {
@@ -143,17 +149,13 @@ __global__ void sum_split3_kernel(const float* __restrict__ src, int planes, lon
   out[((g * 3 + 2) * rpg + j) * d + c] = lo;
 }
 
-__global__ void sum_planes_kernel(const float* __restrict__ src, int planes, long plane_stride, long n, float* __restrict__ out) {
-  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out[i] = sum_planes(src, planes, plane_stride, i);
-}
-
 // ---------------------------------------------------------------- cosine-max epilogue (paper Sec. III-A.1)
 // One wave per token; lanes stride over the query keywords.  The scalar arithmetic is fp64 so that the only
 // error left in the score is that of the fp32-accumulated contractions feeding it.
-__global__ __launch_bounds__(256) void cosine_max_kernel(const float* __restrict__ logits, int planes,
-                                                          const float* __restrict__ vnorm2, int nparts,
-                                                          const float* __restrict__ qnorm2, float* __restrict__ s_query,
+template <typename F>
+__global__ __launch_bounds__(256) void cosine_max_kernel(const F* __restrict__ logits, int planes,
+                                                          const F* __restrict__ vnorm2, int nparts,
+                                                          const F* __restrict__ qnorm2, float* __restrict__ s_query,
                                                           long tokens, int N, int T) {
   const int lane = threadIdx.x & 63;
   const long token = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(256) void cosine_max_kernel(const float* __restrict
   double n2 = 0.0;
   for (int t = 0; t < nparts; ++t) n2 += (double)vnorm2[token * nparts + t];
   const double nv = sqrt(n2);
-  const float* L = logits + token * (long)planes * T;
+  const F* L = logits + token * (long)planes * T;
   double best = -INFINITY;
   for (int j = lane; j < T; j += 64) {
     double dot = (double)L[j];
@@ -177,33 +179,35 @@ __global__ __launch_bounds__(256) void cosine_max_kernel(const float* __restrict
 
 // ---------------------------------------------------------------- softmax relevance (variant)
 // stats[row] = (max_i scale*S[row,i], sum_i exp(scale*S[row,i] - max)); one wave per row.
-__global__ __launch_bounds__(256) void softmax_stats_kernel(const float* __restrict__ S, float2* __restrict__ stats,
-                                                             long rows, int N, float scale) {
+template <typename F>
+__global__ __launch_bounds__(256) void softmax_stats_kernel(const F* __restrict__ S, double2* __restrict__ stats,
+                                                             long rows, int N, double scale) {
   const int lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const float* p = S + row * (long)N;
-  float m = -INFINITY;
-  for (int i = lane; i < N; i += 64) m = fmaxf(m, p[i] * scale);
+  const F* p = S + row * (long)N;
+  F m = -INFINITY;
+  for (int i = lane; i < N; i += 64) { const F v = p[i] * (F)scale; m = v > m ? v : m; }
   m = wave_max(m);
   double z = 0.0;
-  for (int i = lane; i < N; i += 64) z += (double)expf(p[i] * scale - m);
+  for (int i = lane; i < N; i += 64) z += (double)exp(p[i] * (F)scale - m);
   z = wave_sum(z);
-  if (lane == 0) stats[row] = make_float2(m, (float)z);
+  if (lane == 0) stats[row] = make_double2((double)m, z);
 }
 
 // s_query[b,i] = (1/HT) sum_{row < HT} exp(scale*S[b,row,i] - max_row) / Z_row, rows added in order.
-__global__ __launch_bounds__(256) void softmax_mean_kernel(const float* __restrict__ S, const float2* __restrict__ stats,
-                                                            float* __restrict__ s_query, int HT, int N, float scale) {
+template <typename F>
+__global__ __launch_bounds__(256) void softmax_mean_kernel(const F* __restrict__ S, const double2* __restrict__ stats,
+                                                            float* __restrict__ s_query, int HT, int N, double scale) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   const int b = blockIdx.y;
   if (i >= N) return;
-  const float* p = S + (long)b * HT * N + i;
-  const float2* st = stats + (long)b * HT;
+  const F* p = S + (long)b * HT * N + i;
+  const double2* st = stats + (long)b * HT;
   double acc = 0.0;
   for (int r = 0; r < HT; ++r) {
-    float2 mz = st[r];
-    acc += (double)expf(p[(long)r * N] * scale - mz.x) / (double)mz.y;
+    const double2 mz = st[r];
+    acc += (double)exp(p[(long)r * N] * (F)scale - (F)mz.x) / mz.y;
   }
   s_query[(long)b * N + i] = (float)(acc / HT);
 }
@@ -278,17 +282,21 @@ hipError_t launch_activity(const void* hidden, float* s_act, int B, int N, int d
                           : activity_dispatch<DT_F32>(hidden, s_act, tokens, N, d, K, st);
 }
 
-hipError_t launch_row_norm2(const void* x, float* out, long rows, int d, int dtype, hipStream_t st) {
+hipError_t launch_row_norm2(const void* x, int in_type, void* out, bool out_f64, long rows, int d, hipStream_t st) {
   dim3 grid(blocks_for(rows, 4)), block(256);
-  if (dtype == DT_BF16) hipLaunchKernelGGL((row_norm2_kernel<DT_BF16>), grid, block, 0, st, x, out, rows, d);
-  else hipLaunchKernelGGL((row_norm2_kernel<DT_F32>), grid, block, 0, st, x, out, rows, d);
+  if (in_type == IN_BF16 && !out_f64) hipLaunchKernelGGL((row_norm2_kernel<bf16_t, float>), grid, block, 0, st, (const bf16_t*)x, (float*)out, rows, d);
+  else if (in_type == IN_F32 && !out_f64) hipLaunchKernelGGL((row_norm2_kernel<float, float>), grid, block, 0, st, (const float*)x, (float*)out, rows, d);
+  else if (in_type == IN_F32 && out_f64) hipLaunchKernelGGL((row_norm2_kernel<float, double>), grid, block, 0, st, (const float*)x, (double*)out, rows, d);
+  else if (in_type == IN_F64 && out_f64) hipLaunchKernelGGL((row_norm2_kernel<double, double>), grid, block, 0, st, (const double*)x, (double*)out, rows, d);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
-hipError_t launch_to_f32(const void* src, float* dst, long n, int dtype, hipStream_t st) {
+hipError_t launch_convert(const void* src, int in_type, void* dst, bool out_f64, long n, hipStream_t st) {
   dim3 grid(blocks_for(n, 256)), block(256);
-  if (dtype == DT_BF16) hipLaunchKernelGGL((to_f32_kernel<DT_BF16>), grid, block, 0, st, src, dst, n);
-  else hipLaunchKernelGGL((to_f32_kernel<DT_F32>), grid, block, 0, st, src, dst, n);
+  if (in_type == IN_BF16 && !out_f64) hipLaunchKernelGGL((convert_kernel<bf16_t, float>), grid, block, 0, st, (const bf16_t*)src, (float*)dst, n);
+  else if (in_type == IN_F32 && out_f64) hipLaunchKernelGGL((convert_kernel<float, double>), grid, block, 0, st, (const float*)src, (double*)dst, n);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
@@ -299,30 +307,27 @@ hipError_t launch_sum_split3(const float* src, int planes, long plane_stride, lo
   return hipGetLastError();
 }
 
-hipError_t launch_sum_planes(const float* src, int planes, long plane_stride, long n, float* out, hipStream_t st) {
-  dim3 grid(blocks_for(n, 256)), block(256);
-  hipLaunchKernelGGL(sum_planes_kernel, grid, block, 0, st, src, planes, plane_stride, n, out);
-  return hipGetLastError();
-}
-
-hipError_t launch_cosine_max(const float* logits, int planes, const float* vnorm2, int nparts, const float* qnorm2,
+hipError_t launch_cosine_max(const void* logits, int planes, const void* vnorm2, int nparts, const void* qnorm2, bool f64,
                              float* s_query, int B, int N, int T, hipStream_t st) {
   long tokens = (long)B * N;
   dim3 grid(blocks_for(tokens, 4)), block(256);
-  hipLaunchKernelGGL(cosine_max_kernel, grid, block, 0, st, logits, planes, vnorm2, nparts, qnorm2, s_query, tokens, N, T);
+  if (f64) hipLaunchKernelGGL((cosine_max_kernel<double>), grid, block, 0, st, (const double*)logits, planes, (const double*)vnorm2, nparts, (const double*)qnorm2, s_query, tokens, N, T);
+  else hipLaunchKernelGGL((cosine_max_kernel<float>), grid, block, 0, st, (const float*)logits, planes, (const float*)vnorm2, nparts, (const float*)qnorm2, s_query, tokens, N, T);
   return hipGetLastError();
 }
 
-hipError_t launch_softmax_stats(const float* S, float2* stats, long rows, int N, float scale, hipStream_t st) {
+hipError_t launch_softmax_stats(const void* S, bool f64, void* stats, long rows, int N, double scale, hipStream_t st) {
   dim3 grid(blocks_for(rows, 4)), block(256);
-  hipLaunchKernelGGL(softmax_stats_kernel, grid, block, 0, st, S, stats, rows, N, scale);
+  if (f64) hipLaunchKernelGGL((softmax_stats_kernel<double>), grid, block, 0, st, (const double*)S, (double2*)stats, rows, N, scale);
+  else hipLaunchKernelGGL((softmax_stats_kernel<float>), grid, block, 0, st, (const float*)S, (double2*)stats, rows, N, scale);
   return hipGetLastError();
 }
 
-hipError_t launch_softmax_mean(const float* S, const float2* stats, float* s_query, int B, int HT, int N, float scale,
+hipError_t launch_softmax_mean(const void* S, bool f64, const void* stats, float* s_query, int B, int HT, int N, double scale,
                                hipStream_t st) {
   dim3 grid((N + 255) / 256, B), block(256);
-  hipLaunchKernelGGL(softmax_mean_kernel, grid, block, 0, st, S, stats, s_query, HT, N, scale);
+  if (f64) hipLaunchKernelGGL((softmax_mean_kernel<double>), grid, block, 0, st, (const double*)S, (const double2*)stats, s_query, HT, N, scale);
+  else hipLaunchKernelGGL((softmax_mean_kernel<float>), grid, block, 0, st, (const float*)S, (const double2*)stats, s_query, HT, N, scale);
   return hipGetLastError();
 }
 

@@ -35,6 +35,15 @@ struct GemmArgs {
 int gemm_tiles_n(int N);
 hipError_t launch_gemm_nt(const GemmArgs& g, int dtype, hipStream_t stream);
 
+// ---------------------------------------------------------------- gemm64.hip
+// Same contraction entirely in fp64 (v_mfma_f64_16x16x4); A and B are fp32 or fp64, C is fp64.
+// Epilogues: EPI_STORE_F64, EPI_ROWNORM2 (fp64 partials, one per 64-column tile).
+int gemm64_tiles_n(int N);
+hipError_t launch_gemm64_nt(const GemmArgs& g, bool a_is_f64, bool b_is_f64, hipStream_t stream);
+// Both operands bf16: products of bf16 values are exact in fp64 and the sum is fp64, so the result is the
+// exactly rounded contraction to ~1e-16 (used where differences of Gram entries decide a ranking).
+hipError_t launch_gemm64_bf16(const GemmArgs& g, hipStream_t stream);
+
 // ---------------------------------------------------------------- elementwise.hip
 // out[c][r] = in[r][c] for a rows x cols matrix of bf16 or fp32 elements.
 hipError_t launch_transpose(const void* in, void* out, int rows, int cols, int dtype, hipStream_t stream);
@@ -42,31 +51,32 @@ hipError_t launch_transpose(const void* in, void* out, int rows, int cols, int d
 // Token activity (paper Sec. III-A.2): s_act[b,i] = (1/K) sum_l ||hidden[b,l,i,:] - hidden[b,l-1,i,:]||_2.
 hipError_t launch_activity(const void* hidden, float* s_act, int B, int N, int d, int K, int dtype, hipStream_t stream);
 
-// out[row] = sum_c x[row,c]^2 (fp32 result, fp64 when out64 != nullptr) for rows x d.
-hipError_t launch_row_norm2(const void* x, float* out, long rows, int d, int dtype, hipStream_t stream);
+enum { IN_BF16 = 0, IN_F32 = 1, IN_F64 = 2 };
 
-// dst fp32 = convert(src), n elements.
-hipError_t launch_to_f32(const void* src, float* dst, long n, int dtype, hipStream_t stream);
+// out[row] = sum_c x[row,c]^2 for rows x d; out is fp32 (accumulated in fp32) or fp64.
+hipError_t launch_row_norm2(const void* x, int in_type, void* out, bool out_f64, long rows, int d, hipStream_t stream);
+
+// dst = convert(src), n elements: bf16 -> fp32 or fp32 -> fp64.
+hipError_t launch_convert(const void* src, int in_type, void* dst, bool out_f64, long n, hipStream_t stream);
 
 // v[r,c] = sum_{p < planes} src[p*plane_stride + r*d + c] (added in plane order), then split into three
 // bf16 planes hi/mid/lo with hi+mid+lo == v to ~2^-25 relative.  Output row of (r, s):
 // ((r / rows_per_group) * 3 + s) * rows_per_group + r % rows_per_group.
 hipError_t launch_sum_split3(const float* src, int planes, long plane_stride, long rows, int d, long rows_per_group,
                              unsigned short* out, hipStream_t stream);
-// v as above, stored as fp32 (the fp32 path needs no split).
-hipError_t launch_sum_planes(const float* src, int planes, long plane_stride, long n, float* out, hipStream_t stream);
 
 // Query-aware score (paper Sec. III-A.1): s_query[b,i] = max_j L[b,i,j] / max(|e(v_i)| |e(q_j)|, 1e-30) with
 // L[b,i,j] = sum_{s<planes} logits[b,i,s*T+j], |e(v_i)|^2 = sum_{t<nparts} vnorm2[(b*N+i)*nparts + t],
-// |e(q_j)|^2 = qnorm2[b*T+j].
-hipError_t launch_cosine_max(const float* logits, int planes, const float* vnorm2, int nparts, const float* qnorm2,
+// |e(q_j)|^2 = qnorm2[b*T+j].  The three inputs are fp32, or fp64 when f64 is set.
+hipError_t launch_cosine_max(const void* logits, int planes, const void* vnorm2, int nparts, const void* qnorm2, bool f64,
                              float* s_query, int B, int N, int T, hipStream_t stream);
 
-// Attention-softmax relevance (variant): S is [B,H,T,N] fp32 logits (unscaled).  Pass 1 writes per (b,h,j)
-// the row maximum and the sum of exponentials of scale*S; pass 2 averages the probabilities over (h,j).
-hipError_t launch_softmax_stats(const float* S, float2* stats, long rows, int N, float scale, hipStream_t stream);
-hipError_t launch_softmax_mean(const float* S, const float2* stats, float* s_query, int B, int HT, int N, float scale,
-                               hipStream_t stream);
+// Attention-softmax relevance (variant): S is [B,H,T,N] logits (unscaled; fp32, or fp64 when f64 is set).
+// Pass 1 writes per (b,h,j) the row maximum and the sum of exponentials of scale*S as a double2; pass 2
+// averages the probabilities over (h,j).
+hipError_t launch_softmax_stats(const void* S, bool f64, void* stats, long rows, int N, double scale, hipStream_t stream);
+hipError_t launch_softmax_mean(const void* S, bool f64, const void* stats, float* s_query, int B, int HT, int N,
+                               double scale, hipStream_t stream);
 
 // Per-image min-max normalisation and fusion (paper fusion equation):
 // s_fused = lambda*minmax(s_query) + (1-lambda)*minmax(s_act);  s_act == nullptr => s_fused = minmax(s_query).
