@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the visual-token-reduction path (score + select + gather) on one MI355X.
+
+A step is one covspec_reduce call over one batch of a synthetic workload whose inputs are
+already resident in HBM.  Prints ONE JSON line: images/sec, the roofline position of the
+dominant kernel (stage times measured live with HIP events recorded by the library on the
+work stream) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK = {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0, "mfma_fp64_TFLOPs": 78.6}
+
+
+def _params(C, w, rel, lr):
+    return C.Params(batch=w.batch, n_tokens=w.n_tokens, d_model=w.d_model, n_query=w.n_query, n_heads=w.n_heads,
+                    n_act_layers=w.n_act_layers, dtype=w.dtype, rel_mode=rel, lr_mode=lr, preselect_m=w.preselect_m,
+                    rank_r=w.rank_r, keep_k=w.keep_k, lam=w.lam)
+
+
+def _upload(batch, dtype):
+    import numpy as np
+    import torch
+    import covspec_inputs as I
+    out = {}
+    for k, v in batch.items():
+        if dtype == I.BF16:
+            out[k] = torch.from_numpy(np.ascontiguousarray(v).view(np.int16)).cuda().view(torch.bfloat16)
+        else:
+            out[k] = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).cuda()
+    return out
+
+
+def _gen(w, workers=16):
+    from concurrent.futures import ThreadPoolExecutor
+    import numpy as np
+    import covspec_inputs as I
+    with ThreadPoolExecutor(max_workers=min(workers, w.batch)) as ex:
+        per = list(ex.map(lambda b: I.make_image(w, b), range(w.batch)))
+    out = {k: np.stack([p[k] for p in per]) for k in ("X", "Q", "hidden")}
+    out.update(I.make_weights(w))
+    return out
+
+
+def time_reduce(C, p, dev, ws, steps, warmup):
+    """Wall-clock ms per step of covspec_reduce, K steps bracketed by synchronisation."""
+    import torch
+    k, _, _ = C.resolve(p)
+    idx = torch.empty(p.batch, k, dtype=torch.int32, device="cuda")
+    tok = torch.empty(p.batch, k, p.d_model, dtype=dev["X"].dtype, device="cuda")
+    args = (p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    for _ in range(warmup):
+        C.reduce(*args, workspace=ws, idx_out=idx, tokens_out=tok)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        C.reduce(*args, workspace=ws, idx_out=idx, tokens_out=tok)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def stage_times(C, p, dev, ws, steps):
+    """Mean ms per stage over `steps` calls, from events the library records on the work stream."""
+    import torch
+    k, _, _ = C.resolve(p)
+    idx = torch.empty(p.batch, k, dtype=torch.int32, device="cuda")
+    tok = torch.empty(p.batch, k, p.d_model, dtype=dev["X"].dtype, device="cuda")
+    sets = []
+    for _ in range(steps):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(C.NUM_STAGE_EVENTS)]
+        for e in evs:
+            e.record()           # creates the underlying hipEvent_t
+        sets.append(evs)
+    torch.cuda.synchronize()
+    for evs in sets:
+        C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"], workspace=ws, idx_out=idx,
+                 tokens_out=tok, stage_events=evs)
+    torch.cuda.synchronize()
+    out = {}
+    for i, name in enumerate(C.STAGES):
+        out[name] = sum(evs[i].elapsed_time(evs[i + 1]) for evs in sets) / steps
+    return out
+
+
+def roofline_for(w, p_modes, stages, C):
+    """Roofline object of the dominant stage's kernel (algorithmic work / measured duration)."""
+    import covspec_inputs as I
+    B, N, d, T, K = w.batch, w.n_tokens, w.d_model, w.n_query, w.n_act_layers
+    M, k = w.preselect_m, w.keep_k
+    e = 2 if w.dtype == I.BF16 else 4
+    nP = (M + 15) // 16 * 16
+    nb = nP // 8
+    # stage -> (kernel, bound, peak, unit, algorithmic work per launch, launches per step)
+    table = {
+        "token_projection": ("gemm_nt_kernel<bf16,rownorm2>" if p_modes[0] == 0 else "gemm_nt_kernel<bf16,store>",
+                             "mfma", PEAK["mfma_bf16_TFLOPs"] if e == 2 else PEAK["mfma_fp64_TFLOPs"], "TFLOP/s",
+                             2.0 * B * N * d * d / 1e12, 1),
+        "activity": ("activity_kernel", "hbm", PEAK["hbm_GBps"], "GB/s", (K + 1) * B * N * d * e / 1e9, 1),
+        "gather": ("gather_rows_kernel", "hbm", PEAK["hbm_GBps"], "GB/s", 2.0 * B * k * d * e / 1e9, 1),
+        "gram": ("gemm_nt_kernel<gather,f64>" if p_modes[1] == 0 else "gemm64_kernel<bf16>",
+                 "mfma", PEAK["mfma_bf16_TFLOPs"] if (e == 2 and p_modes[1] == 0) else PEAK["mfma_fp64_TFLOPs"],
+                 "TFLOP/s", 2.0 * B * M * M * d / 1e12, 1),
+    }
+    if p_modes[1] == 0:
+        # one launch = one tournament round: every pair of 8-row blocks forms a 16x16 Gram block (2*16*16*nP flops)
+        # and applies a 16x16 rotation block (2*16*16*nP flops) on the fp64 MFMA
+        table["lowrank"] = ("jacobi_round_kernel", "mfma", PEAK["mfma_fp64_TFLOPs"], "TFLOP/s",
+                            B * (nb // 2) * 4.0 * 256 * nP / 1e12, C.JACOBI_MAX_SWEEPS * (nb - 1))
+    else:
+        table["lowrank"] = ("greedy_kernel", "alu", 78.6, "TFLOP/s", 1.0 * B * M * k * k / 1e12, 1)
+    dom = max((s for s in stages if s in table), key=lambda s: stages[s])
+    kern, bound, peak, unit, work, launches = table[dom]
+    avg_ms = stages[dom] / launches
+    achieved = work / (avg_ms / 1e3)
+    return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+            "frac": round(achieved / peak, 5), "traffic": None, "kernel": kern, "stage": dom,
+            "launches_per_step": launches, "avg_launch_ms": round(avg_ms, 5)}
+
+
+def cpu_baseline(w, batch, rel, lr, budget_s=20.0):
+    """The oracle, as it stands, on a bounded sample of the workload's images."""
+    import covspec_inputs as I
+    from oracle import covspec_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([t.get("num_threads", 1) for t in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    op = O.Params(n_heads=w.n_heads, rel_mode=rel, lr_mode=lr, preselect_m=w.preselect_m, rank_r=w.rank_r,
+                  keep_k=w.keep_k, lam=w.lam)
+    Wq, Wk = I.as_f64(batch["Wq"], w.dtype), I.as_f64(batch["Wk"], w.dtype)
+    done, t0 = 0, time.perf_counter()
+    while done < w.batch and (done == 0 or (time.perf_counter() - t0) * (done + 1) / done < budget_s):
+        b = done
+        O.reduce(I.as_f64(batch["X"][b], w.dtype), I.as_f64(batch["hidden"][b], w.dtype),
+                 I.as_f64(batch["Q"][b], w.dtype), Wq, Wk, op)
+        done += 1
+    dt = time.perf_counter() - t0
+    return {"value": round(done / dt, 4), "unit": "images/s", "cores": int(cores), "kind": "oracle",
+            "sample": "first %d of %d images of the workload, %.1f s (fp64 NumPy incl. conversion of the stored inputs)"
+                      % (done, w.batch, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=5, help="1..5 (default 5: the largest single-GPU workload)")
+    ap.add_argument("--pipeline", choices=["paper", "variant"], default="paper")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all", action="store_true", help="also time the other workloads and pipeline (extra keys)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (images shard trivially across GPUs; no multi-GPU path "
+                 "exists or is measured) -- rerun with --gpus 1")
+
+    import torch
+    import covspec_inputs as I
+    import paper_2605_02218_amd as C
+    C.load_library()
+    torch.cuda.set_device(0)
+    modes = (0, 0) if a.pipeline == "paper" else (1, 1)
+    w = I.WORKLOADS[a.workload]
+
+    batch = _gen(w)
+    dev = _upload(batch, w.dtype)
+    p = _params(C, w, *modes)
+    ws = C.alloc_workspace(p)
+    ms = time_reduce(C, p, dev, ws, a.steps, a.warmup)
+    stages = stage_times(C, p, dev, ws, min(a.steps, 10))
+    line = {
+        "metric": "images/sec for visual-token reduction (score+select+gather)",
+        "value": round(w.batch / ms * 1e3, 3), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == I.BF16 else "f64", "data": "synthetic",
+        "config": {"workload": "%d:%s B=%d N=%d d=%d T=%d H=%d K=%d k=%d M=%d r=%d" % (
+            w.cid, w.name, w.batch, w.n_tokens, w.d_model, w.n_query, w.n_heads, w.n_act_layers, w.keep_k,
+            w.preselect_m, w.rank_r), "pipeline": "paper: cosine-max relevance + rank-r SVD energy" if modes == (0, 0)
+            else "variant: attention-softmax relevance + greedy residual picks", "entry_point": "covspec_reduce"},
+        "roofline": roofline_for(w, modes, stages, C),
+        "stages_ms": {k: round(v, 4) for k, v in stages.items()},
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, batch, *modes)
+    if a.all:
+        extra = {}
+        other = (1, 1) if modes == (0, 0) else (0, 0)
+        p2 = _params(C, w, *other)
+        ws2 = C.alloc_workspace(p2)
+        extra["%d:%s" % (w.cid, "variant" if other == (1, 1) else "paper")] = round(
+            w.batch / time_reduce(C, p2, dev, ws2, max(3, a.steps // 4), 1) * 1e3, 2)
+        del ws2, dev, ws
+        for cid in sorted(I.WORKLOADS):
+            if cid == w.cid:
+                continue
+            wo = I.WORKLOADS[cid]
+            devo = _upload(_gen(wo), wo.dtype)
+            for name, m in (("paper", (0, 0)), ("variant", (1, 1))):
+                po = _params(C, wo, *m)
+                wso = C.alloc_workspace(po)
+                extra["%d:%s" % (cid, name)] = round(wo.batch / time_reduce(C, po, devo, wso, 3, 1) * 1e3, 2)
+                del wso
+            del devo
+            torch.cuda.empty_cache()
+        line["other_images_per_s"] = extra
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

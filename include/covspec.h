@@ -66,7 +66,7 @@ typedef struct covspec_params {
   int32_t n_tokens;     /* N visual tokens per image, 1 <= N <= 16384                              */
   int32_t d_model;      /* d feature width; multiple of 8 (bf16) or 4 (fp32)                      */
   int32_t n_query;      /* T >= 1 query-keyword embeddings per image (no padding mask)            */
-  int32_t n_heads;      /* H; used by ATTN_SOFTMAX only, which needs d / H == 128                 */
+  int32_t n_heads;      /* H; used by ATTN_SOFTMAX only, which needs (d / H) % 4 == 0            */
   int32_t n_act_layers; /* K in [0, 8]; hidden holds K+1 slices; K = 0 drops the activity term    */
   int32_t dtype;        /* COVSPEC_FP32 / COVSPEC_BF16                                            */
   int32_t rel_mode;     /* COVSPEC_REL_*                                                          */
@@ -122,6 +122,32 @@ int covspec_select(const covspec_params* p, const void* X, const float* s_fused,
 int covspec_reduce(const covspec_params* p, const void* X, const void* hidden, const void* Q,
                    const void* Wq, const void* Wk, int32_t* idx_out, void* tokens_out,
                    void* workspace, size_t workspace_bytes, covspec_stream_t stream);
+
+/*
+ * covspec_reduce with per-stage timing marks, for benchmarks and profilers (the paper gives no
+ * time breakdown of Sec. III-A; this is how one is measured).  `stage_events` is a HOST array of
+ * COVSPEC_NUM_STAGE_EVENTS hipEvent_t handles created by the caller with timing enabled; event i is
+ * recorded on `stream` when stage i begins, the last one when all work has been enqueued.  Stage i
+ * lasted from event i to event i+1.  Same results, arguments and errors as covspec_reduce.
+ */
+enum {
+  COVSPEC_STAGE_QUERY_SIDE = 0,       /* weight transposes, e(q) = q Wq, |e(q)|, folded query matrix    */
+  COVSPEC_STAGE_TOKEN_PROJECTION = 1, /* x Wk for every token (norms, or e(v) itself for ATTN_SOFTMAX)  */
+  COVSPEC_STAGE_RELEVANCE = 2,        /* query/token inner products and the cosine-max / softmax tail    */
+  COVSPEC_STAGE_ACTIVITY = 3,         /* activity score stream pass                                      */
+  COVSPEC_STAGE_FUSE = 4,             /* min-max normalisation and fusion                                */
+  COVSPEC_STAGE_PRESELECT = 5,        /* top-M by fused score                                            */
+  COVSPEC_STAGE_GRAM = 6,             /* Gram matrix of the pre-selected tokens                          */
+  COVSPEC_STAGE_LOWRANK = 7,          /* eigen-solve (ENERGY_TOPK) or greedy picks (GREEDY_RESIDUAL)     */
+  COVSPEC_STAGE_KEEP = 8,             /* subspace energies and top-k, or ordering of the greedy picks    */
+  COVSPEC_STAGE_GATHER = 9,           /* gather of the kept rows                                         */
+  COVSPEC_STAGE_END = 10,
+  COVSPEC_NUM_STAGE_EVENTS = 11
+};
+int covspec_reduce_staged(const covspec_params* p, const void* X, const void* hidden, const void* Q,
+                          const void* Wq, const void* Wk, int32_t* idx_out, void* tokens_out,
+                          void* workspace, size_t workspace_bytes, covspec_stream_t stream,
+                          void* const* stage_events);
 
 /* Static, NUL-terminated description of a status code. */
 const char* covspec_status_string(int status);

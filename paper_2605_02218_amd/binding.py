@@ -21,7 +21,7 @@ LR_ENERGY_TOPK, LR_GREEDY_RESIDUAL = 0, 1
 OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
 
 EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
-           "covspec_reduce", "covspec_status_string")
+           "covspec_reduce", "covspec_reduce_staged", "covspec_status_string")
 
 
 class CovspecParams(ctypes.Structure):
@@ -60,6 +60,8 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_select.argtypes = [pp] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
     lib.covspec_reduce.restype = ctypes.c_int
     lib.covspec_reduce.argtypes = [pp] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
+    lib.covspec_reduce_staged.restype = ctypes.c_int
+    lib.covspec_reduce_staged.argtypes = [pp] + [vp] * 7 + [vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
     lib.covspec_status_string.restype = ctypes.c_char_p
     lib.covspec_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -188,8 +190,18 @@ def select(p: Params, X, s_fused, workspace=None):
     return out
 
 
-def reduce(p: Params, X, hidden, Q, Wq, Wk, workspace=None, idx_out=None, tokens_out=None):
-    """covspec_reduce: returns (idx [B,k] int32, tokens [B,k,d] in X's dtype)."""
+STAGES = ("query_side", "token_projection", "relevance", "activity", "fuse", "preselect", "gram", "lowrank",
+          "keep", "gather")
+NUM_STAGE_EVENTS = len(STAGES) + 1
+JACOBI_MAX_SWEEPS = 14  # launches of the eigen-solve per call = this x (tournament rounds); mirrors eigen.hip
+
+
+def reduce(p: Params, X, hidden, Q, Wq, Wk, workspace=None, idx_out=None, tokens_out=None, stage_events=None):
+    """covspec_reduce: returns (idx [B,k] int32, tokens [B,k,d] in X's dtype).
+
+    With `stage_events` (NUM_STAGE_EVENTS torch.cuda.Event objects, timing enabled, each recorded at least
+    once before so that its handle exists) covspec_reduce_staged is called and the events mark the stages.
+    """
     import torch
     ws = workspace if workspace is not None else alloc_workspace(p, X.device)
     k, _, _ = resolve(p)
@@ -197,8 +209,15 @@ def reduce(p: Params, X, hidden, Q, Wq, Wk, workspace=None, idx_out=None, tokens
     tok = tokens_out if tokens_out is not None else torch.empty(p.batch, k, p.d_model, dtype=X.dtype, device=X.device)
     wp, wb = _ws_args(ws)
     cs = p.c_struct()
-    st = load_library().covspec_reduce(ctypes.byref(cs), _ptr(X), _ptr(hidden), _ptr(Q), _ptr(Wq), _ptr(Wk),
-                                       _ptr(idx), _ptr(tok), wp, wb, _stream())
+    if stage_events is None:
+        st = load_library().covspec_reduce(ctypes.byref(cs), _ptr(X), _ptr(hidden), _ptr(Q), _ptr(Wq), _ptr(Wk),
+                                           _ptr(idx), _ptr(tok), wp, wb, _stream())
+    else:
+        if len(stage_events) != NUM_STAGE_EVENTS:
+            raise ValueError("need %d stage events" % NUM_STAGE_EVENTS)
+        handles = (ctypes.c_void_p * NUM_STAGE_EVENTS)(*[e.cuda_event for e in stage_events])
+        st = load_library().covspec_reduce_staged(ctypes.byref(cs), _ptr(X), _ptr(hidden), _ptr(Q), _ptr(Wq),
+                                                  _ptr(Wk), _ptr(idx), _ptr(tok), wp, wb, _stream(), handles)
     if st != OK:
         raise CovspecError(st, "covspec_reduce")
     return idx, tok

@@ -124,6 +124,16 @@ int make_plan(const covspec_params* p, Plan* pl) {
 template <typename T>
 inline T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
 
+// Optional per-stage timing: records the caller's events on the work stream at stage boundaries.
+struct StageMarks {
+  hipEvent_t* ev = nullptr;
+  hipStream_t st = nullptr;
+  bool ok = true;
+  void mark(int stage) {
+    if (ev && hipEventRecord(ev[stage], st) != hipSuccess) ok = false;
+  }
+};
+
 int check_ws(const Plan& pl, void* ws, size_t bytes) {
   if (!ws || ((uintptr_t)ws & 255u)) return COVSPEC_INVALID_ARG;
   if (bytes < pl.total) return COVSPEC_WORKSPACE_TOO_SMALL;
@@ -135,7 +145,7 @@ int check_ws(const Plan& pl, void* ws, size_t bytes) {
 // bf16 storage: contractions on the bf16 MFMA with fp32 accumulation, fp32 intermediates.
 // fp32 storage: every contraction and intermediate in fp64 (see gemm64.hip).
 int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, const void* Wq, const void* Wk,
-              float* s_query, float* s_act, float* s_fused, void* ws, hipStream_t st) {
+              float* s_query, float* s_act, float* s_fused, void* ws, hipStream_t st, StageMarks& marks) {
   const long B = q.B, N = q.N, d = q.d, T = q.T, BT = B * T, BN = B * N;
   const bool f64 = q.dtype == COVSPEC_FP32;
   const int in_x = f64 ? IN_F32 : IN_BF16;      // storage type of X, Q, W
@@ -151,6 +161,7 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
     return f64 ? launch_gemm64_nt(g, a_mid, b_mid, st) : launch_gemm_nt(g, DT_BF16, st);
   };
 
+  marks.mark(COVSPEC_STAGE_QUERY_SIDE);
   // e(q) = q Wq
   if (Wq) {
     HIPCHK(launch_transpose(Wq, at<void>(ws, q.wqT), q.d, q.d, q.dtype, st));
@@ -184,6 +195,7 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
         HIPCHK(launch_gemm64_nt(g, true, false, st));
         Gq = Graw;
       }
+      marks.mark(COVSPEC_STAGE_TOKEN_PROJECTION);
       GemmArgs n;
       n.A = X; n.B = at<void>(ws, q.wkT); n.C = vn2; n.M = (int)BN; n.N = q.d; n.K = q.d; n.lda = d; n.ldb = d;
       n.ldc = q.nparts; n.epilogue = EPI_ROWNORM2;
@@ -196,9 +208,11 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
       } else {
         Gq = Eq;
       }
+      marks.mark(COVSPEC_STAGE_TOKEN_PROJECTION);
       HIPCHK(launch_row_norm2(X, in_x, vn2, f64, BN, q.d, st));
       nparts = 1;
     }
+    marks.mark(COVSPEC_STAGE_RELEVANCE);
     void* logits = at<void>(ws, q.logits);
     GemmArgs l;
     l.A = X; l.B = Gq; l.C = logits; l.M = q.N; l.N = q.planes * q.T; l.K = q.d; l.lda = d; l.ldb = d; l.ldc = q.planes * T;
@@ -208,6 +222,7 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
     HIPCHK(launch_cosine_max(logits, q.planes, vn2, nparts, qn2, f64, sq, q.B, q.N, q.T, st));
   } else {
     // variant: e(v) materialised, per-head logits, softmax over the visual tokens
+    marks.mark(COVSPEC_STAGE_TOKEN_PROJECTION);
     void* Ev = at<void>(ws, q.Ev);
     if (Wk) {
       GemmArgs g;
@@ -217,6 +232,7 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
     } else {
       HIPCHK(launch_convert(X, in_x, Ev, f64, BN * d, st));
     }
+    marks.mark(COVSPEC_STAGE_RELEVANCE);
     const int dh = q.d / q.H;
     void* S = at<void>(ws, q.S);
     GemmArgs g;
@@ -231,19 +247,23 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
     HIPCHK(launch_softmax_mean(S, f64, stats, sq, q.B, q.H * q.T, q.N, scale, st));
   }
 
+  marks.mark(COVSPEC_STAGE_ACTIVITY);
   if (has_act) HIPCHK(launch_activity(hidden, sa, q.B, q.N, q.d, q.K, q.dtype, st));
+  marks.mark(COVSPEC_STAGE_FUSE);
   HIPCHK(launch_fuse(sq, sa, sf, q.B, q.N, q.lambda, st));
   return COVSPEC_OK;
 }
 
 // ---- selection: paper Sec. III-A.3
 int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_out, float* c_out, int32_t* idx_m_out,
-               int32_t* pick_order_out, float* resid_out, void* ws, hipStream_t st) {
+               int32_t* pick_order_out, float* resid_out, void* ws, hipStream_t st, StageMarks& marks) {
   const long N = q.N, d = q.d;
+  marks.mark(COVSPEC_STAGE_PRESELECT);
   int32_t* idxm = idx_m_out ? idx_m_out : at<int32_t>(ws, q.idxm);
   HIPCHK(launch_select_top(s_fused, q.B, q.N, q.M, nullptr, idxm, st));
 
   // token Gram matrix of the pre-selected rows, fp64, zero-padded to the pitch
+  marks.mark(COVSPEC_STAGE_GRAM);
   double* A = at<double>(ws, q.Awork);
   HIPCHK(launch_fill_zero(A, (size_t)q.B * q.nP * q.nP * 8, st));
   GemmArgs g;
@@ -260,13 +280,17 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
 
   if (q.lr == COVSPEC_LR_ENERGY_TOPK) {
     float* c = c_out ? c_out : at<float>(ws, q.c);
+    marks.mark(COVSPEC_STAGE_LOWRANK);
     HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, at<void>(ws, q.ctl), st));
+    marks.mark(COVSPEC_STAGE_KEEP);
     HIPCHK(launch_subspace_energy(A, q.B, q.M, q.nP, q.r, at<double>(ws, q.lam), c, st));
     HIPCHK(launch_select_top(c, q.B, q.M, q.k, idxm, idx_out, st));
   } else {
     int32_t* order = at<int32_t>(ws, q.order);
     float* resid = resid_out ? resid_out : at<float>(ws, q.resid);
+    marks.mark(COVSPEC_STAGE_LOWRANK);
     HIPCHK(launch_greedy(A, q.B, q.M, q.nP, q.k, at<double>(ws, q.Lt), order, resid, st));
+    marks.mark(COVSPEC_STAGE_KEEP);
     HIPCHK(launch_greedy_finish(order, idxm, q.B, q.M, q.k, idx_out, pick_order_out, st));
   }
   return COVSPEC_OK;
@@ -300,7 +324,8 @@ int covspec_score(const covspec_params* p, const void* X, const void* hidden, co
   if (st != COVSPEC_OK) return st;
   if (!X || !Q) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
-  return run_score(pl, X, hidden, Q, Wq, Wk, s_query, s_act, s_fused, workspace, (hipStream_t)stream);
+  StageMarks none;
+  return run_score(pl, X, hidden, Q, Wq, Wk, s_query, s_act, s_fused, workspace, (hipStream_t)stream, none);
 }
 
 int covspec_select(const covspec_params* p, const void* X, const float* s_fused, int32_t* idx_out, float* c_out,
@@ -311,25 +336,46 @@ int covspec_select(const covspec_params* p, const void* X, const float* s_fused,
   if (st != COVSPEC_OK) return st;
   if (!X || !s_fused || !idx_out) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
-  return run_select(pl, X, s_fused, idx_out, c_out, idx_m_out, pick_order_out, resid_out, workspace, (hipStream_t)stream);
+  StageMarks none;
+  return run_select(pl, X, s_fused, idx_out, c_out, idx_m_out, pick_order_out, resid_out, workspace, (hipStream_t)stream, none);
 }
 
-int covspec_reduce(const covspec_params* p, const void* X, const void* hidden, const void* Q, const void* Wq,
-                   const void* Wk, int32_t* idx_out, void* tokens_out, void* workspace, size_t workspace_bytes,
-                   covspec_stream_t stream) {
+static int reduce_impl(const covspec_params* p, const void* X, const void* hidden, const void* Q, const void* Wq,
+                       const void* Wk, int32_t* idx_out, void* tokens_out, void* workspace, size_t workspace_bytes,
+                       hipStream_t s, StageMarks& marks) {
   Plan pl;
   int st = make_plan(p, &pl);
   if (st != COVSPEC_OK) return st;
   if (!X || !Q || !idx_out || !tokens_out) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
-  hipStream_t s = (hipStream_t)stream;
   float* sf = at<float>(workspace, pl.sf);
-  st = run_score(pl, X, hidden, Q, Wq, Wk, nullptr, nullptr, sf, workspace, s);
+  st = run_score(pl, X, hidden, Q, Wq, Wk, nullptr, nullptr, sf, workspace, s, marks);
   if (st != COVSPEC_OK) return st;
-  st = run_select(pl, X, sf, idx_out, nullptr, nullptr, nullptr, nullptr, workspace, s);
+  st = run_select(pl, X, sf, idx_out, nullptr, nullptr, nullptr, nullptr, workspace, s, marks);
   if (st != COVSPEC_OK) return st;
+  marks.mark(COVSPEC_STAGE_GATHER);
   HIPCHK(launch_gather_rows(X, idx_out, tokens_out, pl.B, pl.N, pl.k, (long)pl.d * pl.esz, s));
-  return COVSPEC_OK;
+  marks.mark(COVSPEC_STAGE_END);
+  return marks.ok ? COVSPEC_OK : COVSPEC_HIP_ERROR;
+}
+
+int covspec_reduce(const covspec_params* p, const void* X, const void* hidden, const void* Q, const void* Wq,
+                   const void* Wk, int32_t* idx_out, void* tokens_out, void* workspace, size_t workspace_bytes,
+                   covspec_stream_t stream) {
+  StageMarks none;
+  return reduce_impl(p, X, hidden, Q, Wq, Wk, idx_out, tokens_out, workspace, workspace_bytes, (hipStream_t)stream, none);
+}
+
+int covspec_reduce_staged(const covspec_params* p, const void* X, const void* hidden, const void* Q, const void* Wq,
+                          const void* Wk, int32_t* idx_out, void* tokens_out, void* workspace, size_t workspace_bytes,
+                          covspec_stream_t stream, void* const* stage_events) {
+  if (!stage_events) return COVSPEC_INVALID_ARG;
+  for (int i = 0; i < COVSPEC_NUM_STAGE_EVENTS; ++i)
+    if (!stage_events[i]) return COVSPEC_INVALID_ARG;
+  StageMarks marks;
+  marks.ev = (hipEvent_t*)stage_events;
+  marks.st = (hipStream_t)stream;
+  return reduce_impl(p, X, hidden, Q, Wq, Wk, idx_out, tokens_out, workspace, workspace_bytes, (hipStream_t)stream, marks);
 }
 
 const char* covspec_status_string(int status) {
