@@ -98,8 +98,8 @@ def roofline_for(w, p_modes, stages, C):
     B, N, d, T, K = w.batch, w.n_tokens, w.d_model, w.n_query, w.n_act_layers
     M, k = w.preselect_m, w.keep_k
     e = 2 if w.dtype == I.BF16 else 4
-    nP = (M + 15) // 16 * 16
-    nb = nP // 8
+    nP = (M + 63) // 64 * 64          # padded order of the eigen-solve
+    nsb = nP // 32                    # 32-row super-blocks; one launch = one tournament round over their pairs
     # stage -> (kernel, bound, peak, unit, algorithmic work per launch, launches per step)
     table = {
         "token_projection": ("gemm_nt_kernel<bf16,rownorm2>" if p_modes[0] == 0 else "gemm_nt_kernel<bf16,store>",
@@ -112,10 +112,10 @@ def roofline_for(w, p_modes, stages, C):
                  "TFLOP/s", 2.0 * B * M * M * d / 1e12, 1),
     }
     if p_modes[1] == 0:
-        # one launch = one tournament round: every pair of 8-row blocks forms a 16x16 Gram block (2*16*16*nP flops)
-        # and applies a 16x16 rotation block (2*16*16*nP flops) on the fp64 MFMA
+        # one launch = one tournament round: every pair of super-blocks forms a 64x64 Gram block (2*64*64*nP flops)
+        # and applies a 64x64 rotation block (2*64*64*nP flops) on the fp64 MFMA
         table["lowrank"] = ("jacobi_round_kernel", "mfma", PEAK["mfma_fp64_TFLOPs"], "TFLOP/s",
-                            B * (nb // 2) * 4.0 * 256 * nP / 1e12, C.JACOBI_MAX_SWEEPS * (nb - 1))
+                            B * (nsb // 2) * 4.0 * 4096 * nP / 1e12, C.JACOBI_MAX_SWEEPS * (nsb - 1))
     else:
         table["lowrank"] = ("greedy_kernel", "alu", 78.6, "TFLOP/s", 1.0 * B * M * k * k / 1e12, 1)
     dom = max((s for s in stages if s in table), key=lambda s: stages[s])

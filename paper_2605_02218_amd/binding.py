@@ -193,7 +193,7 @@ def select(p: Params, X, s_fused, workspace=None):
 STAGES = ("query_side", "token_projection", "relevance", "activity", "fuse", "preselect", "gram", "lowrank",
           "keep", "gather")
 NUM_STAGE_EVENTS = len(STAGES) + 1
-JACOBI_MAX_SWEEPS = 14  # launches of the eigen-solve per call = this x (tournament rounds); mirrors eigen.hip
+JACOBI_MAX_SWEEPS = 30  # launches of the eigen-solve per call = this x (tournament rounds); mirrors eigen.hip
 
 
 def reduce(p: Params, X, hidden, Q, Wq, Wk, workspace=None, idx_out=None, tokens_out=None, stage_events=None):

@@ -23,7 +23,7 @@ struct Plan {
   int esz;        // bytes per stored element
   int planes;     // bf16: 3 split planes of the folded query matrix, fp32: 1
   int nparts;     // per-token partial sums of |e(v)|^2 written by the projection GEMM
-  int nP;         // Gram pitch, multiple of 16
+  int nP;         // Gram pitch (padded order of the eigen-solve)
   // workspace offsets (bytes)
   size_t wqT, wkT, Eq, qn2, Eq3, G3raw, G3, vn2p, logits, Ev, S, stats, sq, sa, sf;
   size_t idxm, Awork, ctl, lam, c, Lt, order, resid;
@@ -76,7 +76,7 @@ int make_plan(const covspec_params* p, Plan* pl) {
   q.planes = p->dtype == COVSPEC_BF16 ? 3 : 1;
   q.nparts = p->dtype == COVSPEC_BF16 ? gemm_tiles_n(q.d) : gemm64_tiles_n(q.d);
   const size_t fsz = p->dtype == COVSPEC_BF16 ? 4 : 8;  // bytes per intermediate value
-  q.nP = (M + 15) / 16 * 16;
+  q.nP = jacobi_pitch(M);
 
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -281,7 +281,7 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
   if (q.lr == COVSPEC_LR_ENERGY_TOPK) {
     float* c = c_out ? c_out : at<float>(ws, q.c);
     marks.mark(COVSPEC_STAGE_LOWRANK);
-    HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, at<void>(ws, q.ctl), st));
+    HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), st));
     marks.mark(COVSPEC_STAGE_KEEP);
     HIPCHK(launch_subspace_energy(A, q.B, q.M, q.nP, q.r, at<double>(ws, q.lam), c, st));
     HIPCHK(launch_select_top(c, q.B, q.M, q.k, idxm, idx_out, st));

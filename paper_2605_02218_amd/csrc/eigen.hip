@@ -8,13 +8,17 @@
 // rows of J^T G become mutually orthogonal exactly when J holds the eigenvectors.  Then
 // |row k| = lambda_k and c_i = sum over the r longest rows of A_ki^2 / |row k|.
 //
-// Parallel form: rows are grouped in blocks of 8; a round-robin tournament pairs the
-// blocks, one launch per tournament round, one wave per block pair.  The wave
-//   1. forms the 16x16 Gram H = P P^T of its 16 rows with v_mfma_f64_16x16x4 (the A and
-//      B operand of that product are the same registers),
-//   2. runs one cyclic sweep of two-sided Jacobi rotations on H in LDS, accumulating the
-//      16x16 orthogonal W,
+// Parallel form: rows are grouped in super-blocks of 32; a round-robin tournament pairs the
+// super-blocks, one launch per tournament round, one 256-thread workgroup per pair.  The workgroup
+//   1. forms the 64x64 Gram H = P P^T of its 64 rows with v_mfma_f64_16x16x4 (waves split the
+//      columns, partial tiles are summed in LDS; the A and B operand of a diagonal tile are the
+//      same registers),
+//   2. runs two-sided Jacobi rotations on H in LDS, accumulating the 64x64 orthogonal W: every
+//      cross pair (one row from each super-block) once, or - in the first round of a sweep, which
+//      also has to orthogonalise the rows inside a super-block - every pair once,
 //   3. applies P <- W^T P with the same MFMA.
+// So the 64 x n panel crosses HBM three times per 1024 (or 2016) rotations, and all rotation
+// arithmetic runs on LDS-resident data.
 // fp64 MFMA layouts (checked on the device): operand lane l holds (row|col = l%16,
 // k = l/16); result lane l, register v holds (row 4v + l/16, col l%16).
 #include "common.h"
@@ -25,15 +29,22 @@ namespace covspec {
 namespace {
 
 struct JacobiCtl {
-  unsigned long long maxoff;  // bits of the largest |cos| between two rows seen in the current sweep
+  unsigned long long maxoff;  // bits of the largest admixture weight seen in the current sweep (see below)
   int done;
   int sweeps;
   double floor2;              // rows with squared norm below this are treated as zero
+  double long2;               // squared length of the r-th longest row after the previous sweep
 };
 
+// Only the r longest rows enter the energies, and they settle many sweeps before the short rows (the
+// tail of a graded spectrum) become orthogonal among themselves.  Leaving a pair (p, q) unrotated mixes
+// the direction of the longer row with relative weight |cos(p,q)| * (shorter/longer)^2 (the rotation
+// angle is ~ gamma / (alpha - beta), and the admixture carries the shorter row's length), so a sweep
+// counts as converged when that weight is below kConvTol for every visited pair that holds one of the r
+// longest rows; which rows those are is re-measured after every sweep.
 constexpr double kRotEps = 1e-15;   // rotations below this relative size are skipped
-constexpr double kConvTol = 1e-9;   // sweep-level convergence: every visited pair below this
-constexpr int kMaxSweeps = 14;
+constexpr double kConvTol = 3e-8;
+constexpr int kMaxSweeps = 30;
 
 __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restrict__ A, int n, int nP, JacobiCtl* ctl) {
   __shared__ double red[4];
@@ -51,17 +62,39 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restri
     ctl[b].sweeps = 0;
     double f = 1e-13 * t;
     ctl[b].floor2 = f * f;
+    ctl[b].long2 = 0.0;       // first sweep: every row counts
   }
 }
 
-__global__ void jacobi_check_kernel(JacobiCtl* ctl, int B) {
-  int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  if (!ctl[b].done) {
+// End of a sweep, one workgroup per image: decide convergence, then re-measure which rows are long.
+__global__ __launch_bounds__(256) void jacobi_check_kernel(const double* __restrict__ A, int n, int nP, int r, JacobiCtl* ctl) {
+  __shared__ double len2[4096];
+  const int b = blockIdx.x;
+  if (ctl[b].done) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const double* Ab = A + (long)b * nP * nP;
+  for (int k = w; k < n; k += 4) {
+    const double* row = Ab + (long)k * nP;
+    double s = 0.0;
+    for (int j = lane; j < nP; j += 64) s = fma(row[j], row[j], s);
+    s = wave_sum(s);
+    if (lane == 0) len2[k] = s;
+  }
+  __syncthreads();
+  for (int k = threadIdx.x; k < n; k += 256) {
+    const double v = len2[k];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      const double u = len2[j];
+      rank += (u > v || (u == v && j < k)) ? 1 : 0;
+    }
+    if (rank == r - 1) ctl[b].long2 = v * (1.0 - 1e-12);
+  }
+  if (threadIdx.x == 0) {
     ctl[b].sweeps += 1;
     if (__longlong_as_double((long long)ctl[b].maxoff) < kConvTol) ctl[b].done = 1;
+    ctl[b].maxoff = 0ull;
   }
-  ctl[b].maxoff = 0ull;
 }
 
 // circle-method tournament over `np` (even) players: pair `m` of round `rd`
@@ -70,51 +103,92 @@ __device__ __forceinline__ void tournament_pair(int np, int rd, int m, int& p, i
   else { p = (rd + m) % (np - 1); q = (rd - m + (np - 1)) % (np - 1); }
 }
 
-__global__ __launch_bounds__(64) void jacobi_round_kernel(double* __restrict__ A, int nP, int nb, int round, JacobiCtl* ctl) {
-  __shared__ double Hs[16][17];
-  __shared__ double Ws[16][17];
-  __shared__ double cs_c[8], cs_s[8];
-  __shared__ int any_rot;
+constexpr int SB = 32;        // rows per super-block
+constexpr int PR = 2 * SB;    // rows per workgroup
+constexpr int HP = PR + 1;    // LDS pitch (doubles)
 
-  const int npairs = nb >> 1;
+__global__ __launch_bounds__(256, 2) void jacobi_round_kernel(double* __restrict__ A, int nP, int nsb, int round, JacobiCtl* ctl) {
+  __shared__ double Hs[PR * HP];
+  __shared__ double Ws[PR * HP];
+  __shared__ double cs_c[32], cs_s[32];
+  __shared__ int any_rot;
+  __shared__ double off_w[4];
+
+  const int npairs = nsb >> 1;
   const int b = blockIdx.x / npairs, pr = blockIdx.x - b * npairs;
   if (ctl[b].done) return;
   int I, J;
-  tournament_pair(nb, round, pr, I, J);
-  const int l = threadIdx.x, i16 = l & 15, kq = l >> 4;
+  tournament_pair(nsb, round, pr, I, J);
+  const int tid = threadIdx.x, l = tid & 63, w = tid >> 6, i16 = l & 15, kq = l >> 4;
   double* Ab = A + (long)b * nP * nP;
-  auto grow = [&](int i) -> long { return (i < 8) ? (long)I * 8 + i : (long)J * 8 + (i - 8); };
+  auto grow = [&](int i) -> long { return (i < SB) ? (long)I * SB + i : (long)J * SB + (i - SB); };
+  const int nchunks = nP >> 4;
 
-  // ---- 1. H = P P^T
+  // ---- 1. H = P P^T : wave w takes column chunks w, w+4, ...; upper tiles only
+  for (int e = tid; e < PR * HP; e += 256) { Hs[e] = 0.0; Ws[e] = 0.0; }
+  if (tid == 0) any_rot = 0;
   {
-    const double* rp = Ab + grow(i16) * nP + 4 * kq;
-    f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
-    for (int c0 = 0; c0 < nP; c0 += 16) {
-      f64x4_t a = *(const f64x4_t*)(rp + c0);
+    f64x4_t acc[10];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[t], a[t], acc, 0, 0, 0);
+    for (int t = 0; t < 10; ++t) acc[t] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+    const double* rp[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) rp[x] = Ab + grow(16 * x + i16) * nP + 4 * kq;
+    for (int c = w; c < nchunks; c += 4) {
+      f64x4_t f[4];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) f[x] = *(const f64x4_t*)(rp[x] + 16 * c);
+      int t = 0;
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int y = x; y < 4; ++y) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(f[x][k], f[y][k], acc[t], 0, 0, 0);
+          ++t;
+        }
     }
+    __syncthreads();  // zero fill visible
+    for (int ww = 0; ww < 4; ++ww) {
+      if (w == ww) {
+        int t = 0;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) Hs[4 * v + kq][i16] = acc[v];
-    for (int e = l; e < 256; e += 64) Ws[e >> 4][e & 15] = ((e >> 4) == (e & 15)) ? 1.0 : 0.0;
-    if (l == 0) any_rot = 0;
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+          for (int y = x; y < 4; ++y) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Hs[(16 * x + 4 * v + kq) * HP + 16 * y + i16] += acc[t][v];
+            ++t;
+          }
+      }
+      __syncthreads();
+    }
+    // mirror the strictly-upper tiles, identity into W
+    for (int e = tid; e < PR * PR; e += 256) {
+      const int r = e >> 6, c = e & 63;
+      if ((r >> 4) > (c >> 4)) Hs[r * HP + c] = Hs[c * HP + r];
+      Ws[r * HP + c] = (r == c) ? 1.0 : 0.0;
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
-  // ---- 2. one cyclic sweep of rotations on H, W <- W J
-  const double floor2 = ctl[b].floor2;
+  // ---- 2. rotations on H (two-sided), W <- W J
+  const double floor2 = ctl[b].floor2, long2 = ctl[b].long2;
+  const bool full = (round == 0);
+  const int nrounds = full ? PR - 1 : SB;
   double offmax = 0.0;
-  const int m = l >> 3, u = l & 7;
-  for (int rd = 0; rd < 15; ++rd) {
+  const int m = tid >> 3, u = tid & 7;   // pair m, slice u of 8 elements
+  for (int rd = 0; rd < nrounds; ++rd) {
     int p, q;
-    tournament_pair(16, rd, m, p, q);
+    if (full) tournament_pair(PR, rd, m, p, q);
+    else { p = m; q = SB + ((m + rd) & (SB - 1)); }
     if (u == 0) {
-      const double al = Hs[p][p], be = Hs[q][q], ga = Hs[p][q];
+      const double al = Hs[p * HP + p], be = Hs[q * HP + q], ga = Hs[p * HP + q];
       double c = 1.0, s = 0.0;
       if (al > floor2 && be > floor2) {
         const double lim = sqrt(al * be);
         const double aga = fabs(ga);
-        offmax = fmax(offmax, aga / lim);
+        if (fmax(al, be) >= long2) offmax = fmax(offmax, (aga / lim) * (fmin(al, be) / fmax(al, be)));
         if (aga > kRotEps * lim) {
           const double zeta = (be - al) / (2.0 * ga);
           const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
@@ -128,48 +202,66 @@ __global__ __launch_bounds__(64) void jacobi_round_kernel(double* __restrict__ A
     }
     __syncthreads();
     const double c = cs_c[m], s = cs_s[m];
+    if (s != 0.0) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {  // rows p,q of H:  J^T H
-      const int jj = u + 8 * h;
-      const double hp = Hs[p][jj], hq = Hs[q][jj];
-      Hs[p][jj] = c * hp - s * hq;
-      Hs[q][jj] = s * hp + c * hq;
+      for (int h = 0; h < 8; ++h) {  // rows p,q of H:  J^T H
+        const int jj = u + 8 * h;
+        const double hp = Hs[p * HP + jj], hq = Hs[q * HP + jj];
+        Hs[p * HP + jj] = c * hp - s * hq;
+        Hs[q * HP + jj] = s * hp + c * hq;
+      }
     }
     __syncthreads();
+    if (s != 0.0) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {  // columns p,q of H and W:  (.) J
-      const int ii = u + 8 * h;
-      const double hp = Hs[ii][p], hq = Hs[ii][q];
-      Hs[ii][p] = c * hp - s * hq;
-      Hs[ii][q] = s * hp + c * hq;
-      const double wp = Ws[ii][p], wq = Ws[ii][q];
-      Ws[ii][p] = c * wp - s * wq;
-      Ws[ii][q] = s * wp + c * wq;
+      for (int h = 0; h < 8; ++h) {  // columns p,q of H and W:  (.) J
+        const int ii = u + 8 * h;
+        const double hp = Hs[ii * HP + p], hq = Hs[ii * HP + q];
+        Hs[ii * HP + p] = c * hp - s * hq;
+        Hs[ii * HP + q] = s * hp + c * hq;
+        const double wp = Ws[ii * HP + p], wq = Ws[ii * HP + q];
+        Ws[ii * HP + p] = c * wp - s * wq;
+        Ws[ii * HP + q] = s * wp + c * wq;
+      }
     }
     __syncthreads();
   }
 
   // ---- 3. P <- W^T P  (skipped when every rotation of this pair was the identity)
   if (any_rot) {
-    double wa[4];
+    double wa[4][16];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) wa[t] = Ws[4 * t + kq][i16];
-    long rload[4], rstore[4];
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) { rload[t] = grow(4 * t + kq) * nP + i16; rstore[t] = rload[t]; }
-    for (int c0 = 0; c0 < nP; c0 += 16) {
-      double pb[4];
+      for (int t = 0; t < 16; ++t) wa[a][t] = Ws[(4 * t + kq) * HP + 16 * a + i16];
+    long roff[16];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) pb[t] = Ab[rload[t] + c0];
-      f64x4_t d = {0.0, 0.0, 0.0, 0.0};
+    for (int t = 0; t < 16; ++t) roff[t] = grow(4 * t + kq) * nP + i16;
+    for (int c = w; c < nchunks; c += 4) {
+      double pb[16];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) d = __builtin_amdgcn_mfma_f64_16x16x4f64(wa[t], pb[t], d, 0, 0, 0);
+      for (int t = 0; t < 16; ++t) pb[t] = Ab[roff[t] + 16 * c];
+      f64x4_t d[4];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) Ab[rstore[v] + c0] = d[v];
+      for (int a = 0; a < 4; ++a) d[a] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int t = 0; t < 16; ++t)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) d[a] = __builtin_amdgcn_mfma_f64_16x16x4f64(wa[a][t], pb[t], d[a], 0, 0, 0);
+      // result tile a, register v -> row 16a + 4v + kq = (4*(4a+v) + kq): the load offset of k-step 4a+v
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Ab[roff[4 * a + v] + 16 * c] = d[a][v];
     }
   }
   offmax = wave_max(offmax);
-  if (l == 0 && offmax > 0.0) atomicMax(&ctl[b].maxoff, (unsigned long long)__double_as_longlong(offmax));
+  if (l == 0) off_w[w] = offmax;
+  __syncthreads();
+  if (tid == 0) {
+    const double o = fmax(fmax(off_w[0], off_w[1]), fmax(off_w[2], off_w[3]));
+    if (o > 0.0) atomicMax(&ctl[b].maxoff, (unsigned long long)__double_as_longlong(o));
+  }
 }
 
 // lam[b*nP + k] = |row k of A[b]|, one wave per row
@@ -220,18 +312,18 @@ __global__ __launch_bounds__(256) void energy_kernel(const double* __restrict__ 
 }  // namespace
 
 size_t jacobi_ctl_bytes(int B) { return sizeof(JacobiCtl) * (size_t)B; }
+int jacobi_pitch(int n) { return (n + PR - 1) / PR * PR; }
+int jacobi_launches(int n) { return kMaxSweeps * (jacobi_pitch(n) / SB - 1); }
 
-hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, void* ctl_, hipStream_t st) {
-  if (nP % 16 != 0 || n > nP) return hipErrorInvalidValue;
+hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl_, hipStream_t st) {
+  if (nP % 64 != 0 || n > nP || n > 4096 || r < 1 || r > n) return hipErrorInvalidValue;
   JacobiCtl* ctl = (JacobiCtl*)ctl_;
-  const int nb = nP / 8;  // even, since nP % 16 == 0
+  const int nsb = nP / SB;  // even, since nP % 64 == 0
   hipLaunchKernelGGL(jacobi_init_kernel, dim3(B), dim3(256), 0, st, A, n, nP, ctl);
-  if (nb >= 2) {
-    for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
-      for (int round = 0; round < nb - 1; ++round)
-        hipLaunchKernelGGL(jacobi_round_kernel, dim3((unsigned)(B * (nb / 2))), dim3(64), 0, st, A, nP, nb, round, ctl);
-      hipLaunchKernelGGL(jacobi_check_kernel, dim3((B + 63) / 64), dim3(64), 0, st, ctl, B);
-    }
+  for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
+    for (int round = 0; round < nsb - 1; ++round)
+      hipLaunchKernelGGL(jacobi_round_kernel, dim3((unsigned)(B * (nsb / 2))), dim3(256), 0, st, A, nP, nsb, round, ctl);
+    hipLaunchKernelGGL(jacobi_check_kernel, dim3(B), dim3(256), 0, st, A, n, nP, r, ctl);
   }
   return hipGetLastError();
 }
