@@ -281,7 +281,7 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
   if (q.lr == COVSPEC_LR_ENERGY_TOPK) {
     float* c = c_out ? c_out : at<float>(ws, q.c);
     marks.mark(COVSPEC_STAGE_LOWRANK);
-    HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), st));
+    HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), st));
     marks.mark(COVSPEC_STAGE_KEEP);
     HIPCHK(launch_subspace_energy(A, q.B, q.M, q.nP, q.r, at<double>(ws, q.lam), c, st));
     HIPCHK(launch_select_top(c, q.B, q.M, q.k, idxm, idx_out, st));

@@ -97,11 +97,11 @@ hipError_t launch_select_top(const float* scores, int B, int n, int m, const int
 
 // ---------------------------------------------------------------- eigen.hip
 // One-sided block Jacobi on the rows of the symmetric PSD matrices A[b] (fp64, pitch nP = jacobi_pitch(n),
-// rows/cols >= n zero).  On return the r longest rows k of A[b] are lambda_k v_k^T (shorter rows only span the rest).  `ctl` is scratch of jacobi_ctl_bytes(B).
+// rows/cols >= n zero).  On return the r longest rows k of A[b] are lambda_k v_k^T (shorter rows only span the rest).  `ctl` is scratch of jacobi_ctl_bytes(B), `len2` scratch of B*nP doubles.
 size_t jacobi_ctl_bytes(int B);
 int jacobi_pitch(int n);      // row pitch (and padded order) the solver needs: n rounded up to 64
 int jacobi_launches(int n);   // tournament-round launches per solve
-hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl, hipStream_t stream);
+hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl, double* len2, hipStream_t stream);
 // Subspace energy (paper energy equation) from the converged rows: c[b,i] = sum over the r rows with the
 // largest norm of A[k][i]^2 / |row k|.   `lam` is scratch of B*nP doubles.
 hipError_t launch_subspace_energy(const double* A, int B, int n, int nP, int r, double* lam, float* c,
