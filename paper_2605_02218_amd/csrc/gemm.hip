@@ -5,8 +5,9 @@
 // inner products behind the cosine score, and the token Gram matrix of the
 // pre-selected tokens behind the rank-r SVD (paper Sec. III-A.3).
 //
-// Shape: 256 threads = 4 waves in a 2x2 grid, block tile 128x128, wave tile
-// 64x64 = 2x2 MFMA 32x32 tiles, k-tile of 128 bytes per row.  Operand tiles go
+// Shape: 256 threads = 4 waves in a 2x2 grid; block tile 128x128 (wave tile 64x64 =
+// 2x2 MFMA 32x32 tiles) or, for large problems, 256x256 (wave tile 128x128 = 4x4
+// MFMA tiles, 256 accumulator registers); k-tile of 128 bytes per row.  Operand tiles go
 // global -> registers -> LDS (double buffered, one barrier per k-tile); LDS rows
 // are 128 B with the 16-byte chunk index XOR-swizzled by (row & 7), so both the
 // 16-byte stores and the MFMA fragment reads are bank-conflict free.
@@ -14,6 +15,8 @@
 //   fp32: v_mfma_f32_32x32x2_f32; a lane reads two consecutive k and feeds them
 //         to two MFMAs (the contraction order is permuted identically for A and B).
 // Result layout of both: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -21,7 +24,7 @@ namespace covspec {
 
 namespace {
 
-constexpr int BM = 128, BN = 128, ROWB = 128;  // tile rows / cols, bytes per LDS row
+constexpr int ROWB = 128;  // bytes per LDS row (one k-tile of a tile row)
 constexpr int THREADS = 256;
 
 template <typename In> struct Tr;
@@ -53,192 +56,424 @@ __device__ __forceinline__ TileMap map_block(int bid, int nblocks, int tiles_m, 
   return t;
 }
 
-template <typename In, int EPI, bool GATHER>
+// TW = MFMA 32x32 tiles per wave and dimension: block tile (64*TW)^2, wave tile (32*TW)^2.
+template <typename In, int EPI, bool GATHER, int TW>
 __global__ __launch_bounds__(THREADS) void gemm_nt_kernel(GemmArgs g, int tiles_m, int tiles_n) {
   constexpr int BK = Tr<In>::BK;
   constexpr int ESZ = Tr<In>::ESZ;
-  constexpr int EPC = 16 / ESZ;  // elements per 16-byte chunk
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][BM * ROWB];  // [stage][A|B]
+  constexpr int EPC = 16 / ESZ;       // elements per 16-byte chunk
+  constexpr int BT = 64 * TW;         // block tile rows = cols
+  constexpr int WT = 32 * TW;         // wave tile rows = cols
+  constexpr int NS = BT / 32;         // 16-byte load slots per thread and operand
+  constexpr int STAGE = 2 * BT * ROWB;  // bytes per stage: A tile then B tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][A|B][BT*ROWB]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const TileMap tmap = map_block(blockIdx.x, gridDim.x, tiles_m, tiles_n);
-  const int row0 = tmap.tm * BM, col0 = tmap.tn * BN;
+  const int row0 = tmap.tm * BT, col0 = tmap.tn * BT;
 
   const int bo = tmap.b / g.batch_inner, bi = tmap.b - bo * g.batch_inner;
   const In* __restrict__ A = (const In*)g.A + (long)bo * g.strideA + (long)bi * g.strideA2;
   const In* __restrict__ B = (const In*)g.B + (long)bo * g.strideB + (long)bi * g.strideB2;
   const long coff = (long)bo * g.strideC + (long)bi * g.strideC2;
 
-  // this thread's four (row, chunk) slots of each operand tile
+  // this thread's (row, chunk) slots of each operand tile: rows lrow + 32*s, chunk lchunk.  Without a
+  // gather list the slots are a fixed stride apart, so one base offset per operand is kept.
   const int lchunk = tid & 7;
-  const int lrow = tid >> 3;  // + 32*s
-  long aoff[4], boff[4];
-  bool aok[4], bok[4];
+  const int lrow = tid >> 3;
+  long aoff[GATHER ? NS : 1], boff[GATHER ? NS : 1];
+  if (GATHER) {
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    int ra = row0 + lrow + 32 * s, rb = col0 + lrow + 32 * s;
-    aok[s] = ra < g.M;
-    bok[s] = rb < g.N;
-    long ia = ra, ib = rb;
-    if (GATHER) {
-      if (g.gatherA && aok[s]) ia = g.gatherA[(long)bo * g.gstrideA + ra];
-      if (g.gatherB && bok[s]) ib = g.gatherB[(long)bo * g.gstrideB + rb];
+    for (int s = 0; s < NS; ++s) {
+      const int ra = row0 + lrow + 32 * s, rb = col0 + lrow + 32 * s;
+      long ia = ra, ib = rb;
+      if (g.gatherA && ra < g.M) ia = g.gatherA[(long)bo * g.gstrideA + ra];
+      if (g.gatherB && rb < g.N) ib = g.gatherB[(long)bo * g.gstrideB + rb];
+      aoff[GATHER ? s : 0] = ia * g.lda;
+      boff[GATHER ? s : 0] = ib * g.ldb;
     }
-    aoff[s] = ia * g.lda;
-    boff[s] = ib * g.ldb;
+  } else {
+    aoff[0] = (long)(row0 + lrow) * g.lda;
+    boff[0] = (long)(col0 + lrow) * g.ldb;
   }
+  const long astep = 32 * g.lda, bstep = 32 * g.ldb;
+  const int arows = g.M - row0 - lrow, brows = g.N - col0 - lrow;   // slot s is in range iff 32*s < rows
 
-  u32x4_t ra_[4], rb_[4];
-  auto gload = [&](int kt) {
+  // global -> registers -> LDS staging of the next k-tile (a second register set, to give loads two
+  // k-tiles to land, was measured slower: the extra registers and moves cost more than the latency hid)
+  u32x4_t ra0[NS], rb0[NS];
+  auto gload = [&](int kt, u32x4_t (&ra_)[NS], u32x4_t (&rb_)[NS]) {
     const int k = kt * BK + lchunk * EPC;
     const bool kok = k < g.K;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
+    for (int s = 0; s < NS; ++s) {
       u32x4_t z = {0u, 0u, 0u, 0u};
-      ra_[s] = (aok[s] && kok) ? *(const u32x4_t*)(A + aoff[s] + k) : z;
-      rb_[s] = (bok[s] && kok) ? *(const u32x4_t*)(B + boff[s] + k) : z;
+      const long ao = GATHER ? aoff[GATHER ? s : 0] : aoff[0] + s * astep;
+      const long bo_ = GATHER ? boff[GATHER ? s : 0] : boff[0] + s * bstep;
+      ra_[s] = (32 * s < arows && kok) ? *(const u32x4_t*)(A + ao + k) : z;
+      rb_[s] = (32 * s < brows && kok) ? *(const u32x4_t*)(B + bo_ + k) : z;
     }
   };
-  auto lstore = [&](int st) {
+  auto lstore = [&](int st, const u32x4_t (&ra_)[NS], const u32x4_t (&rb_)[NS]) {
+    unsigned char* sa = smem + st * STAGE;
+    unsigned char* sb = sa + BT * ROWB;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
+    for (int s = 0; s < NS; ++s) {
       int r = lrow + 32 * s;
-      *(u32x4_t*)(&smem[st][0][swz(r, lchunk)]) = ra_[s];
-      *(u32x4_t*)(&smem[st][1][swz(r, lchunk)]) = rb_[s];
+      *(u32x4_t*)(sa + swz(r, lchunk)) = ra_[s];
+      *(u32x4_t*)(sb + swz(r, lchunk)) = rb_[s];
     }
   };
 
-  f32x16_t acc[2][2];
+  f32x16_t acc[TW][TW];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TW; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TW; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  double acc64[(EPI == EPI_STORE_F64) ? 64 : 1];
+  double acc64[(EPI == EPI_STORE_F64) ? TW * TW * 16 : 1];
   if (EPI == EPI_STORE_F64) {
 #pragma unroll
-    for (int v = 0; v < 64; ++v) acc64[v] = 0.0;
+    for (int v = 0; v < TW * TW * 16; ++v) acc64[v] = 0.0;
   }
 
   const int nk = (g.K + BK - 1) / BK;
   const int li = lane & 31, lh = lane >> 5;
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int st = kt & 1;
-    if (kt + 1 < nk) gload(kt + 1);
-    const unsigned char* sa = smem[st][0];
-    const unsigned char* sb = smem[st][1];
+
+  auto compute = [&](int st) {
+    const unsigned char* sa = smem + st * STAGE;
+    const unsigned char* sb = sa + BT * ROWB;
     if constexpr (ESZ == 2) {
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        bf16x8_t af[2], bfr[2];
+        bf16x8_t af[TW], bfr[TW];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          int r = wm * 64 + i * 32 + li;
+        for (int i = 0; i < TW; ++i) {
+          int r = wm * WT + i * 32 + li;
           u32x4_t t = *(const u32x4_t*)(sa + swz(r, 2 * ks + lh));
           af[i] = __builtin_bit_cast(bf16x8_t, t);
-          int c = wn * 64 + i * 32 + li;
+          int c = wn * WT + i * 32 + li;
           u32x4_t u = *(const u32x4_t*)(sb + swz(c, 2 * ks + lh));
           bfr[i] = __builtin_bit_cast(bf16x8_t, u);
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TW; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < TW; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
       }
     } else {
 #pragma unroll
       for (int ch = 0; ch < 8; ++ch) {
-        float2 af[2], bfr[2];
+        float2 af[TW], bfr[TW];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          int r = wm * 64 + i * 32 + li;
+        for (int i = 0; i < TW; ++i) {
+          int r = wm * WT + i * 32 + li;
           af[i] = *(const float2*)(sa + swz(r, ch) + 8 * lh);
-          int c = wn * 64 + i * 32 + li;
+          int c = wn * WT + i * 32 + li;
           bfr[i] = *(const float2*)(sb + swz(c, ch) + 8 * lh);
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TW; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
+          for (int j = 0; j < TW; ++j) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].x, bfr[j].x, acc[i][j], 0, 0, 0);
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].y, bfr[j].y, acc[i][j], 0, 0, 0);
           }
       }
     }
+  };
+  auto flush64 = [&](int kt) {
     if (EPI == EPI_STORE_F64) {
       // flush the fp32 partial sums into fp64 every 256 contraction steps
       constexpr int FLUSH = 256 / BK;
       if ((kt % FLUSH) == FLUSH - 1 || kt + 1 == nk) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TW; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < TW; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-              acc64[(i * 2 + j) * 16 + v] += (double)acc[i][j][v];
+              acc64[(i * TW + j) * 16 + v] += (double)acc[i][j][v];
               acc[i][j][v] = 0.f;
             }
       }
     }
-    if (kt + 1 < nk) lstore(st ^ 1);
+  };
+
+  gload(0, ra0, rb0);
+  lstore(0, ra0, rb0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int st = kt & 1;
+    if (kt + 1 < nk) gload(kt + 1, ra0, rb0);   // lands while this k-tile feeds the MFMAs
+    compute(st);
+    flush64(kt);
+    if (kt + 1 < nk) lstore(st ^ 1, ra0, rb0);
     __syncthreads();
   }
 
   // ---- epilogue ----
   if (EPI == EPI_STORE_F32 || EPI == EPI_STORE_F64) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TW; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TW; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          int r = row0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-          int c = col0 + wn * 64 + j * 32 + li;
+          int r = row0 + wm * WT + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+          int c = col0 + wn * WT + j * 32 + li;
           if (r < g.M && c < g.N) {
             long o = coff + (long)r * g.ldc + c;
             if (EPI == EPI_STORE_F32) ((float*)g.C)[o] = acc[i][j][v];
-            else ((double*)g.C)[o] = acc64[(i * 2 + j) * 16 + v];
+            else ((double*)g.C)[o] = acc64[(i * TW + j) * 16 + v];
           }
         }
   } else if (EPI == EPI_ROWNORM2) {
-    // sum over this tile's columns of C^2, one value per row; columns beyond N hold exact zeros
-    float* red = (float*)&smem[0][0][0];  // [2][128]
+    // per row: sum over 128 output columns of C^2 (columns beyond N hold exact zeros).  A wave covers WT
+    // columns: with TW = 2 the two wave columns are combined through LDS, with TW = 4 each wave column is
+    // one 128-column part of its own.
+    float* red = (float*)smem;  // [2][BT]
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TW; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float s = acc[i][0][v] * acc[i][0][v] + acc[i][1][v] * acc[i][1][v];
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < TW; ++j) s = fmaf(acc[i][j][v], acc[i][j][v], s);
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-        if (li == 0) red[wn * 128 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3)] = s;
+        if (li == 0) red[wn * BT + wm * WT + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3)] = s;
       }
     __syncthreads();
-    if (tid < 128) {
-      int r = row0 + tid;
-      if (r < g.M) ((float*)g.C)[coff + (long)r * g.ldc + tmap.tn] = red[tid] + red[128 + tid];
+    for (int t = tid; t < BT; t += THREADS) {
+      int r = row0 + t;
+      if (r < g.M) {
+        float* out = (float*)g.C + coff + (long)r * g.ldc;
+        if (TW == 2) out[tmap.tn] = red[t] + red[BT + t];
+        else {
+          out[2 * tmap.tn] = red[t];
+          if ((2 * tmap.tn + 1) * 128 < g.N) out[2 * tmap.tn + 1] = red[BT + t];
+        }
+      }
     }
   }
 }
 
-template <typename In, int EPI>
-hipError_t launch_t(const GemmArgs& g, hipStream_t stream) {
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+// ---- large bf16 problems: 256x256 block tile, k-tile 32, four LDS stages filled by direct
+// global -> LDS loads (global_load_lds_dwordx4: lane l of a wave deposits its 16 bytes at base + 16*l),
+// so two k-tiles are in flight while one feeds the MFMAs and no register staging is needed; the MFMA
+// fragments of the next k-tile are read from LDS while the current one is multiplied.  (A 512-thread
+// variant with two waves per SIMD measured the same: at ~1.0 PFLOP/s the kernel runs at ~1.9 GHz under
+// the power limit and is co-limited by the L2 -> LDS path, 13 TB/s for 256x256 tiles.)
+// LDS rows are 64 bytes (4 chunks); chunk index XORed with bit2(row) | (bit1(row)^bit3(row))<<1, which
+// keeps every aligned group of 8 and of 16 consecutive rows on distinct banks for 16-byte reads.
+// Rows beyond M / N are clamped to the last valid row when loading and masked in the epilogue;
+// requires K % 64 == 0 (an even number of k-tiles).
+__device__ __forceinline__ int swz64(int row, int chunk) {
+  const int f = ((row >> 2) & 1) | ((((row >> 1) ^ (row >> 3)) & 1) << 1);
+  return row * 64 + ((chunk ^ f) << 4);
+}
+
+template <int EPI>
+__global__ __launch_bounds__(THREADS) void gemm_nt_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  constexpr int BT = 256, WT = 128, TW = 4, BK = 32, NST = 4;
+  constexpr int STAGE = 2 * BT * 64;  // bytes: A tile then B tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const TileMap tmap = map_block(blockIdx.x, gridDim.x, tiles_m, tiles_n);
+  const int row0 = tmap.tm * BT, col0 = tmap.tn * BT;
+  const int bo = tmap.b / g.batch_inner, bi = tmap.b - bo * g.batch_inner;
+  const bf16_t* __restrict__ A = (const bf16_t*)g.A + (long)bo * g.strideA + (long)bi * g.strideA2;
+  const bf16_t* __restrict__ B = (const bf16_t*)g.B + (long)bo * g.strideB + (long)bi * g.strideB2;
+  const long coff = (long)bo * g.strideC + (long)bi * g.strideC2;
+
+  // wave w issues loads j = 0..3 per operand and stage; load j fills tile rows 16*(4w+j) .. +15:
+  // lane l -> row 16*(4w+j) + l/4, physical chunk l%4
+  const bf16_t* ga[4];
+  const bf16_t* gb[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = 16 * (4 * wave + j) + (lane >> 2);
+    const int f = ((r >> 2) & 1) | ((((r >> 1) ^ (r >> 3)) & 1) << 1);
+    const int c = (lane & 3) ^ f;  // logical chunk that belongs at this physical slot
+    const int ra = min(row0 + r, g.M - 1), rb = min(col0 + r, g.N - 1);
+    ga[j] = A + (long)ra * g.lda + c * 8;
+    gb[j] = B + (long)rb * g.ldb + c * 8;
+  }
+  auto issue = [&](int kt) {
+    unsigned char* sa = smem + (kt & (NST - 1)) * STAGE + wave * 4096;
+    unsigned char* sb = sa + BT * 64;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ga[j] + kt * BK),
+                                       (__attribute__((address_space(3))) void*)(sa + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gb[j] + kt * BK),
+                                       (__attribute__((address_space(3))) void*)(sb + j * 1024), 16, 0, 0);
+    }
+  };
+
+  f32x16_t acc[TW][TW];
+#pragma unroll
+  for (int i = 0; i < TW; ++i)
+#pragma unroll
+    for (int j = 0; j < TW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nk = g.K / BK;
+  const int li = lane & 31, lh = lane >> 5;
+  // fragment byte offsets inside a stage, per k-step (2) and 32-row group (4)
+  int offA[2][TW], offB[2][TW];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+    for (int i = 0; i < TW; ++i) {
+      offA[ks][i] = swz64(wm * WT + i * 32 + li, 2 * ks + lh);
+      offB[ks][i] = BT * 64 + swz64(wn * WT + i * 32 + li, 2 * ks + lh);
+    }
+  auto frags = [&](const unsigned char* st, int ks, bf16x8_t (&af)[TW], bf16x8_t (&bfr)[TW]) {
+#pragma unroll
+    for (int i = 0; i < TW; ++i) {
+      af[i] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(st + offA[ks][i]));
+      bfr[i] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(st + offB[ks][i]));
+    }
+  };
+  auto mma = [&](const bf16x8_t (&af)[TW], const bf16x8_t (&bfr)[TW]) {
+#pragma unroll
+    for (int i = 0; i < TW; ++i)
+#pragma unroll
+      for (int j = 0; j < TW; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+  };
+
+  // Software pipeline, per k-tile kt (one barrier each):
+  //   wait until tile kt+1 has landed (at most the loads of tiles kt+2, kt+3 outstanding), barrier;
+  //   start the loads of tile kt+3 into the stage that held tile kt-1;
+  //   read the MFMA fragments of tile kt+1 from LDS into the idle register set WHILE the fragments of
+  //   tile kt, read one iteration earlier, feed the 32 MFMAs.
+  // A plain s_barrier is used: __syncthreads() would add a fence that waits for ALL outstanding loads
+  // and with it the prefetch depth.  lgkmcnt(0) before the barrier: this wave's LDS reads are done, so
+  // after the barrier the stage they came from may be overwritten.
+  // The loop body is branch-free (the number of k-tiles is even): past the end, `issue` re-loads the
+  // last tile into a stage nobody reads any more and `frags` reads a stage whose values are never used.
+  auto stage_ptr = [&](int kt) -> const unsigned char* { return smem + (kt & (NST - 1)) * STAGE; };
+  bf16x8_t a0[2][TW], b0[2][TW], a1[2][TW], b1[2][TW];   // [k-step][32-row group], two sets
+  issue(0);
+  issue(min(1, nk - 1));
+  issue(min(2, nk - 1));
+  __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0): tile 0 has landed
+  __builtin_amdgcn_s_barrier();
+  frags(stage_ptr(0), 0, a0[0], b0[0]);
+  frags(stage_ptr(0), 1, a0[1], b0[1]);
+  for (int kt = 0; kt < nk; kt += 2) {
+    // even tile: set 0 feeds the MFMAs, set 1 is filled from tile kt+1
+    __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0): all but the newest tile have landed
+    __builtin_amdgcn_s_barrier();
+    issue(min(kt + 3, nk - 1));
+    frags(stage_ptr(kt + 1), 0, a1[0], b1[0]);
+    frags(stage_ptr(kt + 1), 1, a1[1], b1[1]);
+    mma(a0[0], b0[0]);
+    mma(a0[1], b0[1]);
+    // odd tile: set 1 feeds the MFMAs, set 0 is filled from tile kt+2
+    __builtin_amdgcn_s_waitcnt(0x0078);
+    __builtin_amdgcn_s_barrier();
+    issue(min(kt + 4, nk - 1));
+    frags(stage_ptr(kt + 2), 0, a0[0], b0[0]);
+    frags(stage_ptr(kt + 2), 1, a0[1], b0[1]);
+    mma(a1[0], b1[0]);
+    mma(a1[1], b1[1]);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  __builtin_amdgcn_s_barrier();
+
+  if (EPI == EPI_STORE_F32) {
+#pragma unroll
+    for (int i = 0; i < TW; ++i)
+#pragma unroll
+      for (int j = 0; j < TW; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          int r = row0 + wm * WT + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+          int c = col0 + wn * WT + j * 32 + li;
+          if (r < g.M && c < g.N) ((float*)g.C)[coff + (long)r * g.ldc + c] = acc[i][j][v];
+        }
+  } else {  // EPI_ROWNORM2: one part per wave column (128 output columns)
+    __syncthreads();
+    float* red = (float*)smem;  // [2][BT]
+#pragma unroll
+    for (int i = 0; i < TW; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < TW; ++j)
+          if (col0 + wn * WT + j * 32 + li < g.N) s = fmaf(acc[i][j][v], acc[i][j][v], s);
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        if (li == 0) red[wn * BT + wm * WT + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3)] = s;
+      }
+    __syncthreads();
+    for (int t = tid; t < BT; t += THREADS) {
+      int r = row0 + t;
+      if (r < g.M) {
+        float* out = (float*)g.C + coff + (long)r * g.ldc;
+        out[2 * tmap.tn] = red[t];
+        if ((2 * tmap.tn + 1) * 128 < g.N) out[2 * tmap.tn + 1] = red[BT + t];
+      }
+    }
+  }
+}
+
+template <int EPI>
+hipError_t launch_dma(const GemmArgs& g, hipStream_t stream) {
+  constexpr int BT = 256, LDS = 4 * 2 * BT * 64;
+  const int tiles_m = (g.M + BT - 1) / BT, tiles_n = (g.N + BT - 1) / BT;
+  const long nblocks = (long)tiles_m * tiles_n * g.batch;
+  if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
+  auto kern = gemm_nt_dma_kernel<EPI>;
+  static hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(THREADS), LDS, stream, g, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+template <typename In, int EPI, bool GATHER, int TW>
+hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
+  constexpr int BT = 64 * TW;
+  constexpr int LDS = 2 * 2 * BT * ROWB;
+  const int tiles_m = (g.M + BT - 1) / BT, tiles_n = (g.N + BT - 1) / BT;
   const long nblocks = (long)tiles_m * tiles_n * g.batch;
   if (nblocks <= 0) return hipSuccess;
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
-  dim3 grid((unsigned)nblocks), block(THREADS);
-  if (g.gatherA || g.gatherB)
-    hipLaunchKernelGGL((gemm_nt_kernel<In, EPI, true>), grid, block, 0, stream, g, tiles_m, tiles_n);
-  else
-    hipLaunchKernelGGL((gemm_nt_kernel<In, EPI, false>), grid, block, 0, stream, g, tiles_m, tiles_n);
+  auto kern = gemm_nt_kernel<In, EPI, GATHER, TW>;
+  static hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(THREADS), LDS, stream, g, tiles_m, tiles_n);
   return hipGetLastError();
+}
+
+// Large un-gathered bf16 problems take 256x256 block tiles (half the LDS and L2 traffic per flop);
+// everything else takes 128x128 tiles, which also fill the chip at small sizes.
+inline bool use_big_tiles(const GemmArgs& g) {
+  const long tiles = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
+  return !g.gatherA && !g.gatherB && g.N >= 256 && tiles >= 512;
+}
+
+template <typename In, int EPI>
+hipError_t launch_t(const GemmArgs& g, hipStream_t stream) {
+  if (g.gatherA || g.gatherB) return launch_cfg<In, EPI, true, 2>(g, stream);
+  if constexpr (std::is_same<In, bf16_t>::value && EPI != EPI_STORE_F64) {
+    if (use_big_tiles(g)) {
+      if (g.K % 64 == 0 && g.K >= 64 && g.M >= 1 && g.N >= 1) return launch_dma<EPI>(g, stream);
+      return launch_cfg<In, EPI, false, 4>(g, stream);
+    }
+  }
+  return launch_cfg<In, EPI, false, 2>(g, stream);
 }
 
 template <typename In>
@@ -253,7 +488,7 @@ hipError_t launch_e(const GemmArgs& g, hipStream_t stream) {
 
 }  // namespace
 
-int gemm_tiles_n(int N) { return (N + BN - 1) / BN; }
+int gemm_tiles_n(int N) { return (N + 127) / 128; }
 
 hipError_t launch_gemm_nt(const GemmArgs& g, int dtype, hipStream_t stream) {
   return dtype == DT_BF16 ? launch_e<bf16_t>(g, stream) : launch_e<float>(g, stream);

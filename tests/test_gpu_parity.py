@@ -116,6 +116,24 @@ def test_reduce_matches_oracle(C, name, modes):
         np.testing.assert_array_equal(tok[b], X[b][idx[b]])                  # bit copy of the stored rows
 
 
+def test_ragged_shapes_on_the_large_tile_gemm_path(C):
+    # 16 x 1000 tokens x 2176 wide: the projection takes the 256x256-tile kernel (>= 512 tiles) with a
+    # ragged last tile in both directions; the oracle checks three of the sixteen images
+    w = I.small_workload(cid=14, name="bigtile", batch=16, n_tokens=1000, d_model=2176, dtype=I.BF16, n_query=40,
+                         n_heads=17, keep_k=50, preselect_m=100, rank_r=20, factor_rank=128, n_act_layers=1)
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    for rel in (0, 1):
+        p = U.lib_params(C, w, w.batch, rel_mode=rel)
+        sq, sa, sf = C.score(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+        idx, _ = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+        for b in (0, 7, 15):
+            ref = U.oracle_image(w, batch, b, U.oracle_params(w, rel_mode=rel))
+            U.assert_scores_close(_cpu(sq)[b], ref["s_query"], w.dtype, "bigtile s_query rel %d img %d" % (rel, b))
+            U.assert_scores_close(_cpu(sf)[b], ref["s_fused"], w.dtype, "bigtile s_fused rel %d img %d" % (rel, b))
+            np.testing.assert_array_equal(_cpu(idx)[b], ref["idx"], err_msg="margin %r" % ref["margin_topm"])
+
+
 def test_keep_everything_is_identity(C):
     w = SMALL["bf16-ragged"]
     batch = U.gen_batch(w)
