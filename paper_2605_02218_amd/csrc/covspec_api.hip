@@ -14,6 +14,7 @@ namespace {
 constexpr int kMaxTokens = 16384;
 constexpr int kMaxPreselect = 4096;
 constexpr int kMaxActLayers = 8;
+constexpr int kSubspaceIters = 10;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -26,7 +27,8 @@ struct Plan {
   int nP;         // Gram pitch (padded order of the eigen-solve)
   // workspace offsets (bytes)
   size_t wqT, wkT, Eq, qn2, Eq3, G3raw, G3, vn2p, logits, Ev, S, stats, sq, sa, sf;
-  size_t idxm, Awork, ctl, lam, c, Lt, order, resid;
+  size_t idxm, Awork, ctl, lam, c, Lt, order, resid, sub, ok;
+  int P;          // block size of the subspace iteration (0: full Jacobi solve)
   size_t total;
 };
 
@@ -105,6 +107,9 @@ int make_plan(const covspec_params* p, Plan* pl) {
   q.ctl = take(jacobi_ctl_bytes(q.B));
   q.lam = take(B * q.nP * 8);
   q.c = take(B * M * 4);
+  q.P = (q.lr == COVSPEC_LR_ENERGY_TOPK) ? subspace_block(M, r) : 0;
+  q.sub = take(subspace_workspace_bytes(q.B, M, q.nP, q.P));
+  q.ok = take(B * 4);
   q.Lt = q.order = q.resid = 0;
   if (q.lr == COVSPEC_LR_GREEDY_RESIDUAL) {
     q.Lt = take(B * (size_t)k * q.nP * 8);
@@ -281,9 +286,22 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
   if (q.lr == COVSPEC_LR_ENERGY_TOPK) {
     float* c = c_out ? c_out : at<float>(ws, q.c);
     marks.mark(COVSPEC_STAGE_LOWRANK);
-    HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), st));
-    marks.mark(COVSPEC_STAGE_KEEP);
-    HIPCHK(launch_subspace_energy(A, q.B, q.M, q.nP, q.r, at<double>(ws, q.lam), c, st));
+    if (q.P > 0) {
+      // r dominant eigenpairs by block subspace iteration; images whose residual check fails fall back to
+      // the full Jacobi solve (which leaves the others untouched)
+      int* ok = at<int>(ws, q.ok);
+      const double* Ut = nullptr;
+      HIPCHK(launch_subspace_eigen(A, q.B, q.M, q.nP, q.r, q.P, kSubspaceIters, at<void>(ws, q.sub), at<void>(ws, q.ctl),
+                                   at<double>(ws, q.lam), ok, &Ut, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, st));
+      marks.mark(COVSPEC_STAGE_KEEP);
+      HIPCHK(launch_subspace_energy(Ut, q.B, q.P, q.M, q.nP, (long)q.P * q.nP, q.r, at<double>(ws, q.lam), c, ok, 1, st));
+      HIPCHK(launch_subspace_energy(A, q.B, q.M, q.M, q.nP, (long)q.nP * q.nP, q.r, at<double>(ws, q.lam), c, ok, 0, st));
+    } else {
+      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, st));
+      marks.mark(COVSPEC_STAGE_KEEP);
+      HIPCHK(launch_subspace_energy(A, q.B, q.M, q.M, q.nP, (long)q.nP * q.nP, q.r, at<double>(ws, q.lam), c, nullptr, 0, st));
+    }
     HIPCHK(launch_select_top(c, q.B, q.M, q.k, idxm, idx_out, st));
   } else {
     int32_t* order = at<int32_t>(ws, q.order);

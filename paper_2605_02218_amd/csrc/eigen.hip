@@ -48,7 +48,8 @@ constexpr double kRotEps = 1e-15;   // rotations below this relative size are sk
 constexpr double kConvTol = 3e-7;
 constexpr int kMaxSweeps = 30;
 
-__global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restrict__ A, int n, int nP, JacobiCtl* ctl) {
+__global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restrict__ A, int n, int nP, JacobiCtl* ctl,
+                                                             const int* __restrict__ preset_done) {
   __shared__ double red[4];
   const int b = blockIdx.x;
   const double* Ab = A + (long)b * nP * nP;
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restri
   if (threadIdx.x == 0) {
     double t = red[0] + red[1] + red[2] + red[3];
     ctl[b].maxoff = 0ull;
-    ctl[b].done = 0;
+    ctl[b].done = preset_done ? preset_done[b] : 0;
     ctl[b].sweeps = 0;
     double f = 1e-13 * t;
     ctl[b].floor2 = f * f;
@@ -271,32 +272,36 @@ __global__ __launch_bounds__(256, 2) void jacobi_round_kernel(double* __restrict
   if (tid == 0 && meas2 > 0.0) atomicMax(&ctl[b].maxoff, (unsigned long long)__double_as_longlong(sqrt(meas2)));
 }
 
-// lam[b*nP + k] = |row k of A[b]|, one wave per row
-__global__ __launch_bounds__(256) void row_length_kernel(const double* __restrict__ A, int n, int nP, double* __restrict__ lam) {
+// lam[b*rows + k] = |row k of A[b]| (A[b] starts at b*img_stride and has `rows` rows of `pitch`), one wave per row
+__global__ __launch_bounds__(256) void row_length_kernel(const double* __restrict__ A, int rows, int pitch, long img_stride,
+                                                          double* __restrict__ lam) {
   const int lane = threadIdx.x & 63;
   const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int b = blockIdx.y;
-  if (k >= n) return;
-  const double* row = A + ((long)b * nP + k) * nP;
+  if (k >= rows) return;
+  const double* row = A + b * img_stride + (long)k * pitch;
   double s = 0.0;
-  for (int j = lane; j < nP; j += 64) s = fma(row[j], row[j], s);
+  for (int j = lane; j < pitch; j += 64) s = fma(row[j], row[j], s);
   s = wave_sum(s);
-  if (lane == 0) lam[(long)b * nP + k] = sqrt(s);
+  if (lane == 0) lam[(long)b * rows + k] = sqrt(s);
 }
 
-// c[b,i] = sum_{k in top-r by lam} A[k][i]^2 / lam[k], rows added in ascending k
-__global__ __launch_bounds__(256) void energy_kernel(const double* __restrict__ A, int n, int nP, int r,
-                                                      const double* __restrict__ lam, float* __restrict__ c) {
+// c[b,i] = sum over the r longest rows k of A[b] (rows x pitch) of A[k][i]^2 / |row k|, rows added in
+// ascending k; i < n.  Images with flag[b] != run_if are skipped (flag == nullptr: none).
+__global__ __launch_bounds__(256) void energy_kernel(const double* __restrict__ A, int rows, int n, int pitch, long img_stride,
+                                                      int r, const double* __restrict__ lam, float* __restrict__ c,
+                                                      const int* __restrict__ flag, int run_if) {
   __shared__ double slam[4096];
   __shared__ unsigned char sel[4096];
   const int b = blockIdx.y;
-  const double* lb = lam + (long)b * nP;
-  for (int k = threadIdx.x; k < n; k += 256) slam[k] = lb[k];
+  if (flag && flag[b] != run_if) return;
+  const double* lb = lam + (long)b * rows;
+  for (int k = threadIdx.x; k < rows; k += 256) slam[k] = lb[k];
   __syncthreads();
-  for (int k = threadIdx.x; k < n; k += 256) {
+  for (int k = threadIdx.x; k < rows; k += 256) {
     const double v = slam[k];
     int rank = 0;
-    for (int j = 0; j < n; ++j) {
+    for (int j = 0; j < rows; ++j) {
       const double w = slam[j];
       rank += (w > v || (w == v && j < k)) ? 1 : 0;
     }
@@ -305,11 +310,11 @@ __global__ __launch_bounds__(256) void energy_kernel(const double* __restrict__ 
   __syncthreads();
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
-  const double* Ab = A + (long)b * nP * nP + i;
+  const double* Ab = A + b * img_stride + i;
   double acc = 0.0;
-  for (int k = 0; k < n; ++k) {
+  for (int k = 0; k < rows; ++k) {
     if (sel[k]) {
-      const double a = Ab[(long)k * nP];
+      const double a = Ab[(long)k * pitch];
       acc += a * a / slam[k];
     }
   }
@@ -322,11 +327,12 @@ size_t jacobi_ctl_bytes(int B) { return sizeof(JacobiCtl) * (size_t)B; }
 int jacobi_pitch(int n) { return (n + PR - 1) / PR * PR; }
 int jacobi_launches(int n) { return kMaxSweeps * (jacobi_pitch(n) / SB - 1); }
 
-hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl_, double* len2, hipStream_t st) {
+hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl_, double* len2, const int* preset_done,
+                               hipStream_t st) {
   if (nP % 64 != 0 || n > nP || n > 4096 || r < 1 || r > n) return hipErrorInvalidValue;
   JacobiCtl* ctl = (JacobiCtl*)ctl_;
   const int nsb = nP / SB;  // even, since nP % 64 == 0
-  hipLaunchKernelGGL(jacobi_init_kernel, dim3(B), dim3(256), 0, st, A, n, nP, ctl);
+  hipLaunchKernelGGL(jacobi_init_kernel, dim3(B), dim3(256), 0, st, A, n, nP, ctl, preset_done);
   for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
     for (int round = 0; round < nsb - 1; ++round)
       hipLaunchKernelGGL(jacobi_round_kernel, dim3((unsigned)(B * (nsb / 2))), dim3(256), 0, st, A, nP, nsb, round, ctl, len2);
@@ -335,10 +341,16 @@ hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl
   return hipGetLastError();
 }
 
-hipError_t launch_subspace_energy(const double* A, int B, int n, int nP, int r, double* lam, float* c, hipStream_t st) {
-  if (n > 4096) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(row_length_kernel, dim3((n + 3) / 4, B), dim3(256), 0, st, A, n, nP, lam);
-  hipLaunchKernelGGL(energy_kernel, dim3((n + 255) / 256, B), dim3(256), 0, st, A, n, nP, r, lam, c);
+hipError_t launch_row_lengths(const double* A, int B, int rows, int pitch, long img_stride, double* lam, hipStream_t st) {
+  hipLaunchKernelGGL(row_length_kernel, dim3((rows + 3) / 4, B), dim3(256), 0, st, A, rows, pitch, img_stride, lam);
+  return hipGetLastError();
+}
+
+hipError_t launch_subspace_energy(const double* A, int B, int rows, int n, int pitch, long img_stride, int r, double* lam,
+                                  float* c, const int* flag, int run_if, hipStream_t st) {
+  if (rows > 4096 || r > rows) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(row_length_kernel, dim3((rows + 3) / 4, B), dim3(256), 0, st, A, rows, pitch, img_stride, lam);
+  hipLaunchKernelGGL(energy_kernel, dim3((n + 255) / 256, B), dim3(256), 0, st, A, rows, n, pitch, img_stride, r, lam, c, flag, run_if);
   return hipGetLastError();
 }
 

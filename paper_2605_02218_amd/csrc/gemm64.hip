@@ -24,7 +24,7 @@ __device__ __forceinline__ double as_f64(double v) { return v; }
 __device__ __forceinline__ double as_f64(float v) { return (double)v; }
 __device__ __forceinline__ double as_f64(bf16_t v) { return (double)bf16_to_f32(v); }
 
-template <typename TA, typename TB, int EPI, bool GATHER>
+template <typename TA, typename TB, int EPI, bool GATHER, bool TRANSB>
 __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, int tiles_n) {
   __shared__ double sA[TM * PITCH];
   __shared__ double sB[TN * PITCH];
@@ -37,6 +37,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
   const int tm = pidx / tiles_n, tn = pidx - tm * tiles_n;
   const int row0 = tm * TM, col0 = tn * TN;
   const int bo = bidx / g.batch_inner, bi = bidx - bo * g.batch_inner;
+  if (g.skip && g.skip[bo] == g.skip_if) return;   // uniform per workgroup
   const TA* __restrict__ A = (const TA*)g.A + (long)bo * g.strideA + (long)bi * g.strideA2;
   const TB* __restrict__ B = (const TB*)g.B + (long)bo * g.strideB + (long)bi * g.strideB2;
   const long coff = (long)bo * g.strideC + (long)bi * g.strideC2;
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
       if (g.gatherB && bok[s]) ib = g.gatherB[(long)bo * g.gstrideB + rb];
     }
     aoff[s] = ia * g.lda;
-    boff[s] = ib * g.ldb;
+    boff[s] = TRANSB ? ib : ib * g.ldb;   // TRANSB: B is stored [K][N], element (n, k) at k*ldb + n
   }
 
   f64x4_t acc[2][2];
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
     for (int s = 0; s < 4; ++s) {
       const int r = (tid >> 4) + 16 * s;
       sA[r * PITCH + lk] = (aok[s] && kok) ? as_f64(A[aoff[s] + k0 + lk]) : 0.0;
-      sB[r * PITCH + lk] = (bok[s] && kok) ? as_f64(B[boff[s] + k0 + lk]) : 0.0;
+      sB[r * PITCH + lk] = (bok[s] && kok) ? as_f64(B[TRANSB ? boff[s] + (long)(k0 + lk) * g.ldb : boff[s] + k0 + lk]) : 0.0;
     }
     __syncthreads();
 #pragma unroll
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
     __syncthreads();
   }
 
-  if (EPI == EPI_STORE_F64) {
+  if (EPI == EPI_STORE_F64 || EPI == EPI_SUB_F64) {
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -101,7 +102,11 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
         for (int v = 0; v < 4; ++v) {
           const int r = row0 + wm * 32 + i * 16 + 4 * v + kq;
           const int c = col0 + wn * 32 + j * 16 + i16;
-          if (r < g.M && c < g.N) ((double*)g.C)[coff + (long)r * g.ldc + c] = acc[i][j][v];
+          if (r < g.M && c < g.N) {
+            double* out = (double*)g.C + coff + (long)r * g.ldc + c;
+            if (EPI == EPI_SUB_F64) *out -= acc[i][j][v];
+            else *out = acc[i][j][v];
+          }
         }
   } else {  // EPI_ROWNORM2: per-row sum over this tile's columns of C^2 (fp64)
 #pragma unroll
@@ -129,11 +134,18 @@ hipError_t launch_ab(const GemmArgs& g, hipStream_t stream) {
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
   dim3 grid((unsigned)nblocks), block(256);
   const bool gather = g.gatherA || g.gatherB;
-  if (g.epilogue == EPI_STORE_F64) {
-    if (gather) hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_STORE_F64, true>), grid, block, 0, stream, g, tiles_m, tiles_n);
-    else hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_STORE_F64, false>), grid, block, 0, stream, g, tiles_m, tiles_n);
+  if (g.transB) {
+    if (gather) return hipErrorInvalidValue;
+    if (g.epilogue == EPI_STORE_F64) hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_STORE_F64, false, true>), grid, block, 0, stream, g, tiles_m, tiles_n);
+    else if (g.epilogue == EPI_SUB_F64) hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_SUB_F64, false, true>), grid, block, 0, stream, g, tiles_m, tiles_n);
+    else return hipErrorInvalidValue;
+  } else if (g.epilogue == EPI_STORE_F64) {
+    if (gather) hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_STORE_F64, true, false>), grid, block, 0, stream, g, tiles_m, tiles_n);
+    else hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_STORE_F64, false, false>), grid, block, 0, stream, g, tiles_m, tiles_n);
+  } else if (g.epilogue == EPI_SUB_F64) {
+    hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_SUB_F64, false, false>), grid, block, 0, stream, g, tiles_m, tiles_n);
   } else if (g.epilogue == EPI_ROWNORM2) {
-    hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_ROWNORM2, false>), grid, block, 0, stream, g, tiles_m, tiles_n);
+    hipLaunchKernelGGL((gemm64_kernel<TA, TB, EPI_ROWNORM2, false, false>), grid, block, 0, stream, g, tiles_m, tiles_n);
   } else {
     return hipErrorInvalidValue;
   }

@@ -15,6 +15,7 @@ enum GemmEpilogue {
   EPI_STORE_F32 = 0,  // C fp32 [M,N]
   EPI_ROWNORM2 = 1,   // C fp32 [M, tiles_n]: per-tile sums over columns of C^2 (C itself is not stored)
   EPI_STORE_F64 = 2,  // C fp64 [M,N]; the fp32 accumulators are flushed into fp64 every 256 k
+  EPI_SUB_F64 = 3,    // C fp64 [M,N] -= A*B^T (fp64 kernel only)
 };
 
 struct GemmArgs {
@@ -31,6 +32,10 @@ struct GemmArgs {
   const int32_t* gatherB = nullptr;
   long gstrideA = 0, gstrideB = 0;
   int epilogue = EPI_STORE_F32;
+  // fp64 kernel only:
+  bool transB = false;                         // B is stored [K][N] (row pitch ldb), i.e. C = A * B
+  const int* skip = nullptr;                   // per outer batch: the work is skipped when skip[b] == skip_if
+  int skip_if = 1;
 };
 int gemm_tiles_n(int N);
 hipError_t launch_gemm_nt(const GemmArgs& g, int dtype, hipStream_t stream);
@@ -101,11 +106,26 @@ hipError_t launch_select_top(const float* scores, int B, int n, int m, const int
 size_t jacobi_ctl_bytes(int B);
 int jacobi_pitch(int n);      // row pitch (and padded order) the solver needs: n rounded up to 64
 int jacobi_launches(int n);   // tournament-round launches per solve
-hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl, double* len2, hipStream_t stream);
-// Subspace energy (paper energy equation) from the converged rows: c[b,i] = sum over the r rows with the
-// largest norm of A[k][i]^2 / |row k|.   `lam` is scratch of B*nP doubles.
-hipError_t launch_subspace_energy(const double* A, int B, int n, int nP, int r, double* lam, float* c,
-                                  hipStream_t stream);
+// preset_done (optional, [B]): images whose entry is non-zero are left untouched.
+hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl, double* len2, const int* preset_done,
+                               hipStream_t stream);
+hipError_t launch_row_lengths(const double* A, int B, int rows, int pitch, long img_stride, double* lam, hipStream_t stream);
+// Subspace energy (paper energy equation) from rows of the form lambda_k v_k^T: c[b,i] = sum over the r
+// longest of the `rows` rows of A[b] of A[k][i]^2 / |row k|, i < n.  A[b] starts at b*img_stride, rows have
+// `pitch` doubles.  `lam` is scratch of B*rows doubles.  Images with flag[b] != run_if are skipped
+// (flag == nullptr: none).
+hipError_t launch_subspace_energy(const double* A, int B, int rows, int n, int pitch, long img_stride, int r, double* lam,
+                                  float* c, const int* flag, int run_if, hipStream_t stream);
+
+// ---------------------------------------------------------------- subspace.hip
+// Block subspace iteration for the r dominant eigenpairs of G[b] (fp64, n x n, pitch nP, left untouched).
+// subspace_block: block size P for (n, r), 0 when the full solve is the better choice.
+// On return ok[b] = 1 where the residual check passed; then the P rows of (*ut)[b] (pitch nP) are
+// theta_k u_k^T with the r longest converged.  jacobi_ctl / jacobi_len2 as for launch_jacobi_eigen.
+int subspace_block(int n, int r);
+size_t subspace_workspace_bytes(int B, int n, int nP, int P);
+hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, void* ws, void* jacobi_ctl,
+                                 double* jacobi_len2, int* ok, const double** ut, hipStream_t stream);
 
 // ---------------------------------------------------------------- greedy.hip
 // Greedy residual picks (variant): pivoted Cholesky of G[b] (fp64, pitch nP).  Lt is scratch [B][k][nP] fp64.
