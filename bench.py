@@ -19,7 +19,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # MI355X published peaks
-PEAK = {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0, "mfma_fp64_TFLOPs": 78.6}
+PEAK = {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0, "mfma_fp64_TFLOPs": 78.6, "valu_fp64_TFLOPs": 78.6}
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this program (profiles/), scaled by
+# the counters' reading for a copy of known size; keyed by (workload, kernel).  None where not collected.
+TRAFFIC = {}
 
 
 def _params(C, w, rel, lr):
@@ -89,42 +93,50 @@ def stage_times(C, p, dev, ws, steps):
     out = {}
     for i, name in enumerate(C.STAGES):
         out[name] = sum(evs[i].elapsed_time(evs[i + 1]) for evs in sets) / steps
-    return out
+    probe = sum(evs[C.PROBE_BEGIN].elapsed_time(evs[C.PROBE_END]) for evs in sets) / steps
+    return out, probe
 
 
-def roofline_for(w, p_modes, stages, C):
-    """Roofline object of the dominant stage's kernel (algorithmic work / measured duration)."""
+def roofline_for(w, p, p_modes, stages, probe_ms, C):
+    """Roofline object of the kernel the step spends most of its time in.
+
+    Candidates are the kernels that make up (nearly) all of a stage by themselves, with the stage time as the
+    launch duration, and the fp64 product of the subspace iteration, timed by the library's probe events
+    around one of its equal launches.  achieved = algorithmic work of one launch / its measured duration.
+    """
     import covspec_inputs as I
     B, N, d, T, K = w.batch, w.n_tokens, w.d_model, w.n_query, w.n_act_layers
     M, k = w.preselect_m, w.keep_k
     e = 2 if w.dtype == I.BF16 else 4
-    nP = (M + 63) // 64 * 64          # padded order of the eigen-solve
-    nsb = nP // 32                    # 32-row super-blocks; one launch = one tournament round over their pairs
-    # stage -> (kernel, bound, peak, unit, algorithmic work per launch, launches per step)
-    table = {
-        "token_projection": ("gemm_nt_kernel<bf16,rownorm2>" if p_modes[0] == 0 else "gemm_nt_kernel<bf16,store>",
-                             "mfma", PEAK["mfma_bf16_TFLOPs"] if e == 2 else PEAK["mfma_fp64_TFLOPs"], "TFLOP/s",
-                             2.0 * B * N * d * d / 1e12, 1),
-        "activity": ("activity_kernel", "hbm", PEAK["hbm_GBps"], "GB/s", (K + 1) * B * N * d * e / 1e9, 1),
-        "gather": ("gather_rows_kernel", "hbm", PEAK["hbm_GBps"], "GB/s", 2.0 * B * k * d * e / 1e9, 1),
-        "gram": ("gemm_nt_kernel<gather,f64>" if p_modes[1] == 0 else "gemm64_kernel<bf16>",
-                 "mfma", PEAK["mfma_bf16_TFLOPs"] if (e == 2 and p_modes[1] == 0) else PEAK["mfma_fp64_TFLOPs"],
-                 "TFLOP/s", 2.0 * B * M * M * d / 1e12, 1),
+    bf = e == 2
+    # name -> (kernel, bound, peak, unit, algorithmic work per launch, launches per step, ms per launch)
+    cand = {
+        "token_projection": ("gemm_nt_dma_kernel<rownorm2>" if (bf and p_modes[0] == 0) else
+                             "gemm_nt_dma_kernel<store>" if bf else "gemm64_kernel<f32>",
+                             "mfma", PEAK["mfma_bf16_TFLOPs"] if bf else PEAK["mfma_fp64_TFLOPs"], "TFLOP/s",
+                             2.0 * B * N * d * d / 1e12, 1, stages["token_projection"]),
+        "activity": ("activity_kernel", "hbm", PEAK["hbm_GBps"], "GB/s", (K + 1) * B * N * d * e / 1e9, 1,
+                     stages["activity"]),
+        "gather": ("gather_rows_kernel", "hbm", PEAK["hbm_GBps"], "GB/s", 2.0 * B * k * d * e / 1e9, 1,
+                   stages["gather"]),
+        "gram": ("gemm_nt_kernel<bf16,gather,f64>" if (bf and p_modes[1] == 0) else "gemm64_kernel<gather>",
+                 "mfma", PEAK["mfma_bf16_TFLOPs"] if (bf and p_modes[1] == 0) else PEAK["mfma_fp64_TFLOPs"],
+                 "TFLOP/s", 2.0 * B * M * M * d / 1e12, 1, stages["gram"]),
     }
-    if p_modes[1] == 0:
-        # one launch = one tournament round: every pair of super-blocks forms a 64x64 Gram block (2*64*64*nP flops)
-        # and applies a 64x64 rotation block (2*64*64*nP flops) on the fp64 MFMA
-        table["lowrank"] = ("jacobi_round_kernel", "mfma", PEAK["mfma_fp64_TFLOPs"], "TFLOP/s",
-                            B * (nsb // 2) * 4.0 * 4096 * nP / 1e12, C.JACOBI_MAX_SWEEPS * (nsb - 1))
-    else:
-        table["lowrank"] = ("greedy_kernel", "alu", 78.6, "TFLOP/s", 1.0 * B * M * k * k / 1e12, 1)
-    dom = max((s for s in stages if s in table), key=lambda s: stages[s])
-    kern, bound, peak, unit, work, launches = table[dom]
-    avg_ms = stages[dom] / launches
-    achieved = work / (avg_ms / 1e3)
+    n_probe, pr, pc, pk = C.probe_launches(p)
+    if n_probe > 0 and probe_ms > 0:
+        cand["lowrank_product"] = ("gemm64_kernel<f64,f64,store>", "mfma", PEAK["mfma_fp64_TFLOPs"], "TFLOP/s",
+                                   2.0 * B * pr * pc * pk / 1e12, n_probe, probe_ms)
+    elif p_modes[1] == 1:
+        cand["lowrank"] = ("greedy_kernel", "alu", PEAK["valu_fp64_TFLOPs"], "TFLOP/s", 1.0 * B * M * k * k / 1e12, 1,
+                           stages["lowrank"])
+    dom = max(cand, key=lambda s: cand[s][5] * cand[s][6])
+    kern, bound, peak, unit, work, launches, ms = cand[dom]
+    achieved = work / (ms / 1e3)
     return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-            "frac": round(achieved / peak, 5), "traffic": None, "kernel": kern, "stage": dom,
-            "launches_per_step": launches, "avg_launch_ms": round(avg_ms, 5)}
+            "frac": round(achieved / peak, 5), "traffic": TRAFFIC.get((w.cid, kern)), "kernel": kern,
+            "launches_per_step": launches, "avg_launch_ms": round(ms, 5),
+            "ms_per_step_in_kernel": round(ms * launches, 4)}
 
 
 def cpu_baseline(w, batch, rel, lr, budget_s=20.0):
@@ -178,7 +190,7 @@ def main():
     p = _params(C, w, *modes)
     ws = C.alloc_workspace(p)
     ms = time_reduce(C, p, dev, ws, a.steps, a.warmup)
-    stages = stage_times(C, p, dev, ws, min(a.steps, 10))
+    stages, probe_ms = stage_times(C, p, dev, ws, min(a.steps, 10))
     line = {
         "metric": "images/sec for visual-token reduction (score+select+gather)",
         "value": round(w.batch / ms * 1e3, 3), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -188,7 +200,7 @@ def main():
             w.cid, w.name, w.batch, w.n_tokens, w.d_model, w.n_query, w.n_heads, w.n_act_layers, w.keep_k,
             w.preselect_m, w.rank_r), "pipeline": "paper: cosine-max relevance + rank-r SVD energy" if modes == (0, 0)
             else "variant: attention-softmax relevance + greedy residual picks", "entry_point": "covspec_reduce"},
-        "roofline": roofline_for(w, modes, stages, C),
+        "roofline": roofline_for(w, p, modes, stages, probe_ms, C),
         "stages_ms": {k: round(v, 4) for k, v in stages.items()},
     }
     if not a.no_cpu_baseline:

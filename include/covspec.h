@@ -127,8 +127,11 @@ int covspec_reduce(const covspec_params* p, const void* X, const void* hidden, c
  * covspec_reduce with per-stage timing marks, for benchmarks and profilers (the paper gives no
  * time breakdown of Sec. III-A; this is how one is measured).  `stage_events` is a HOST array of
  * COVSPEC_NUM_STAGE_EVENTS hipEvent_t handles created by the caller with timing enabled; event i is
- * recorded on `stream` when stage i begins, the last one when all work has been enqueued.  Stage i
- * lasted from event i to event i+1.  Same results, arguments and errors as covspec_reduce.
+ * recorded on `stream` when stage i begins, event COVSPEC_STAGE_END when all work has been enqueued.
+ * Stage i lasted from event i to event i+1.  The two probe events bracket ONE launch of the kernel
+ * the low-rank stage spends most of its time in (ENERGY_TOPK with the subspace iteration: the fp64
+ * product Y^T G of the first iteration, of covspec_probe_launches() equal launches; otherwise they are
+ * recorded back to back).  Same results, arguments and errors as covspec_reduce.
  */
 enum {
   COVSPEC_STAGE_QUERY_SIDE = 0,       /* weight transposes, e(q) = q Wq, |e(q)|, folded query matrix    */
@@ -142,12 +145,21 @@ enum {
   COVSPEC_STAGE_KEEP = 8,             /* subspace energies and top-k, or ordering of the greedy picks    */
   COVSPEC_STAGE_GATHER = 9,           /* gather of the kept rows                                         */
   COVSPEC_STAGE_END = 10,
-  COVSPEC_NUM_STAGE_EVENTS = 11
+  COVSPEC_PROBE_BEGIN = 11,
+  COVSPEC_PROBE_END = 12,
+  COVSPEC_NUM_STAGE_EVENTS = 13
 };
 int covspec_reduce_staged(const covspec_params* p, const void* X, const void* hidden, const void* Q,
                           const void* Wq, const void* Wk, int32_t* idx_out, void* tokens_out,
                           void* workspace, size_t workspace_bytes, covspec_stream_t stream,
                           void* const* stage_events);
+
+/*
+ * Description of the probed launch for these parameters: number of equal launches per call (0 when
+ * nothing is probed) and, if non-NULL, its dimensions: the product is [rows x inner] * [inner x cols]
+ * per image in fp64 (2*rows*cols*inner flops per image).
+ */
+int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols, int32_t* inner);
 
 /* Static, NUL-terminated description of a status code. */
 const char* covspec_status_string(int status);

@@ -21,7 +21,7 @@ LR_ENERGY_TOPK, LR_GREEDY_RESIDUAL = 0, 1
 OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
 
 EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
-           "covspec_reduce", "covspec_reduce_staged", "covspec_status_string")
+           "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string")
 
 
 class CovspecParams(ctypes.Structure):
@@ -62,6 +62,8 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_reduce.argtypes = [pp] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
     lib.covspec_reduce_staged.restype = ctypes.c_int
     lib.covspec_reduce_staged.argtypes = [pp] + [vp] * 7 + [vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
+    lib.covspec_probe_launches.restype = ctypes.c_int
+    lib.covspec_probe_launches.argtypes = [pp] + [ctypes.POINTER(ctypes.c_int32)] * 3
     lib.covspec_status_string.restype = ctypes.c_char_p
     lib.covspec_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -192,8 +194,17 @@ def select(p: Params, X, s_fused, workspace=None):
 
 STAGES = ("query_side", "token_projection", "relevance", "activity", "fuse", "preselect", "gram", "lowrank",
           "keep", "gather")
-NUM_STAGE_EVENTS = len(STAGES) + 1
-JACOBI_MAX_SWEEPS = 30  # launches of the eigen-solve per call = this x (tournament rounds); mirrors eigen.hip
+PROBE_BEGIN = len(STAGES) + 1       # event indices of the probed launch
+PROBE_END = len(STAGES) + 2
+NUM_STAGE_EVENTS = len(STAGES) + 3
+
+
+def probe_launches(p: Params):
+    """covspec_probe_launches: (equal launches per call, rows, cols, inner) of the probed fp64 product."""
+    cs = p.c_struct()
+    r, c, k = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    n = load_library().covspec_probe_launches(ctypes.byref(cs), ctypes.byref(r), ctypes.byref(c), ctypes.byref(k))
+    return n, r.value, c.value, k.value
 
 
 def reduce(p: Params, X, hidden, Q, Wq, Wk, workspace=None, idx_out=None, tokens_out=None, stage_events=None):

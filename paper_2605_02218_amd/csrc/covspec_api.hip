@@ -283,6 +283,7 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
   else if (q.lr == COVSPEC_LR_GREEDY_RESIDUAL) HIPCHK(launch_gemm64_bf16(g, st));
   else HIPCHK(launch_gemm_nt(g, DT_BF16, st));
 
+  bool probed = false;
   if (q.lr == COVSPEC_LR_ENERGY_TOPK) {
     float* c = c_out ? c_out : at<float>(ws, q.c);
     marks.mark(COVSPEC_STAGE_LOWRANK);
@@ -292,7 +293,9 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
       int* ok = at<int>(ws, q.ok);
       const double* Ut = nullptr;
       HIPCHK(launch_subspace_eigen(A, q.B, q.M, q.nP, q.r, q.P, kSubspaceIters, at<void>(ws, q.sub), at<void>(ws, q.ctl),
-                                   at<double>(ws, q.lam), ok, &Ut, st));
+                                   at<double>(ws, q.lam), ok, &Ut, marks.ev ? marks.ev[COVSPEC_PROBE_BEGIN] : nullptr,
+                                   marks.ev ? marks.ev[COVSPEC_PROBE_END] : nullptr, st));
+      probed = true;
       HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, st));
       marks.mark(COVSPEC_STAGE_KEEP);
       HIPCHK(launch_subspace_energy(Ut, q.B, q.P, q.M, q.nP, (long)q.P * q.nP, q.r, at<double>(ws, q.lam), c, ok, 1, st));
@@ -310,6 +313,10 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
     HIPCHK(launch_greedy(A, q.B, q.M, q.nP, q.k, at<double>(ws, q.Lt), order, resid, st));
     marks.mark(COVSPEC_STAGE_KEEP);
     HIPCHK(launch_greedy_finish(order, idxm, q.B, q.M, q.k, idx_out, pick_order_out, st));
+  }
+  if (!probed) {
+    marks.mark(COVSPEC_PROBE_BEGIN);
+    marks.mark(COVSPEC_PROBE_END);
   }
   return COVSPEC_OK;
 }
@@ -394,6 +401,16 @@ int covspec_reduce_staged(const covspec_params* p, const void* X, const void* hi
   marks.ev = (hipEvent_t*)stage_events;
   marks.st = (hipStream_t)stream;
   return reduce_impl(p, X, hidden, Q, Wq, Wk, idx_out, tokens_out, workspace, workspace_bytes, (hipStream_t)stream, marks);
+}
+
+int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols, int32_t* inner) {
+  Plan pl;
+  if (make_plan(p, &pl) != COVSPEC_OK) return 0;
+  if (pl.lr != COVSPEC_LR_ENERGY_TOPK || pl.P <= 0) return 0;
+  if (rows) *rows = pl.P;
+  if (cols) *cols = pl.nP;
+  if (inner) *inner = pl.nP;
+  return subspace_product_launches(kSubspaceIters);
 }
 
 const char* covspec_status_string(int status) {

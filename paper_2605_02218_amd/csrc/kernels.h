@@ -124,8 +124,12 @@ hipError_t launch_subspace_energy(const double* A, int B, int rows, int n, int p
 // theta_k u_k^T with the r longest converged.  jacobi_ctl / jacobi_len2 as for launch_jacobi_eigen.
 int subspace_block(int n, int r);
 size_t subspace_workspace_bytes(int B, int n, int nP, int P);
+// probe_begin / probe_end (optional): recorded around the first of the subspace_product_launches(iters)
+// equal launches of the product Yt G (P x nP x nP per image).
+int subspace_product_launches(int iters);
 hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, void* ws, void* jacobi_ctl,
-                                 double* jacobi_len2, int* ok, const double** ut, hipStream_t stream);
+                                 double* jacobi_len2, int* ok, const double** ut, hipEvent_t probe_begin, hipEvent_t probe_end,
+                                 hipStream_t stream);
 
 // ---------------------------------------------------------------- greedy.hip
 // Greedy residual picks (variant): pivoted Cholesky of G[b] (fp64, pitch nP).  Lt is scratch [B][k][nP] fp64.

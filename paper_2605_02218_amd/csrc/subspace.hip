@@ -175,8 +175,11 @@ size_t subspace_workspace_bytes(int B, int n, int nP, int P) {
 
 // Runs the iteration on G[b] (n x n, pitch nP, untouched).  On return, for images with ok[b] = 1, rows
 // k of (*ut)[b] (P rows, pitch nP, inside ws) are theta_k u_k^T with the r longest rows converged.
+int subspace_product_launches(int iters) { return iters + 2; }   // start block, one per iteration, residuals
+
 hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, void* ws_, void* jacobi_ctl,
-                                 double* jacobi_len2, int* ok, const double** ut, hipStream_t st) {
+                                 double* jacobi_len2, int* ok, const double** ut, hipEvent_t probe_begin, hipEvent_t probe_end,
+                                 hipStream_t st) {
   if (P <= 0 || P % NB != 0 || P > n || P > 4096) return hipErrorInvalidValue;
   char* ws = (char*)ws_;
   const size_t blk = (size_t)B * P * nP * 8;
@@ -233,6 +236,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
 
   // start block: Omega G
   hipLaunchKernelGGL(omega_kernel, dim3((unsigned)(((long)P * nP + 255) / 256)), dim3(256), 0, st, Om, P, n, nP);
+  if (probe_begin && (e = hipEventRecord(probe_begin, st)) != hipSuccess) return e;
   {
     GemmArgs g;
     g.A = Om; g.B = G; g.C = Yt; g.M = P; g.N = nP; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = nP;
@@ -240,6 +244,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     g.epilogue = EPI_STORE_F64;
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
   }
+  if (probe_end && (e = hipEventRecord(probe_end, st)) != hipSuccess) return e;
   double* cur = Yt;
   double* oth = Zt;
   for (int it = 0; it < iters; ++it) {
