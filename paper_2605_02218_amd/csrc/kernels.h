@@ -33,6 +33,7 @@ struct GemmArgs {
   long gstrideA = 0, gstrideB = 0;
   int epilogue = EPI_STORE_F32;
   // fp64 kernel only:
+  bool lower_only = false;                     // tiles entirely above the diagonal of C are not computed
   bool transB = false;                         // B is stored [K][N] (row pitch ldb), i.e. C = A * B
   const int* skip = nullptr;                   // per outer batch: the work is skipped when skip[b] == skip_if
   int skip_if = 1;

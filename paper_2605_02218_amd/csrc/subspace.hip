@@ -24,6 +24,7 @@ namespace {
 
 constexpr int NB = 64;        // panel width of Cholesky / substitution
 constexpr int NBP = NB + 1;   // LDS pitch
+constexpr size_t kCholLds = (size_t)(2 * NB * NBP + NB) * sizeof(double);
 
 __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -34,93 +35,182 @@ __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
   om[i] = (c < n) ? ((h & 1u) ? 1.0 : -1.0) : 0.0;
 }
 
-// in-LDS Cholesky of a 64x64 SPD block held in a[NB][NBP] (lower triangle valid on return), 256 threads
-__device__ void potrf64_lds(double* a, double floor_) {
-  const int tid = threadIdx.x;
-  for (int k = 0; k < NB; ++k) {
-    if (tid == 0) a[k * NBP + k] = sqrt(fmax(a[k * NBP + k], floor_));
-    __syncthreads();
-    const double d = a[k * NBP + k];
-    if (tid > k && tid < NB) a[tid * NBP + k] /= d;
-    __syncthreads();
-    // trailing update of the lower triangle: (i, j), k < j <= i < 64
-    const int m = NB - 1 - k;                 // remaining order
-    for (int e = tid; e < m * m; e += 256) {
-      const int i = k + 1 + e / m, j = k + 1 + e % m;
-      if (j <= i) a[i * NBP + j] -= a[i * NBP + k] * a[j * NBP + k];
-    }
-    __syncthreads();
-  }
-}
-
-// Step J of the blocked Cholesky of S[b] (P x P, pitch P): every workgroup factors the diagonal block
-// S[J,J] in LDS (redundantly - it is small), workgroup 0 of an image stores the factor in D[b][J], and
-// each thread solves one row of the panel below:  X L_JJ^T = S[I,J]  (in place).
-__global__ __launch_bounds__(256) void chol_step_kernel(double* __restrict__ S, double* __restrict__ D, int P, int J,
-                                                         int wg_per_image, const int* __restrict__ skip) {
-  __shared__ double a[NB * NBP];
-  const int b = blockIdx.x / wg_per_image, w = blockIdx.x - b * wg_per_image;
+// Cholesky factorisation S[b] = L L^T (P x P, pitch P, P % 64 == 0; only the lower triangle is read), one
+// 512-thread workgroup per image, right-looking over 64-wide panels:
+//   diagonal block: factored in LDS, then inverted in LDS; the inverse goes to Dinv[b][J] (64 x 64);
+//   panel below:    X = S[I,J] inv(L_JJ)^T on the MFMA, in place (these blocks are L[I,J]);
+//   trailing part:  S[I,I'] -= X_I X_I'^T for I' <= I on the MFMA, 16 x 64 units dealt round-robin to the waves.
+// On return the strictly-lower blocks of S hold L; its diagonal blocks are represented by their inverses.
+// Pivots are floored at 1e-28 * trace(first block) so that a numerically rank-deficient block cannot
+// produce NaNs (the residual check afterwards decides whether the result is usable).
+// Dynamic LDS: 2 * 64 * 65 doubles + 64 doubles.
+__global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, const int* __restrict__ skip) {
+  extern __shared__ double lds[];
+  double* a = lds;                  // [64][65] diagonal block -> its factor
+  double* inv = lds + NB * NBP;     // [64][65] inverse of the factor
+  double* colk = inv + NB * NBP;    // [64] current column of the factor
+  const int b = blockIdx.x;
   if (skip && skip[b]) return;
   double* Sb = S + (long)b * P * P;
-  const int tid = threadIdx.x;
-  const int j0 = J * NB;
-  double tr = 0.0;
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e >> 6, j = e & 63;
-    a[i * NBP + j] = Sb[(long)(j0 + i) * P + j0 + j];
-  }
-  __syncthreads();
-  for (int i = 0; i < NB; ++i) tr += a[i * NBP + i];          // same value in every thread
-  potrf64_lds(a, 1e-300 + 1e-28 * tr);
-  if (w == 0) {
-    double* Db = D + ((long)b * (P / NB) + J) * NB * NB;
-    for (int e = tid; e < NB * NB; e += 256) {
+  const int nblk = P / NB;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i16 = lane & 15, kq = lane >> 4;
+  double floor_ = 0.0;
+
+  for (int J = 0; J < nblk; ++J) {
+    const int j0 = J * NB;
+    for (int e = tid; e < NB * NB; e += 512) {
       const int i = e >> 6, j = e & 63;
-      Db[e] = (j <= i) ? a[i * NBP + j] : 0.0;
+      a[i * NBP + j] = (j <= i) ? Sb[(long)(j0 + i) * P + j0 + j] : 0.0;
     }
-  }
-  const int row = (J + 1) * NB + w * 256 + tid;
-  if (row < P) {
-    double* x = Sb + (long)row * P + j0;
-    double v[NB];
-#pragma unroll
-    for (int k = 0; k < NB; ++k) v[k] = x[k];
-#pragma unroll
+    __syncthreads();
+    if (J == 0) {
+      double tr = 0.0;
+      for (int i = 0; i < NB; ++i) tr += a[i * NBP + i];   // same value in every thread
+      floor_ = 1e-300 + 1e-28 * tr;
+    }
+    // ---- factor the diagonal block
     for (int k = 0; k < NB; ++k) {
-      double s = v[k];
-#pragma unroll
-      for (int m = 0; m < k; ++m) s -= v[m] * a[k * NBP + m];
-      v[k] = s / a[k * NBP + k];
+      if (tid < NB) {   // wave 0: all its reads are issued before its writes
+        const double akk = a[k * NBP + k], aik = a[tid * NBP + k];
+        const double d = sqrt(fmax(akk, floor_));
+        const double val = (tid == k) ? d : aik / d;
+        if (tid >= k) a[tid * NBP + k] = val;
+        colk[tid] = (tid > k) ? val : 0.0;
+      }
+      __syncthreads();
+      {
+        const int i = k + 1 + (tid >> 3);
+        if (i < NB) {
+          const double ci = colk[i];
+          for (int j = k + 1 + (tid & 7); j <= i; j += 8) a[i * NBP + j] -= ci * colk[j];
+        }
+      }
+      __syncthreads();
     }
+    // ---- inv = a^-1 (lower triangular): column j by the 8 threads tid/8 == j, forward substitution
+    {
+      const int j = tid >> 3, part = tid & 7;
+      for (int i = 0; i < NB; ++i) {
+        double s_ = 0.0;
+        for (int m = j + part; m < i; m += 8) s_ = fma(a[i * NBP + m], inv[m * NBP + j], s_);
+        s_ += __shfl_xor(s_, 1, 64);
+        s_ += __shfl_xor(s_, 2, 64);
+        s_ += __shfl_xor(s_, 4, 64);
+        if (part == 0) inv[i * NBP + j] = (i < j) ? 0.0 : (((i == j) ? 1.0 : 0.0) - s_) / a[i * NBP + i];
+        __syncthreads();
+      }
+    }
+    {
+      double* Db = Dinv + ((long)b * nblk + J) * NB * NB;
+      for (int e = tid; e < NB * NB; e += 512) Db[e] = inv[(e >> 6) * NBP + (e & 63)];
+    }
+    // ---- panel: X = S[I,J] inv^T, 16-row tiles dealt to the waves
+    const int below = P - j0 - NB;
+    for (int t = w; t < below / 16; t += 8) {
+      const long rb = j0 + NB + 16 * t;
+      f64x4_t f[4], out[4];
 #pragma unroll
-    for (int k = 0; k < NB; ++k) x[k] = v[k];
+      for (int c = 0; c < 4; ++c) f[c] = *(const f64x4_t*)(Sb + (rb + i16) * P + j0 + 16 * c + 4 * kq);
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        out[y] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj)
+            out[y] = __builtin_amdgcn_mfma_f64_16x16x4f64(f[c][jj], inv[(16 * y + i16) * NBP + 16 * c + 4 * kq + jj], out[y], 0, 0, 0);
+      }
+#pragma unroll
+      for (int y = 0; y < 4; ++y)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Sb[(rb + 4 * v + kq) * P + j0 + 16 * y + i16] = out[y][v];
+    }
+    __syncthreads();
+    // ---- trailing update, unit = 16 rows of block I x the 64 columns of block I' <= I
+    {
+      const int nb = below / NB;
+      int cnt = 0;
+      for (int I = 0; I < nb; ++I)
+        for (int I2 = 0; I2 <= I; ++I2)
+          for (int q = 0; q < 4; ++q, ++cnt) {
+            if ((cnt & 7) != w) continue;
+            const long ra = j0 + NB + (long)I * NB + 16 * q;
+            const long rc = j0 + NB + (long)I2 * NB;
+            f64x4_t acc[4];
+#pragma unroll
+            for (int y = 0; y < 4; ++y) acc[y] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const f64x4_t fa = *(const f64x4_t*)(Sb + (ra + i16) * P + j0 + 16 * c + 4 * kq);
+#pragma unroll
+              for (int y = 0; y < 4; ++y) {
+                const f64x4_t fb = *(const f64x4_t*)(Sb + (rc + 16 * y + i16) * P + j0 + 16 * c + 4 * kq);
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) acc[y] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[jj], fb[jj], acc[y], 0, 0, 0);
+              }
+            }
+#pragma unroll
+            for (int y = 0; y < 4; ++y)
+#pragma unroll
+              for (int v = 0; v < 4; ++v) Sb[(ra + 4 * v + kq) * P + rc + 16 * y + i16] -= acc[y][v];
+          }
+    }
+    __syncthreads();
   }
 }
 
-// Yt[b][bi*64 .. +63][:] <- D[b][bi]^-1 Yt[...]: one thread per column, forward substitution
-__global__ __launch_bounds__(256) void solve64_kernel(double* __restrict__ Yt, const double* __restrict__ D, int P, int nP,
-                                                       int bi, int wg_per_image, const int* __restrict__ skip) {
-  __shared__ double a[NB * NBP];
-  const int b = blockIdx.x / wg_per_image, w = blockIdx.x - b * wg_per_image;
+// Yt[b] <- L^-1 Yt[b] (P x nP, pitch nP) by blocked forward substitution with the factor chol_kernel left
+// in S (strictly-lower blocks) and Dinv (inverted diagonal blocks).  Columns are independent: each wave
+// owns 16 of them and never reads what another wave writes, so the whole solve is one launch.
+//   for block row bi:  T = Yt[bi] - sum_{K<bi} L[bi,K] Yt[K];   Yt[bi] = inv(L_bibi) T
+// T comes out of the MFMA in exactly the layout its B operand wants (lane = column, register = k), so the
+// second product takes the accumulator registers as they are.
+__global__ __launch_bounds__(256) void trsm_kernel(double* Yt, const double* __restrict__ S, const double* __restrict__ Dinv,
+                                                    int P, int nP, int wg_per_image, const int* __restrict__ skip) {
+  const int b = blockIdx.x / wg_per_image, cw = blockIdx.x - b * wg_per_image;
   if (skip && skip[b]) return;
-  const double* Db = D + ((long)b * (P / NB) + bi) * NB * NB;
-  for (int e = threadIdx.x; e < NB * NB; e += 256) a[(e >> 6) * NBP + (e & 63)] = Db[e];
-  __syncthreads();
-  const int col = w * 256 + threadIdx.x;
-  if (col >= nP) return;
-  double* y = Yt + ((long)b * P + (long)bi * NB) * nP + col;
-  double v[NB];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, i16 = lane & 15, kq = lane >> 4;
+  const int col = cw * 64 + w * 16 + i16;    // nP % 64 == 0, so every column exists
+  const int nblk = P / NB;
+  double* Yb = Yt + (long)b * P * nP;
+  const double* Lb = S + (long)b * P * P;
+  for (int bi = 0; bi < nblk; ++bi) {
+    f64x4_t acc[4];
 #pragma unroll
-  for (int k = 0; k < NB; ++k) v[k] = y[(long)k * nP];
+    for (int x = 0; x < 4; ++x) acc[x] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+    for (int kk = 0; kk < bi * NB; kk += 16) {
+      f64x4_t fa[4];
+      double fb[4];
 #pragma unroll
-  for (int k = 0; k < NB; ++k) {
-    double s = v[k];
+      for (int x = 0; x < 4; ++x) fa[x] = *(const f64x4_t*)(Lb + (long)(bi * NB + 16 * x + i16) * P + kk + 4 * kq);
 #pragma unroll
-    for (int m = 0; m < k; ++m) s -= a[k * NBP + m] * v[m];
-    v[k] = s / a[k * NBP + k];
+      for (int jj = 0; jj < 4; ++jj) fb[jj] = Yb[(long)(kk + 4 * kq + jj) * nP + col];
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[x][jj], fb[jj], acc[x], 0, 0, 0);
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[x][v] = Yb[(long)(bi * NB + 16 * x + 4 * v + kq) * nP + col] - acc[x][v];
+    const double* Db = Dinv + ((long)b * nblk + bi) * NB * NB;
+    f64x4_t out[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      out[a] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)   // this step contracts k = 16x + 4v + kq, the row acc[x][v] holds in this lane
+          out[a] = __builtin_amdgcn_mfma_f64_16x16x4f64(Db[(16 * a + i16) * NB + 16 * x + 4 * v + kq], acc[x][v], out[a], 0, 0, 0);
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Yb[(long)(bi * NB + 16 * a + 4 * v + kq) * nP + col] = out[a][v];
+    __threadfence_block();   // the rows just written are B operands of the next block rows
   }
-#pragma unroll
-  for (int k = 0; k < NB; ++k) y[(long)k * nP] = v[k];
 }
 
 // Residual check of the r dominant Ritz pairs.  Ut rows are theta_k u_k^T, Rt = Ut G.  ok[b] = 1 when
@@ -180,7 +270,16 @@ int subspace_product_launches(int iters) { return iters + 2; }   // start block,
 hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, void* ws_, void* jacobi_ctl,
                                  double* jacobi_len2, int* ok, const double** ut, hipEvent_t probe_begin, hipEvent_t probe_end,
                                  hipStream_t st) {
-  if (P <= 0 || P % NB != 0 || P > n || P > 4096) return hipErrorInvalidValue;
+  hipError_t e0;
+  if (P <= 0 || P % NB != 0 || P > n || P > 4096 || nP % NB != 0) return hipErrorInvalidValue;
+  {
+    static bool raised = false;
+    if (!raised) {
+      if ((e0 = hipFuncSetAttribute((const void*)chol_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kCholLds)) != hipSuccess)
+        return e0;
+      raised = true;
+    }
+  }
   char* ws = (char*)ws_;
   const size_t blk = (size_t)B * P * nP * 8;
   double* Yt = (double*)ws;                 // after the call: Ut
@@ -205,32 +304,11 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     g.A = X; g.B = X; g.C = S; g.M = P; g.N = P; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = P;
     g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)P * nP; g.strideC = (long)P * P;
     g.epilogue = EPI_STORE_F64;
+    g.lower_only = true;
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
-    for (int J = 0; J < nblk; ++J) {
-      const int below = P - (J + 1) * NB;
-      const int wgs = below > 0 ? (below + 255) / 256 : 1;
-      hipLaunchKernelGGL(chol_step_kernel, dim3((unsigned)(B * wgs)), dim3(256), 0, st, S, D, P, J, wgs, (const int*)nullptr);
-      if (below > 0) {
-        GemmArgs u;   // trailing block -= panel panel^T
-        u.A = S + (long)(J + 1) * NB * P + (long)J * NB; u.B = u.A; u.C = S + (long)(J + 1) * NB * P + (long)(J + 1) * NB;
-        u.M = below; u.N = below; u.K = NB; u.lda = P; u.ldb = P; u.ldc = P;
-        u.batch = B; u.strideA = (long)P * P; u.strideB = (long)P * P; u.strideC = (long)P * P;
-        u.epilogue = EPI_SUB_F64;
-        if ((e = launch_gemm64_nt(u, true, true, st)) != hipSuccess) return e;
-      }
-    }
-    const int cw = (nP + 255) / 256;
-    for (int bi = 0; bi < nblk; ++bi) {
-      if (bi > 0) {
-        GemmArgs u;   // X[bi] -= L[bi, 0:bi] X[0:bi]
-        u.A = S + (long)bi * NB * P; u.B = X; u.C = X + (long)bi * NB * nP;
-        u.M = NB; u.N = nP; u.K = bi * NB; u.lda = P; u.ldb = nP; u.ldc = nP; u.transB = true;
-        u.batch = B; u.strideA = (long)P * P; u.strideB = (long)P * nP; u.strideC = (long)P * nP;
-        u.epilogue = EPI_SUB_F64;
-        if ((e = launch_gemm64_nt(u, true, true, st)) != hipSuccess) return e;
-      }
-      hipLaunchKernelGGL(solve64_kernel, dim3((unsigned)(B * cw)), dim3(256), 0, st, X, D, P, nP, bi, cw, (const int*)nullptr);
-    }
+    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), kCholLds, st, S, D, P, (const int*)nullptr);
+    hipLaunchKernelGGL(trsm_kernel, dim3((unsigned)(B * (nP / NB))), dim3(256), 0, st, X, (const double*)S, (const double*)D, P, nP,
+                       nP / NB, (const int*)nullptr);
     return hipGetLastError();
   };
 
