@@ -9,7 +9,10 @@
 // |row k| = lambda_k and c_i = sum over the r longest rows of A_ki^2 / |row k|.
 //
 // Parallel form: rows are grouped in super-blocks of 32; a round-robin tournament pairs the
-// super-blocks, one launch per tournament round, one 256-thread workgroup per pair.  The workgroup
+// super-blocks, one 256-thread workgroup per pair and image.  The whole solve is ONE launch: the
+// workgroups of an image meet at a barrier in global memory after every tournament round (all of
+// them are resident at once - the launcher sizes the grid to the occupancy and takes the images in
+// chunks if need be - and every wait is bounded by a wall-clock limit).  In a round the workgroup
 //   1. forms the 64x64 Gram H = P P^T of its 64 rows with v_mfma_f64_16x16x4 (waves split the
 //      columns, partial tiles are summed in LDS; the A and B operand of a diagonal tile are the
 //      same registers),
@@ -28,9 +31,13 @@ namespace covspec {
 
 namespace {
 
+constexpr int kMaxSweeps = 30;
+
 struct JacobiCtl {
-  unsigned long long maxoff;  // bits of the largest admixture weight seen in the current sweep (see below)
+  unsigned long long maxoff[kMaxSweeps + 2];  // per sweep: bits of the largest admixture weight seen (see below)
+  unsigned int arrived;       // barrier counter of the image's workgroups (monotonic)
   int done;
+  int failed;                 // a barrier wait ran into its time limit: the result is invalid (rows are set to NaN)
   int sweeps;
   double floor2;              // rows with squared norm below this are treated as zero
   double long2;               // squared length of the r-th longest row after the previous sweep
@@ -46,7 +53,7 @@ struct JacobiCtl {
 // measures it also reduces it, so 3e-7 leaves the energies converged to well below their last bit.
 constexpr double kRotEps = 1e-15;   // rotations below this relative size are skipped
 constexpr double kConvTol = 3e-7;
-constexpr int kMaxSweeps = 30;
+constexpr long long kBarrierLimitTicks = 200000000LL;   // 2 s of the 100 MHz wall clock per barrier wait
 
 __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restrict__ A, int n, int nP, JacobiCtl* ctl,
                                                              const int* __restrict__ preset_done) {
@@ -60,36 +67,14 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restri
   __syncthreads();
   if (threadIdx.x == 0) {
     double t = red[0] + red[1] + red[2] + red[3];
-    ctl[b].maxoff = 0ull;
+    for (int k = 0; k < kMaxSweeps + 2; ++k) ctl[b].maxoff[k] = 0ull;
+    ctl[b].arrived = 0u;
     ctl[b].done = preset_done ? preset_done[b] : 0;
+    ctl[b].failed = 0;
     ctl[b].sweeps = 0;
     double f = 1e-13 * t;
     ctl[b].floor2 = f * f;
     ctl[b].long2 = 0.0;       // first sweep: every row counts
-  }
-}
-
-// End of a sweep, one workgroup per image: decide convergence, then find the squared length of the r-th
-// longest row from the lengths the round kernels left behind.
-__global__ __launch_bounds__(256) void jacobi_check_kernel(const double* __restrict__ len2g, int n, int nP, int r, JacobiCtl* ctl) {
-  __shared__ double len2[4096];
-  const int b = blockIdx.x;
-  if (ctl[b].done) return;
-  for (int k = threadIdx.x; k < n; k += 256) len2[k] = len2g[(long)b * nP + k];
-  __syncthreads();
-  for (int k = threadIdx.x; k < n; k += 256) {
-    const double v = len2[k];
-    int rank = 0;
-    for (int j = 0; j < n; ++j) {
-      const double u = len2[j];
-      rank += (u > v || (u == v && j < k)) ? 1 : 0;
-    }
-    if (rank == r - 1) ctl[b].long2 = v * (1.0 - 1e-12);
-  }
-  if (threadIdx.x == 0) {
-    ctl[b].sweeps += 1;
-    if (__longlong_as_double((long long)ctl[b].maxoff) < kConvTol) ctl[b].done = 1;
-    ctl[b].maxoff = 0ull;
   }
 }
 
@@ -103,22 +88,48 @@ constexpr int SB = 32;        // rows per super-block
 constexpr int PR = 2 * SB;    // rows per workgroup
 constexpr int HP = PR + 1;    // LDS pitch (doubles)
 
-__global__ __launch_bounds__(256, 2) void jacobi_round_kernel(double* __restrict__ A, int nP, int nsb, int round, JacobiCtl* ctl,
-                                                              double* __restrict__ len2) {
-  __shared__ double Hs[PR * HP];
-  __shared__ double Ws[PR * HP];
-  __shared__ double cs_c[32], cs_s[32];
-  __shared__ int any_rot;
+// Barrier over the `npairs` workgroups of one image: `target` is the value cb->arrived reaches when all of
+// them have arrived (the counter only grows).  Every thread's earlier global writes are visible to every
+// thread of the image behind it.  Returns false when the wait hit its time limit or another workgroup of
+// the image reported that (cb->failed); the caller then gives up on the image.
+__device__ __forceinline__ bool image_barrier(JacobiCtl* cb, unsigned int target, int* s_flag) {
+  __threadfence();   // release at device scope (write back what the other XCDs' L2s cannot see)
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int ok = 1;
+    __hip_atomic_fetch_add(&cb->arrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    const long long t0 = wall_clock64();
+    while (__hip_atomic_load(&cb->arrived, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (__hip_atomic_load(&cb->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
+          wall_clock64() - t0 > kBarrierLimitTicks) {
+        ok = 0;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(4);
+    }
+    if (!ok) __hip_atomic_store(&cb->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_flag = ok;
+  }
+  __syncthreads();
+  __threadfence();   // acquire: no stale lines when the other workgroups' rows are read
+  return *s_flag != 0;
+}
 
-  const int npairs = nsb >> 1;
-  const int b = blockIdx.x / npairs, pr = blockIdx.x - b * npairs;
-  if (ctl[b].done) return;
-  int I, J;
-  tournament_pair(nsb, round, pr, I, J);
+// LDS of the solve kernel (file scope: shared by the kernel and the visit function below).
+__shared__ double Hs[PR * HP];
+__shared__ double Ws[PR * HP];
+__shared__ double cs_c[32], cs_s[32];
+__shared__ int any_rot;
+__shared__ int s_flag;
+
+// One visit of a pair of super-blocks (I, J) of the image whose matrix starts at Ab (steps 1-3 of the header).
+// `full`: the rows inside each super-block are paired too (first round of a sweep).  Returns the largest
+// admixture weight seen (valid in wave 0).  Kept out of line so that the registers of the three phases are
+// allocated for this function alone and not held across the sweep loop of the caller.
+__device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, int I, int J, bool full, double floor2, double long2) {
   const int tid = threadIdx.x, l = tid & 63, w = tid >> 6, i16 = l & 15, kq = l >> 4;
-  double* Ab = A + (long)b * nP * nP;
-  auto grow = [&](int i) -> long { return (i < SB) ? (long)I * SB + i : (long)J * SB + (i - SB); };
   const int nchunks = nP >> 4;
+  auto grow = [&](int i) -> int { return (i < SB) ? I * SB + i : J * SB + (i - SB); };   // nP <= 4096: offsets fit an int
 
   // ---- 1. H = P P^T : wave w takes column chunks w, w+4, ...; upper tiles only
   for (int e = tid; e < PR * HP; e += 256) { Hs[e] = 0.0; Ws[e] = 0.0; }
@@ -127,22 +138,35 @@ __global__ __launch_bounds__(256, 2) void jacobi_round_kernel(double* __restrict
     f64x4_t acc[10];
 #pragma unroll
     for (int t = 0; t < 10; ++t) acc[t] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
-    const double* rp[4];
+    int rp[4];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) rp[x] = Ab + grow(16 * x + i16) * nP + 4 * kq;
+    for (int x = 0; x < 4; ++x) rp[x] = grow(16 * x + i16) * nP + 4 * kq;
+    // the rows were last written by other workgroups, so every load is a long trip: keep two chunks in flight
+    f64x4_t f0[4], f1[4], f2[4];
+    auto fetch = [&](f64x4_t* f, int c) {
+      if (c < nchunks) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) f[x] = *(const f64x4_t*)(Ab + rp[x] + 16 * c);
+      }
+    };
+#pragma unroll
+    for (int x = 0; x < 4; ++x) f0[x] = f1[x] = f2[x] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+    fetch(f0, w);
+    fetch(f1, w + 4);
+#pragma unroll 1
     for (int c = w; c < nchunks; c += 4) {
-      f64x4_t f[4];
-#pragma unroll
-      for (int x = 0; x < 4; ++x) f[x] = *(const f64x4_t*)(rp[x] + 16 * c);
+      fetch(f2, c + 8);
       int t = 0;
 #pragma unroll
       for (int x = 0; x < 4; ++x)
 #pragma unroll
         for (int y = x; y < 4; ++y) {
 #pragma unroll
-          for (int k = 0; k < 4; ++k) acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(f[x][k], f[y][k], acc[t], 0, 0, 0);
+          for (int k = 0; k < 4; ++k) acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(f0[x][k], f0[y][k], acc[t], 0, 0, 0);
           ++t;
         }
+#pragma unroll
+      for (int x = 0; x < 4; ++x) { f0[x] = f1[x]; f1[x] = f2[x]; }
     }
     __syncthreads();  // zero fill visible
     for (int ww = 0; ww < 4; ++ww) {
@@ -172,32 +196,58 @@ __global__ __launch_bounds__(256, 2) void jacobi_round_kernel(double* __restrict
   // A round holds 32 disjoint rotations.  Phase A: 32 threads compute them.  Phase B: the 2x2 block of
   // H at (pair a, pair b) becomes R_a^T H_ab R_b and depends on nothing else, so all 1024 blocks (and the
   // column pairs of W) are updated in place in one pass between two barriers.
-  const double floor2 = ctl[b].floor2, long2 = ctl[b].long2;
-  const bool full = (round == 0);
+  // (floor2, long2: read at the top of the round)
   const int nrounds = full ? PR - 1 : SB;
   double meas2 = 0.0;   // largest squared admixture weight seen by this thread
-  auto pair_of = [&](int rd, int m, int& p, int& q) {
-    if (full) tournament_pair(PR, rd, m, p, q);
-    else { p = m; q = SB + ((m + rd) & (SB - 1)); }
+  // This thread's share of a step: column pair b2 (of H and W), H row pairs a0 + 8k, W rows a0 + 8k.
+  // The (p, q) of a pair is carried from step to step: circle method (p, q advance by one mod 63; pair 0
+  // keeps p = 63) when all 64 rows meet, else p = pair id and q walks cyclically over the second super-block.
+  const int b2 = tid & 31, a0 = tid >> 5;
+  int pb = full ? (b2 == 0 ? PR - 1 : b2) : b2;
+  int qb = full ? (b2 == 0 ? 0 : PR - 1 - b2) : SB + b2;
+  int pa[4], qa[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int m = a0 + 8 * k;
+    pa[k] = full ? (m == 0 ? PR - 1 : m) : m;
+    qa[k] = full ? (m == 0 ? 0 : PR - 1 - m) : SB + m;
+  }
+  auto advance = [&](int m, int& p_, int& q_) {
+    if (full) {
+      q_ = (q_ + 1 == PR - 1) ? 0 : q_ + 1;
+      if (m != 0) p_ = (p_ + 1 == PR - 1) ? 0 : p_ + 1;
+    } else {
+      q_ = SB + ((q_ + 1) & (SB - 1));
+    }
   };
+#pragma unroll 1
   for (int rd = 0; rd < nrounds; ++rd) {
-    if (tid < 32) {
-      int p, q;
-      pair_of(rd, tid, p, q);
-      const double al = Hs[p * HP + p], be = Hs[q * HP + q], ga = Hs[p * HP + q];
+    if (tid < 32) {   // pair id = tid = b2
+      const double al = Hs[pb * HP + pb], be = Hs[qb * HP + qb], ga = Hs[pb * HP + qb];
       double c = 1.0, s = 0.0;
       if (al > floor2 && be > floor2) {
         const double g2 = ga * ga, ab = al * be;
         const double hi = fmax(al, be), lo = fmin(al, be);
-        if (hi >= long2) {
-          const double rr = lo / hi;
-          meas2 = fmax(meas2, (g2 / ab) * rr * rr);
+        if (hi >= long2) {   // weight^2 = (g2 / ab) (lo / hi)^2 = g2 lo / hi^3; a few digits are enough
+          const double rh = __builtin_amdgcn_rcp(hi);
+          meas2 = fmax(meas2, g2 * lo * rh * rh * rh);
         }
         if (g2 > (kRotEps * kRotEps) * ab) {
+          // hardware reciprocal / reciprocal square root estimates, refined by Newton steps: the angle needs
+          // few digits, but c^2 + s^2 = 1 has to hold to rounding, so c gets two steps
           const double de = be - al;
-          const double rho = sqrt(de * de + 4.0 * g2);
-          const double t = 2.0 * ga / (de + copysign(rho, de));
-          c = 1.0 / sqrt(1.0 + t * t);
+          const double x = fma(de, de, 4.0 * g2);
+          const double rs = __builtin_amdgcn_rsq(x);
+          double rho = x * rs;
+          rho = fma(0.5 * rs, fma(-rho, rho, x), rho);
+          const double den = de + copysign(rho, de);
+          double rd_ = __builtin_amdgcn_rcp(den);
+          rd_ = rd_ * fma(-den, rd_, 2.0);
+          const double t = 2.0 * ga * rd_;
+          const double u = fma(t, t, 1.0);
+          c = __builtin_amdgcn_rsq(u);
+          c = c * fma(-0.5 * u, c * c, 1.5);
+          c = c * fma(-0.5 * u, c * c, 1.5);
           s = c * t;
           any_rot = 1;
         }
@@ -206,48 +256,69 @@ __global__ __launch_bounds__(256, 2) void jacobi_round_kernel(double* __restrict
       cs_s[tid] = s;
     }
     __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {   // H blocks (a, b2)
-      const int e = tid + 256 * k, a = e >> 5, b2 = e & 31;
-      const double ca = cs_c[a], sa = cs_s[a], cb = cs_c[b2], sb = cs_s[b2];
-      if (sa != 0.0 || sb != 0.0) {
-        int pa, qa, pb, qb;
-        pair_of(rd, a, pa, qa);
-        pair_of(rd, b2, pb, qb);
-        const double h00 = Hs[pa * HP + pb], h01 = Hs[pa * HP + qb], h10 = Hs[qa * HP + pb], h11 = Hs[qa * HP + qb];
-        const double t00 = ca * h00 - sa * h10, t01 = ca * h01 - sa * h11;   // R_a^T H
-        const double t10 = sa * h00 + ca * h10, t11 = sa * h01 + ca * h11;
-        Hs[pa * HP + pb] = cb * t00 - sb * t01;                               // (.) R_b
-        Hs[pa * HP + qb] = sb * t00 + cb * t01;
-        Hs[qa * HP + pb] = cb * t10 - sb * t11;
-        Hs[qa * HP + qb] = sb * t10 + cb * t11;
-      }
-    }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {   // W column pairs (row i, pair b2)
-      const int e = tid + 256 * k, i = e >> 5, b2 = e & 31;
+    {
+      // all loads first, then the arithmetic, then all stores: the blocks are disjoint, which the compiler
+      // cannot know, and it would otherwise wait out one LDS round trip per block
       const double cb = cs_c[b2], sb = cs_s[b2];
-      if (sb != 0.0) {
-        int pb, qb;
-        pair_of(rd, b2, pb, qb);
-        const double wp = Ws[i * HP + pb], wq = Ws[i * HP + qb];
-        Ws[i * HP + pb] = cb * wp - sb * wq;
-        Ws[i * HP + qb] = sb * wp + cb * wq;
+      double ca[4], sa[4], h00[4], h01[4], h10[4], h11[4], wp[8], wq[8];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        ca[k] = cs_c[a0 + 8 * k];
+        sa[k] = cs_s[a0 + 8 * k];
+        h00[k] = Hs[pa[k] * HP + pb];
+        h01[k] = Hs[pa[k] * HP + qb];
+        h10[k] = Hs[qa[k] * HP + pb];
+        h11[k] = Hs[qa[k] * HP + qb];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        wp[k] = Ws[(a0 + 8 * k) * HP + pb];
+        wq[k] = Ws[(a0 + 8 * k) * HP + qb];
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {   // H block (a0 + 8k, b2) <- R_a^T H R_b
+        const double t00 = ca[k] * h00[k] - sa[k] * h10[k], t01 = ca[k] * h01[k] - sa[k] * h11[k];
+        const double t10 = sa[k] * h00[k] + ca[k] * h10[k], t11 = sa[k] * h01[k] + ca[k] * h11[k];
+        h00[k] = cb * t00 - sb * t01;
+        h01[k] = sb * t00 + cb * t01;
+        h10[k] = cb * t10 - sb * t11;
+        h11[k] = sb * t10 + cb * t11;
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {   // W columns (pb, qb), row a0 + 8k
+        const double x0 = cb * wp[k] - sb * wq[k];
+        wq[k] = sb * wp[k] + cb * wq[k];
+        wp[k] = x0;
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        Hs[pa[k] * HP + pb] = h00[k];
+        Hs[pa[k] * HP + qb] = h01[k];
+        Hs[qa[k] * HP + pb] = h10[k];
+        Hs[qa[k] * HP + qb] = h11[k];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        Ws[(a0 + 8 * k) * HP + pb] = wp[k];
+        Ws[(a0 + 8 * k) * HP + qb] = wq[k];
       }
     }
+    advance(b2, pb, qb);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) advance(a0 + 8 * k, pa[k], qa[k]);
     __syncthreads();
   }
   // squared row lengths after this visit (the diagonal of the rotated Gram block)
-  if (tid < PR) len2[(long)b * nP + grow(tid)] = Hs[tid * HP + tid];
+  if (tid < PR) len2b[grow(tid)] = Hs[tid * HP + tid];
 
   // ---- 3. P <- W^T P  (skipped when every rotation of this pair was the identity)
   if (any_rot) {
-    double wa[4][16];
+    double wa[4][16];   // A operand of k-step t, tile a: W[4t + kq][16a + i16]
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
       for (int t = 0; t < 16; ++t) wa[a][t] = Ws[(4 * t + kq) * HP + 16 * a + i16];
-    long roff[16];
+    int roff[16];
 #pragma unroll
     for (int t = 0; t < 16; ++t) roff[t] = grow(4 * t + kq) * nP + i16;
     for (int c = w; c < nchunks; c += 4) {
@@ -268,8 +339,68 @@ __global__ __launch_bounds__(256, 2) void jacobi_round_kernel(double* __restrict
         for (int v = 0; v < 4; ++v) Ab[roff[4 * a + v] + 16 * c] = d[a][v];
     }
   }
-  meas2 = wave_max(meas2);   // only wave 0 holds non-zero values
-  if (tid == 0 && meas2 > 0.0) atomicMax(&ctl[b].maxoff, (unsigned long long)__double_as_longlong(sqrt(meas2)));
+  return wave_max(meas2);
+}
+
+// The whole solve of the images [img0, img0 + gridDim.x / (nsb/2)): workgroup (image b, slot pr) visits the
+// pair `pr` of every tournament round of every sweep; after a sweep, slot 0 decides convergence and
+// re-measures which rows are the r longest.  A and len2 are written and re-read by different workgroups
+// between barriers, hence no __restrict__.
+__global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, int nP, int nsb, int r, int img0, JacobiCtl* ctl,
+                                                              double* len2) {
+  const int npairs = nsb >> 1;
+  const int b = img0 + blockIdx.x / npairs, pr = blockIdx.x % npairs;
+  JacobiCtl* cb = ctl + b;
+  if (cb->done) return;   // set before the launch, so the same for every workgroup of the image
+  const int tid = threadIdx.x;
+  double* Ab = A + (long)b * nP * nP;
+  double* len2b = len2 + (long)b * nP;
+  const double floor2 = cb->floor2;   // written by the init kernel
+  unsigned int target = 0;
+  bool alive = true;
+
+#pragma unroll 1
+  for (int sweep = 0; sweep < kMaxSweeps && alive; ++sweep) {
+    const double long2 = __hip_atomic_load(&cb->long2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll 1
+    for (int round = 0; round < nsb - 1 && alive; ++round) {
+      int I, J;
+      tournament_pair(nsb, round, pr, I, J);
+      const double meas = jacobi_visit(Ab, len2b, nP, I, J, round == 0, floor2, long2);
+      if (tid == 0 && meas > 0.0) atomicMax(&cb->maxoff[sweep], (unsigned long long)__double_as_longlong(sqrt(meas)));
+      target += npairs;
+      alive = image_barrier(cb, target, &s_flag);
+    }
+    if (!alive) break;
+    // ---- end of the sweep: slot 0 decides convergence and finds the squared length of the r-th longest row
+    if (pr == 0) {
+      double* l2 = Hs;   // 4096 doubles fit
+      for (int k = tid; k < n; k += 256) l2[k] = len2b[k];
+      __syncthreads();
+      for (int k = tid; k < n; k += 256) {
+        const double v = l2[k];
+        int rank = 0;
+        for (int j = 0; j < n; ++j) {
+          const double u = l2[j];
+          rank += (u > v || (u == v && j < k)) ? 1 : 0;
+        }
+        if (rank == r - 1) __hip_atomic_store(&cb->long2, v * (1.0 - 1e-12), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (tid == 0) {
+        cb->sweeps = sweep + 1;
+        const unsigned long long m = __hip_atomic_load(&cb->maxoff[sweep], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__longlong_as_double((long long)m) < kConvTol) __hip_atomic_store(&cb->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    target += npairs;
+    alive = image_barrier(cb, target, &s_flag);
+    if (alive && __hip_atomic_load(&cb->done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+  }
+  if (!alive) {
+    // a wait ran out: poison this slot's share of the rows so that nothing downstream passes for a result
+    const double qnan = __longlong_as_double(0x7ff8000000000000LL);
+    for (long e = tid; e < (long)PR * nP; e += 256) Ab[(long)pr * PR * nP + e] = qnan;
+  }
 }
 
 // lam[b*rows + k] = |row k of A[b]| (A[b] starts at b*img_stride and has `rows` rows of `pitch`), one wave per row
@@ -325,18 +456,30 @@ __global__ __launch_bounds__(256) void energy_kernel(const double* __restrict__ 
 
 size_t jacobi_ctl_bytes(int B) { return sizeof(JacobiCtl) * (size_t)B; }
 int jacobi_pitch(int n) { return (n + PR - 1) / PR * PR; }
-int jacobi_launches(int n) { return kMaxSweeps * (jacobi_pitch(n) / SB - 1); }
 
 hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl_, double* len2, const int* preset_done,
                                hipStream_t st) {
   if (nP % 64 != 0 || n > nP || n > 4096 || r < 1 || r > n) return hipErrorInvalidValue;
   JacobiCtl* ctl = (JacobiCtl*)ctl_;
   const int nsb = nP / SB;  // even, since nP % 64 == 0
+  const int npairs = nsb / 2;
+  // every workgroup of a launch has to be resident (they wait for one another): grid <= occupancy x CUs
+  static int capacity = 0;
+  if (capacity == 0) {
+    int dev = 0, per_cu = 0, cus = 0;
+    hipError_t e;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, jacobi_solve_kernel, 256, 0)) != hipSuccess) return e;
+    if (per_cu < 1 || cus < 1) return hipErrorInvalidValue;
+    capacity = per_cu * cus;
+  }
+  if (npairs > capacity) return hipErrorInvalidValue;
+  const int chunk = capacity / npairs;   // images per launch
   hipLaunchKernelGGL(jacobi_init_kernel, dim3(B), dim3(256), 0, st, A, n, nP, ctl, preset_done);
-  for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
-    for (int round = 0; round < nsb - 1; ++round)
-      hipLaunchKernelGGL(jacobi_round_kernel, dim3((unsigned)(B * (nsb / 2))), dim3(256), 0, st, A, nP, nsb, round, ctl, len2);
-    hipLaunchKernelGGL(jacobi_check_kernel, dim3(B), dim3(256), 0, st, len2, n, nP, r, ctl);
+  for (int img0 = 0; img0 < B; img0 += chunk) {
+    const int nimg = B - img0 < chunk ? B - img0 : chunk;
+    hipLaunchKernelGGL(jacobi_solve_kernel, dim3((unsigned)(nimg * npairs)), dim3(256), 0, st, A, n, nP, nsb, r, img0, ctl, len2);
   }
   return hipGetLastError();
 }

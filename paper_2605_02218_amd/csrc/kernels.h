@@ -106,7 +106,6 @@ hipError_t launch_select_top(const float* scores, int B, int n, int m, const int
 // rows/cols >= n zero).  On return the r longest rows k of A[b] are lambda_k v_k^T (shorter rows only span the rest).  `ctl` is scratch of jacobi_ctl_bytes(B), `len2` scratch of B*nP doubles.
 size_t jacobi_ctl_bytes(int B);
 int jacobi_pitch(int n);      // row pitch (and padded order) the solver needs: n rounded up to 64
-int jacobi_launches(int n);   // tournament-round launches per solve
 // preset_done (optional, [B]): images whose entry is non-zero are left untouched.
 hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl, double* len2, const int* preset_done,
                                hipStream_t stream);
