@@ -10,9 +10,11 @@
 //
 // Parallel form: rows are grouped in super-blocks of 32; a round-robin tournament pairs the
 // super-blocks, one 256-thread workgroup per pair and image.  The whole solve is ONE launch: the
-// workgroups of an image meet at a barrier in global memory after every tournament round (all of
-// them are resident at once - the launcher sizes the grid to the occupancy and takes the images in
-// chunks if need be - and every wait is bounded by a wall-clock limit).  In a round the workgroup
+// workgroups of an image meet at a barrier in global memory after every tournament round.  A
+// workgroup takes its (image, slot) from a ticket counter when it starts, so the workgroups that are
+// resident always hold the lowest tickets, i.e. whole images plus at most one partial image whose
+// missing workgroups are the next to be dispatched once any image finishes; the launcher checks that
+// one image fits the device, and every wait is bounded by a wall-clock limit.  In a round the workgroup
 //   1. forms the 64x64 Gram H = P P^T of its 64 rows with v_mfma_f64_16x16x4 (waves split the
 //      columns, partial tiles are summed in LDS; the A and B operand of a diagonal tile are the
 //      same registers),
@@ -36,6 +38,7 @@ constexpr int kMaxSweeps = 30;
 struct JacobiCtl {
   unsigned long long maxoff[kMaxSweeps + 2];  // per sweep: bits of the largest admixture weight seen (see below)
   unsigned int arrived;       // barrier counter of the image's workgroups (monotonic)
+  unsigned int ticket;        // ctl[0] only: next (image, slot) to hand to a starting workgroup
   int done;
   int failed;                 // a barrier wait ran into its time limit: the result is invalid (rows are set to NaN)
   int sweeps;
@@ -69,6 +72,7 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restri
     double t = red[0] + red[1] + red[2] + red[3];
     for (int k = 0; k < kMaxSweeps + 2; ++k) ctl[b].maxoff[k] = 0ull;
     ctl[b].arrived = 0u;
+    ctl[b].ticket = 0u;
     ctl[b].done = preset_done ? preset_done[b] : 0;
     ctl[b].failed = 0;
     ctl[b].sweeps = 0;
@@ -342,17 +346,19 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
   return wave_max(meas2);
 }
 
-// The whole solve of the images [img0, img0 + gridDim.x / (nsb/2)): workgroup (image b, slot pr) visits the
-// pair `pr` of every tournament round of every sweep; after a sweep, slot 0 decides convergence and
-// re-measures which rows are the r longest.  A and len2 are written and re-read by different workgroups
-// between barriers, hence no __restrict__.
-__global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, int nP, int nsb, int r, int img0, JacobiCtl* ctl,
-                                                              double* len2) {
+// The whole solve of all images: workgroup (image b, slot pr) visits the pair `pr` of every tournament round
+// of every sweep; after a sweep, slot 0 decides convergence and re-measures which rows are the r longest.
+// A and len2 are written and re-read by different workgroups between barriers, hence no __restrict__.
+__global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, int nP, int nsb, int r, JacobiCtl* ctl, double* len2) {
   const int npairs = nsb >> 1;
-  const int b = img0 + blockIdx.x / npairs, pr = blockIdx.x % npairs;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_flag = (int)atomicAdd(&ctl[0].ticket, 1u);
+  __syncthreads();
+  const int ticket = s_flag;
+  __syncthreads();   // s_flag is reused by the barriers
+  const int b = ticket / npairs, pr = ticket - b * npairs;
   JacobiCtl* cb = ctl + b;
   if (cb->done) return;   // set before the launch, so the same for every workgroup of the image
-  const int tid = threadIdx.x;
   double* Ab = A + (long)b * nP * nP;
   double* len2b = len2 + (long)b * nP;
   const double floor2 = cb->floor2;   // written by the init kernel
@@ -463,7 +469,7 @@ hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl
   JacobiCtl* ctl = (JacobiCtl*)ctl_;
   const int nsb = nP / SB;  // even, since nP % 64 == 0
   const int npairs = nsb / 2;
-  // every workgroup of a launch has to be resident (they wait for one another): grid <= occupancy x CUs
+  // the workgroups of one image wait for one another, so one image has to fit the device
   static int capacity = 0;
   if (capacity == 0) {
     int dev = 0, per_cu = 0, cus = 0;
@@ -475,12 +481,8 @@ hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl
     capacity = per_cu * cus;
   }
   if (npairs > capacity) return hipErrorInvalidValue;
-  const int chunk = capacity / npairs;   // images per launch
   hipLaunchKernelGGL(jacobi_init_kernel, dim3(B), dim3(256), 0, st, A, n, nP, ctl, preset_done);
-  for (int img0 = 0; img0 < B; img0 += chunk) {
-    const int nimg = B - img0 < chunk ? B - img0 : chunk;
-    hipLaunchKernelGGL(jacobi_solve_kernel, dim3((unsigned)(nimg * npairs)), dim3(256), 0, st, A, n, nP, nsb, r, img0, ctl, len2);
-  }
+  hipLaunchKernelGGL(jacobi_solve_kernel, dim3((unsigned)(B * npairs)), dim3(256), 0, st, A, n, nP, nsb, r, ctl, len2);
   return hipGetLastError();
 }
 
