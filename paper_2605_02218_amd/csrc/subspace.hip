@@ -24,7 +24,7 @@ namespace {
 
 constexpr int NB = 64;        // panel width of Cholesky / substitution
 constexpr int NBP = NB + 1;   // LDS pitch
-constexpr size_t kCholLds = (size_t)(2 * NB * NBP + NB) * sizeof(double);
+constexpr size_t kCholLds = (size_t)(2 * NB * NBP) * sizeof(double);
 
 __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -43,12 +43,11 @@ __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
 // On return the strictly-lower blocks of S hold L; its diagonal blocks are represented by their inverses.
 // Pivots are floored at 1e-28 * trace(first block) so that a numerically rank-deficient block cannot
 // produce NaNs (the residual check afterwards decides whether the result is usable).
-// Dynamic LDS: 2 * 64 * 65 doubles + 64 doubles.
+// Dynamic LDS: 2 * 64 * 65 doubles.
 __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, const int* __restrict__ skip) {
   extern __shared__ double lds[];
-  double* a = lds;                  // [64][65] diagonal block -> its factor
-  double* inv = lds + NB * NBP;     // [64][65] inverse of the factor
-  double* colk = inv + NB * NBP;    // [64] current column of the factor
+  double* a = lds;                  // [64][65] diagonal block, later the inverse of its factor
+  double* fac = lds + NB * NBP;     // [64][65] the factor (lower triangle) and scratch (upper triangle)
   const int b = blockIdx.x;
   if (skip && skip[b]) return;
   double* Sb = S + (long)b * P * P;
@@ -68,38 +67,55 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
       for (int i = 0; i < NB; ++i) tr += a[i * NBP + i];   // same value in every thread
       floor_ = 1e-300 + 1e-28 * tr;
     }
-    // ---- factor the diagonal block
+    // ---- factor the diagonal block: right-looking, one barrier per column.  The block is updated unscaled
+    //      (a_ij -= a_ik a_jk / a_kk), the scaled column goes to a second buffer, so a step only reads column
+    //      k and writes the columns behind it.  Reciprocals: hardware estimate + two Newton steps.
     for (int k = 0; k < NB; ++k) {
-      if (tid < NB) {   // wave 0: all its reads are issued before its writes
-        const double akk = a[k * NBP + k], aik = a[tid * NBP + k];
-        const double d = sqrt(fmax(akk, floor_));
-        const double val = (tid == k) ? d : aik / d;
-        if (tid >= k) a[tid * NBP + k] = val;
-        colk[tid] = (tid > k) ? val : 0.0;
+      const double akk = fmax(a[k * NBP + k], floor_);
+      if (tid < NB) {
+        double rs = __builtin_amdgcn_rsq(akk);
+        rs = rs * fma(-0.5 * akk, rs * rs, 1.5);
+        rs = rs * fma(-0.5 * akk, rs * rs, 1.5);
+        fac[tid * NBP + k] = (tid < k) ? 0.0 : ((tid == k) ? akk * rs : a[tid * NBP + k] * rs);
       }
-      __syncthreads();
-      {
-        const int i = k + 1 + (tid >> 3);
-        if (i < NB) {
-          const double ci = colk[i];
-          for (int j = k + 1 + (tid & 7); j <= i; j += 8) a[i * NBP + j] -= ci * colk[j];
-        }
+      const int i = k + 1 + (tid >> 3);
+      if (i < NB) {
+        double rk = __builtin_amdgcn_rcp(akk);
+        rk = rk * fma(-akk, rk, 2.0);
+        rk = rk * fma(-akk, rk, 2.0);
+        const double ci = a[i * NBP + k] * rk;
+        for (int j = k + 1 + (tid & 7); j <= i; j += 8) a[i * NBP + j] = fma(-ci, a[j * NBP + k], a[i * NBP + j]);
       }
       __syncthreads();
     }
-    // ---- inv = a^-1 (lower triangular): column j by the 8 threads tid/8 == j, forward substitution
-    {
-      const int j = tid >> 3, part = tid & 7;
-      for (int i = 0; i < NB; ++i) {
-        double s_ = 0.0;
-        for (int m = j + part; m < i; m += 8) s_ = fma(a[i * NBP + m], inv[m * NBP + j], s_);
-        s_ += __shfl_xor(s_, 1, 64);
-        s_ += __shfl_xor(s_, 2, 64);
-        s_ += __shfl_xor(s_, 4, 64);
-        if (part == 0) inv[i * NBP + j] = (i < j) ? 0.0 : (((i == j) ? 1.0 : 0.0) - s_) / a[i * NBP + i];
-        __syncthreads();
-      }
+    // ---- inverse of the factor into `a`, by doubling: with L = [A 0; C D], inv(L) = [inv(A) 0; -inv(D) C inv(A) inv(D)].
+    //      Level s joins the inverses of the s x s diagonal blocks pairwise; the intermediate C inv(A) is parked,
+    //      transposed, in the unused upper triangle of `fac`.
+    for (int e = tid; e < NB * NB; e += 512) {
+      const int i = e >> 6, j = e & 63;
+      a[i * NBP + j] = (i == j) ? 1.0 / fac[i * NBP + i] : 0.0;
     }
+    __syncthreads();
+    for (int s_ = 1, ls = 0; s_ < NB; s_ <<= 1, ++ls) {
+      // 32 * s_ elements per level: element e -> block pair m, row i, column j
+      for (int e = tid; e < 32 * s_; e += 512) {
+        const int m = e >> (2 * ls), i = (e >> ls) & (s_ - 1), j = e & (s_ - 1);
+        const int base = 2 * s_ * m;
+        double t1 = 0.0;   // (C inv(A))[i][j], inv(A) lower triangular
+        for (int t = j; t < s_; ++t) t1 = fma(fac[(base + s_ + i) * NBP + base + t], a[(base + t) * NBP + base + j], t1);
+        fac[(base + j) * NBP + base + s_ + i] = t1;
+      }
+      __syncthreads();
+      for (int e = tid; e < 32 * s_; e += 512) {
+        const int m = e >> (2 * ls), i = (e >> ls) & (s_ - 1), j = e & (s_ - 1);
+        const int base = 2 * s_ * m;
+        double x = 0.0;    // (inv(D) T1)[i][j], inv(D) lower triangular
+        for (int u = 0; u <= i; ++u) x = fma(a[(base + s_ + i) * NBP + base + s_ + u], fac[(base + j) * NBP + base + s_ + u], x);
+        a[(base + s_ + i) * NBP + base + j] = -x;
+      }
+      __syncthreads();
+    }
+    double* inv = a;
     {
       double* Db = Dinv + ((long)b * nblk + J) * NB * NB;
       for (int e = tid; e < NB * NB; e += 512) Db[e] = inv[(e >> 6) * NBP + (e & 63)];
