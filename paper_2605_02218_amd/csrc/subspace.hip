@@ -84,7 +84,23 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
         rk = rk * fma(-akk, rk, 2.0);
         rk = rk * fma(-akk, rk, 2.0);
         const double ci = a[i * NBP + k] * rk;
-        for (int j = k + 1 + (tid & 7); j <= i; j += 8) a[i * NBP + j] = fma(-ci, a[j * NBP + k], a[i * NBP + j]);
+        // loads, arithmetic, stores in three batches (the compiler cannot tell that the elements are distinct)
+        double cj[8], v[8];
+        const int jb = k + 1 + (tid & 7);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int j = jb + 8 * u;
+          const bool on = j <= i;
+          cj[u] = on ? a[j * NBP + k] : 0.0;
+          v[u] = on ? a[i * NBP + j] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = fma(-ci, cj[u], v[u]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int j = jb + 8 * u;
+          if (j <= i) a[i * NBP + j] = v[u];
+        }
       }
       __syncthreads();
     }
@@ -142,34 +158,57 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
         for (int v = 0; v < 4; ++v) Sb[(rb + 4 * v + kq) * P + j0 + 16 * y + i16] = out[y][v];
     }
     __syncthreads();
-    // ---- trailing update, unit = 16 rows of block I x the 64 columns of block I' <= I
+    // ---- trailing update, unit = 16 rows of block I x the 64 columns of block I' <= I.  Every wave takes a
+    //      contiguous range of units, so consecutive units mostly share I' and its fragments stay in registers;
+    //      all loads of a unit are issued before its MFMAs.
     {
       const int nb = below / NB;
-      int cnt = 0;
-      for (int I = 0; I < nb; ++I)
-        for (int I2 = 0; I2 <= I; ++I2)
-          for (int q = 0; q < 4; ++q, ++cnt) {
-            if ((cnt & 7) != w) continue;
-            const long ra = j0 + NB + (long)I * NB + 16 * q;
-            const long rc = j0 + NB + (long)I2 * NB;
-            f64x4_t acc[4];
+      const int units = 2 * nb * (nb + 1);            // 4 * nb (nb + 1) / 2
+      const int u0 = (int)((long)units * w / 8), u1 = (int)((long)units * (w + 1) / 8);
+      // unit u -> pair index u / 4 -> (I, I2) with I (I + 1) / 2 + I2 = pair index
+      int I = 0, I2 = 0;
+      {
+        int pi = u0 >> 2;
+        while ((I + 1) * (I + 2) / 2 <= pi) ++I;
+        I2 = pi - I * (I + 1) / 2;
+      }
+      f64x4_t fb[4][4];
+      int have = -1;
+      for (int u = u0; u < u1; ++u) {
+        const int q = u & 3;
+        const long ra = j0 + NB + (long)I * NB + 16 * q;
+        const long rc = j0 + NB + (long)I2 * NB;
+        f64x4_t fa[4], cc[4];
 #pragma unroll
-            for (int y = 0; y < 4; ++y) acc[y] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+        for (int c = 0; c < 4; ++c) fa[c] = *(const f64x4_t*)(Sb + (ra + i16) * P + j0 + 16 * c + 4 * kq);
+        if (have != I2) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const f64x4_t fa = *(const f64x4_t*)(Sb + (ra + i16) * P + j0 + 16 * c + 4 * kq);
+          for (int y = 0; y < 4; ++y)
 #pragma unroll
-              for (int y = 0; y < 4; ++y) {
-                const f64x4_t fb = *(const f64x4_t*)(Sb + (rc + 16 * y + i16) * P + j0 + 16 * c + 4 * kq);
+            for (int c = 0; c < 4; ++c) fb[y][c] = *(const f64x4_t*)(Sb + (rc + 16 * y + i16) * P + j0 + 16 * c + 4 * kq);
+          have = I2;
+        }
+        f64x4_t acc[4];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) acc[y] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[jj], fb[jj], acc[y], 0, 0, 0);
-              }
-            }
+        for (int y = 0; y < 4; ++y) acc[y] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int y = 0; y < 4; ++y)
+        for (int c = 0; c < 4; ++c)
 #pragma unroll
-              for (int v = 0; v < 4; ++v) Sb[(ra + 4 * v + kq) * P + rc + 16 * y + i16] -= acc[y][v];
-          }
+          for (int y = 0; y < 4; ++y)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) acc[y] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[c][jj], fb[y][c][jj], acc[y], 0, 0, 0);
+#pragma unroll
+        for (int y = 0; y < 4; ++y)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) cc[y][v] = Sb[(ra + 4 * v + kq) * P + rc + 16 * y + i16];
+#pragma unroll
+        for (int y = 0; y < 4; ++y)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) Sb[(ra + 4 * v + kq) * P + rc + 16 * y + i16] = cc[y][v] - acc[y][v];
+        if (q == 3) {   // next pair
+          if (I2 == I) { ++I; I2 = 0; } else ++I2;
+        }
+      }
     }
     __syncthreads();
   }
