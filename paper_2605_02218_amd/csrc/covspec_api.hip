@@ -14,7 +14,7 @@ namespace {
 constexpr int kMaxTokens = 16384;
 constexpr int kMaxPreselect = 4096;
 constexpr int kMaxActLayers = 8;
-constexpr int kSubspaceIters = 10;
+constexpr int kSubspaceIters = 14;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -3,7 +3,7 @@
 //
 // Only the r dominant eigenpairs of G = Z_M^T Z_M enter the energies, so instead of
 // diagonalising all of G, a block of P > r vectors is iterated:
-//     Y <- G Y,  Y <- orthonormalise(Y)          (P ~ 2r; error shrinks by lambda_{P+1}/lambda_r per step)
+//     Y <- G Y,  Y <- orthonormalise(Y)          (P = r + 64..127; error shrinks by lambda_{P+1}/lambda_r per step)
 // and the r dominant Ritz pairs of the P x P projection Q^T G Q are taken (Rayleigh-Ritz, solved by
 // the block Jacobi kernel).  All products are fp64 MFMA GEMMs; the cost scales with r, not with M.
 //
@@ -306,9 +306,10 @@ __global__ __launch_bounds__(256) void ritz_check_kernel(const double* __restric
 }  // namespace
 
 int subspace_block(int n, int r) {
-  // P = max(2r, r + 64) rounded up to the panel width; 0 = not worthwhile (P would be most of n)
-  int P = 2 * r > r + 64 ? 2 * r : r + 64;
-  P = (P + NB - 1) / NB * NB;
+  // P = r + 64 rounded up to the panel width: the Ritz problem costs P^3 and each step P^2 n, while a wider
+  // block only buys a better contraction factor lambda_{P+1}/lambda_r per step, so the narrow block with a
+  // few more steps is the cheaper trade.  0 = not worthwhile (P would be most of n).
+  int P = (r + 64 + NB - 1) / NB * NB;
   return (4 * P <= 3 * n) ? P : 0;
 }
 
