@@ -21,9 +21,14 @@ if ROOT not in sys.path:
 # MI355X published peaks
 PEAK = {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0, "mfma_fp64_TFLOPs": 78.6, "valu_fp64_TFLOPs": 78.6}
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this program (profiles/), scaled by
-# the counters' reading for a copy of known size; keyed by (workload, kernel).  None where not collected.
-TRAFFIC = {}
+# Bytes per launch that crossed the L2 <-> memory-fabric boundary, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# runs of this program (summary and commands: profiles/reduce_workload5_paper_hbm_counters.txt), each counter
+# scaled by its reading for a device copy of 2^30 bytes (FETCH_SIZE reads half the bytes: factor 2.0; WRITE_SIZE
+# factor 1.0).  Keyed by (workload, kernel); None where not collected.
+TRAFFIC = {
+    (5, "gemm_nt_dma_kernel<rownorm2>"): 4424852 * 1024 * 2.0 + 23040 * 1024 * 1.0,
+    (5, "activity_kernel"): 3686457 * 1024 * 2.0 + 1994 * 1024 * 1.0,
+}
 
 
 def _params(C, w, rel, lr):
@@ -167,17 +172,29 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=5, help="1..5 (default 5: the largest single-GPU workload)")
     ap.add_argument("--pipeline", choices=["paper", "variant"], default="paper")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other workloads and pipeline (extra keys)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run three plain 1 GiB device copies and exit (reference reading for the HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (images shard trivially across GPUs; no multi-GPU path "
                  "exists or is measured) -- rerun with --gpus 1")
 
     import torch
+    if a.copy_calibration:
+        # a copy of known size: 2^30 bytes read, 2^30 bytes written per launch
+        torch.cuda.set_device(0)
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 3}), flush=True)
+        return
     import covspec_inputs as I
     import paper_2605_02218_amd as C
     C.load_library()
