@@ -353,9 +353,11 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_dma_kernel(GemmArgs g, int ti
 
   // Software pipeline, per k-tile kt (one barrier each):
   //   wait until tile kt+1 has landed (at most the loads of tiles kt+2, kt+3 outstanding), barrier;
-  //   start the loads of tile kt+3 into the stage that held tile kt-1;
+  //   start the loads of tile kt+4 into the stage that held tile kt (its fragments went into registers one
+  //   iteration ago, and every wave's LDS reads are complete before it arrives at the barrier);
   //   read the MFMA fragments of tile kt+1 from LDS into the idle register set WHILE the fragments of
-  //   tile kt, read one iteration earlier, feed the 32 MFMAs.
+  //   tile kt feed the 32 MFMAs.
+  // So three tiles (96 KB per CU) are in flight during the MFMAs of a tile.
   // A plain s_barrier is used: __syncthreads() would add a fence that waits for ALL outstanding loads
   // and with it the prefetch depth.  lgkmcnt(0) before the barrier: this wave's LDS reads are done, so
   // after the barrier the stage they came from may be overwritten.
@@ -366,27 +368,50 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_dma_kernel(GemmArgs g, int ti
   issue(0);
   issue(min(1, nk - 1));
   issue(min(2, nk - 1));
-  __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0): tile 0 has landed
+  issue(min(3, nk - 1));
+  __builtin_amdgcn_s_waitcnt(0x4078);   // vmcnt(24) lgkmcnt(0): tile 0 has landed
   __builtin_amdgcn_s_barrier();
   frags(stage_ptr(0), 0, a0[0], b0[0]);
   frags(stage_ptr(0), 1, a0[1], b0[1]);
+  // Instruction order inside a half iteration, fixed with scheduling groups: nothing moves across the barrier
+  // (MFMAs are register-only and would otherwise be hoisted over it, dragging their fragment reads along);
+  // the 16 fragment reads go out one per MFMA during the first half, the 8 loads one per two MFMAs after
+  // that, so that the matrix pipe (32 cycles per MFMA) always has the next MFMA queued.
+  auto order = [&]() {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (global -> LDS)
+    }
+  };
   for (int kt = 0; kt < nk; kt += 2) {
     // even tile: set 0 feeds the MFMAs, set 1 is filled from tile kt+1
-    __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0): all but the newest tile have landed
+    __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0): all but the two newest tiles have landed
     __builtin_amdgcn_s_barrier();
-    issue(min(kt + 3, nk - 1));
+    __builtin_amdgcn_sched_barrier(0);
     frags(stage_ptr(kt + 1), 0, a1[0], b1[0]);
     frags(stage_ptr(kt + 1), 1, a1[1], b1[1]);
+    issue(min(kt + 4, nk - 1));
     mma(a0[0], b0[0]);
     mma(a0[1], b0[1]);
+    order();
+    __builtin_amdgcn_sched_barrier(0);
     // odd tile: set 1 feeds the MFMAs, set 0 is filled from tile kt+2
-    __builtin_amdgcn_s_waitcnt(0x0078);
+    __builtin_amdgcn_s_waitcnt(0x4070);
     __builtin_amdgcn_s_barrier();
-    issue(min(kt + 4, nk - 1));
+    __builtin_amdgcn_sched_barrier(0);
     frags(stage_ptr(kt + 2), 0, a0[0], b0[0]);
     frags(stage_ptr(kt + 2), 1, a0[1], b0[1]);
+    issue(min(kt + 5, nk - 1));
     mma(a1[0], b1[0]);
     mma(a1[1], b1[1]);
+    order();
+    __builtin_amdgcn_sched_barrier(0);
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
