@@ -58,8 +58,17 @@ enum { COVSPEC_REL_COSINE_MAX = 0, COVSPEC_REL_ATTN_SOFTMAX = 1 };
  *                     keep the k largest (paper Sec. III-A.3).
  *   GREEDY_RESIDUAL : variant that is NOT in the paper: k greedy picks, each the token with the
  *                     largest residual after projecting out the tokens already picked
- *                     (pivoted Cholesky of the token Gram matrix).                               */
-enum { COVSPEC_LR_ENERGY_TOPK = 0, COVSPEC_LR_GREEDY_RESIDUAL = 1 };
+ *                     (pivoted Cholesky of the token Gram matrix).
+ * Ablations of the selector (the paper's Table II compares full-token drafting and random-token
+ * selection; Sec. III-A.3 names "the M highest-scoring tokens" as the straightforward alternative;
+ * full-token drafting is keep_k = preselect_m = n_tokens with any mode):
+ *   SCORE_TOPK      : no low-rank term: keep the k highest fused scores.
+ *   RANDOM          : keep k tokens drawn uniformly at random, reproducibly: token i of image b gets
+ *                     the score (mix64(seed * 0x9E3779B97F4A7C15 + (b << 32 | i) +
+ *                     0x632BE59BD9B4E019) >> 40) * 2^-24, mix64 being the output function of the
+ *                     SplitMix64 generator, and the k largest are kept (ties -> lower index).
+ *                     covspec_reduce then computes no scores at all.                            */
+enum { COVSPEC_LR_ENERGY_TOPK = 0, COVSPEC_LR_GREEDY_RESIDUAL = 1, COVSPEC_LR_SCORE_TOPK = 2, COVSPEC_LR_RANDOM = 3 };
 
 typedef struct covspec_params {
   int32_t batch;        /* B >= 1 images                                                          */
@@ -76,6 +85,7 @@ typedef struct covspec_params {
   int32_t keep_k;       /* k; 0 => floor(keep_ratio*N + 0.5) clamped to [1, M]                    */
   float keep_ratio;     /* used only when keep_k == 0; must then be in (0, 1]                     */
   float lambda;         /* fusion weight of the query score, in [0, 1] (paper fusion equation)    */
+  uint32_t seed;        /* COVSPEC_LR_RANDOM only                                                 */
 } covspec_params;
 
 /* Bytes of device scratch that any of the three entry points needs for `p` (0 if `p` is invalid
@@ -102,11 +112,11 @@ int covspec_score(const covspec_params* p, const void* X, const void* hidden, co
 
 /*
  * Selection from caller-supplied fused scores (paper Sec. III-A.3).
- *   X        [B, N, d]   features; s_fused [B, N] fp32
+ *   X        [B, N, d]   features; s_fused [B, N] fp32 (RANDOM: ignored, may be NULL)
  *   idx_out  [B, k]      kept token positions in [0, N), ascending              (required)
  *   c_out    [B, M]      ENERGY_TOPK: subspace energy of the pre-selected tokens, in idx_m order;
- *                        GREEDY_RESIDUAL: untouched                              (or NULL)
- *   idx_m_out[B, M]      pre-selected positions, ascending                       (or NULL)
+ *                        other modes: untouched                                  (or NULL)
+ *   idx_m_out[B, M]      pre-selected positions, ascending; RANDOM: untouched    (or NULL)
  *   pick_order_out [B,k] GREEDY_RESIDUAL: token positions in pick order          (or NULL)
  *   resid_out [B, k]     GREEDY_RESIDUAL: residual squared norm at each pick     (or NULL)
  */

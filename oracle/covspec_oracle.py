@@ -24,6 +24,10 @@ Steps, in the paper's order (per image; images are independent):
 7. keep the B_vis = k tokens with the largest c_i              (end of Sec. III-A.3)
    variant "greedy": pivoted-Cholesky / column-pivoted Gram-Schmidt picks
    (NOT in the paper; named variant)
+   ablations of the selector (Table II compares full-token drafting and random-token
+   selection; Sec. III-A.3 names top-M by score as the straightforward alternative):
+   "score": keep the k highest fused scores; "random": keep k tokens drawn uniformly at
+   random from a counter-based generator that the GPU path implements too
 8. gather the kept feature rows.
 
 Readings where the paper is silent (all listed in the design notes):
@@ -51,6 +55,8 @@ REL_COSINE_MAX = 0
 REL_ATTN_SOFTMAX = 1
 LR_ENERGY_TOPK = 0
 LR_GREEDY_RESIDUAL = 1
+LR_SCORE_TOPK = 2      # ablation: keep the k highest fused scores, no low-rank term (Sec. III-A.3, first sentence)
+LR_RANDOM = 3          # ablation: k tokens drawn uniformly at random (the "random-token selection" row of Table II)
 
 
 @dataclass
@@ -63,6 +69,7 @@ class Params:
     keep_k: int = 0
     keep_ratio: float = 0.25
     lam: float = 0.5
+    seed: int = 0
 
     def resolved(self, n_tokens: int):
         """(k, M, r) after applying the defaults of the C interface."""
@@ -231,10 +238,41 @@ def score(X, hidden, Q, Wq, Wk, p: Params) -> Dict[str, np.ndarray]:
     return {"s_query": s_query, "s_act": s_act, "s_fused": s_fused}
 
 
-def select(X, s_fused, p: Params) -> Dict[str, np.ndarray]:
-    """Steps 5-7 for one image, from a fused score vector."""
+_MASK64 = (1 << 64) - 1
+
+
+def mix64(x: int) -> int:
+    """The output function of the SplitMix64 generator (Steele, Lea, Flood 2014) on a 64-bit word."""
+    z = x & _MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK64
+    return z ^ (z >> 31)
+
+
+def random_scores(seed: int, image: int, n_tokens: int) -> np.ndarray:
+    """Counter-based uniform scores in [0, 1) with 24 bits, one per (seed, image, token).
+
+    word = seed * 0x9E3779B97F4A7C15 + (image << 32 | token) + 0x632BE59BD9B4E019 (mod 2^64); the score is
+    the top 24 bits of mix64(word) times 2^-24, which float32 holds exactly.  Keeping the k largest (ties ->
+    lower index) draws k tokens uniformly without replacement.
+    """
+    out = np.empty(n_tokens, dtype=np.float64)
+    for i in range(n_tokens):
+        word = (seed * 0x9E3779B97F4A7C15 + ((image << 32) | i) + 0x632BE59BD9B4E019) & _MASK64
+        out[i] = (mix64(word) >> 40) * 2.0 ** -24
+    return out
+
+
+def select(X, s_fused, p: Params, image: int = 0) -> Dict[str, np.ndarray]:
+    """Steps 5-7 for one image, from a fused score vector (`image`: its index in the batch, used by LR_RANDOM)."""
     X = np.asarray(X, dtype=np.float64)
     k, M, r = p.resolved(X.shape[0])
+    if p.lr_mode == LR_RANDOM:
+        u = random_scores(p.seed, image, X.shape[0])
+        return {"idx": top_indices(u, k).astype(np.int32), "random_scores": u}
+    if p.lr_mode == LR_SCORE_TOPK:
+        return {"idx": top_indices(s_fused, k).astype(np.int32), "idx_m": top_indices(s_fused, M),
+                "margin_topk": cut_margin(s_fused, k)}
     idx_m = top_indices(s_fused, M)
     Z = X[idx_m]
     out = {"idx_m": idx_m, "margin_topm": cut_margin(s_fused, M)}
@@ -251,11 +289,11 @@ def select(X, s_fused, p: Params) -> Dict[str, np.ndarray]:
     return out
 
 
-def reduce(X, hidden, Q, Wq, Wk, p: Params) -> Dict[str, np.ndarray]:
+def reduce(X, hidden, Q, Wq, Wk, p: Params, image: int = 0) -> Dict[str, np.ndarray]:
     """Steps 1-8 for one image; 'tokens' are rows of X (the stored features, not embeddings)."""
     sc = score(X, hidden, Q, Wq, Wk, p)
     # the fused score crosses the library boundary as float32; selection sees those bits
-    se = select(X, decision_values(sc["s_fused"]), p)
+    se = select(X, decision_values(sc["s_fused"]), p, image)
     out = dict(sc)
     out.update(se)
     out["tokens"] = np.asarray(X)[se["idx"]]

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libcovspec.so")
 
 FP32, BF16 = 0, 1
 REL_COSINE_MAX, REL_ATTN_SOFTMAX = 0, 1
-LR_ENERGY_TOPK, LR_GREEDY_RESIDUAL = 0, 1
+LR_ENERGY_TOPK, LR_GREEDY_RESIDUAL, LR_SCORE_TOPK, LR_RANDOM = 0, 1, 2, 3
 OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
 
 EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
@@ -28,7 +28,7 @@ class CovspecParams(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "n_tokens", "d_model", "n_query", "n_heads", "n_act_layers", "dtype",
         "rel_mode", "lr_mode", "preselect_m", "rank_r", "keep_k")] + [
-        ("keep_ratio", ctypes.c_float), ("lambda_", ctypes.c_float)]
+        ("keep_ratio", ctypes.c_float), ("lambda_", ctypes.c_float), ("seed", ctypes.c_uint32)]
 
 
 class CovspecError(RuntimeError):
@@ -90,11 +90,12 @@ class Params:
     keep_k: int = 0
     keep_ratio: float = 0.25
     lam: float = 0.5
+    seed: int = 0
 
     def c_struct(self) -> CovspecParams:
         return CovspecParams(self.batch, self.n_tokens, self.d_model, self.n_query, self.n_heads,
                              self.n_act_layers, self.dtype, self.rel_mode, self.lr_mode, self.preselect_m,
-                             self.rank_r, self.keep_k, self.keep_ratio, self.lam)
+                             self.rank_r, self.keep_k, self.keep_ratio, self.lam, self.seed & 0xFFFFFFFF)
 
 
 def workspace_size(p: Params) -> int:
@@ -179,6 +180,11 @@ def select(p: Params, X, s_fused, workspace=None):
     if p.lr_mode == LR_ENERGY_TOPK:
         c = torch.empty(B, M, dtype=torch.float32, device=dev)
         out["c"] = c
+    elif p.lr_mode == LR_RANDOM:
+        idx_m = None
+        del out["idx_m"]
+    elif p.lr_mode == LR_SCORE_TOPK:
+        pass
     else:
         pick = torch.empty(B, k, dtype=torch.int32, device=dev)
         resid = torch.empty(B, k, dtype=torch.float32, device=dev)

@@ -74,4 +74,39 @@ __device__ __forceinline__ int block_exscan_1024(int v, int* wsum, int* total) {
   return wsum[w] + inc - v;
 }
 
+// Barrier in global memory over the workgroups that work on one image.  `arrived` only grows; `target` is the
+// value it reaches when all of them have arrived at this barrier.  Every thread's earlier global writes are
+// visible to every thread of the group behind the barrier (device-scope release before, acquire after: the
+// XCDs' L2s are not coherent with one another).  The wait is bounded: when it exceeds `limit_ticks` of the
+// 100 MHz wall clock, or another workgroup of the image has reported that, `failed` is set and false is
+// returned; the caller then gives up on the image.  Call uniformly from all threads; `s_flag` is one int of LDS.
+struct ImageBarrier {
+  unsigned int arrived;
+  int failed;
+};
+constexpr long long kBarrierLimitTicks = 200000000LL;   // 2 s
+
+__device__ __forceinline__ bool image_barrier_wait(ImageBarrier* bar, unsigned int target, int* s_flag) {
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int ok = 1;
+    __hip_atomic_fetch_add(&bar->arrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    const long long t0 = wall_clock64();
+    while (__hip_atomic_load(&bar->arrived, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (__hip_atomic_load(&bar->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
+          wall_clock64() - t0 > kBarrierLimitTicks) {
+        ok = 0;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(4);
+    }
+    if (!ok) __hip_atomic_store(&bar->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_flag = ok;
+  }
+  __syncthreads();
+  __threadfence();
+  return *s_flag != 0;
+}
+
 }  // namespace covspec

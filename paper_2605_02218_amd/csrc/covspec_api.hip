@@ -21,13 +21,14 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Plan {
   int B, N, d, T, H, K, dtype, rel, lr, M, r, k;
   float lambda;
+  uint32_t seed;
   int esz;        // bytes per stored element
   int planes;     // bf16: 3 split planes of the folded query matrix, fp32: 1
   int nparts;     // per-token partial sums of |e(v)|^2 written by the projection GEMM
   int nP;         // Gram pitch (padded order of the eigen-solve)
   // workspace offsets (bytes)
   size_t wqT, wkT, Eq, qn2, Eq3, G3raw, G3, vn2p, logits, Ev, S, stats, sq, sa, sf;
-  size_t idxm, Awork, ctl, lam, c, Lt, order, resid, sub, ok;
+  size_t idxm, Awork, ctl, lam, c, Lt, order, resid, gscr, sub, ok;
   int P;          // block size of the subspace iteration (0: full Jacobi solve)
   size_t total;
 };
@@ -58,7 +59,7 @@ int make_plan(const covspec_params* p, Plan* pl) {
   if (p->n_act_layers < 0) return COVSPEC_INVALID_ARG;
   if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16) return COVSPEC_INVALID_ARG;
   if (p->rel_mode != COVSPEC_REL_COSINE_MAX && p->rel_mode != COVSPEC_REL_ATTN_SOFTMAX) return COVSPEC_INVALID_ARG;
-  if (p->lr_mode != COVSPEC_LR_ENERGY_TOPK && p->lr_mode != COVSPEC_LR_GREEDY_RESIDUAL) return COVSPEC_INVALID_ARG;
+  if (p->lr_mode < COVSPEC_LR_ENERGY_TOPK || p->lr_mode > COVSPEC_LR_RANDOM) return COVSPEC_INVALID_ARG;
   if (!(p->lambda >= 0.f) || !(p->lambda <= 1.f)) return COVSPEC_INVALID_ARG;
   int k, M, r;
   int st = resolve(p, &k, &M, &r);
@@ -66,14 +67,15 @@ int make_plan(const covspec_params* p, Plan* pl) {
   const int mind = M < p->d_model ? M : p->d_model;
   if (p->lr_mode == COVSPEC_LR_ENERGY_TOPK && (r < 1 || r >= mind)) return COVSPEC_INVALID_ARG;
   // limits of the kernels
-  if (p->n_tokens > kMaxTokens || M > kMaxPreselect || p->n_act_layers > kMaxActLayers) return COVSPEC_UNSUPPORTED;
+  const bool lowrank = p->lr_mode == COVSPEC_LR_ENERGY_TOPK || p->lr_mode == COVSPEC_LR_GREEDY_RESIDUAL;
+  if (p->n_tokens > kMaxTokens || (lowrank && M > kMaxPreselect) || p->n_act_layers > kMaxActLayers) return COVSPEC_UNSUPPORTED;
   if (p->d_model % (p->dtype == COVSPEC_BF16 ? 8 : 4) != 0) return COVSPEC_UNSUPPORTED;
   if (p->rel_mode == COVSPEC_REL_ATTN_SOFTMAX && (p->d_model / p->n_heads) % 4 != 0) return COVSPEC_UNSUPPORTED;
   if ((long)p->batch * p->n_tokens > 0x3fffffffL || (long)p->batch * p->n_query > 0x3fffffffL) return COVSPEC_UNSUPPORTED;
 
   Plan& q = *pl;
   q.B = p->batch; q.N = p->n_tokens; q.d = p->d_model; q.T = p->n_query; q.H = p->n_heads; q.K = p->n_act_layers;
-  q.dtype = p->dtype; q.rel = p->rel_mode; q.lr = p->lr_mode; q.M = M; q.r = r; q.k = k; q.lambda = p->lambda;
+  q.dtype = p->dtype; q.rel = p->rel_mode; q.lr = p->lr_mode; q.M = M; q.r = r; q.k = k; q.lambda = p->lambda; q.seed = p->seed;
   q.esz = p->dtype == COVSPEC_BF16 ? 2 : 4;
   q.planes = p->dtype == COVSPEC_BF16 ? 3 : 1;
   q.nparts = p->dtype == COVSPEC_BF16 ? gemm_tiles_n(q.d) : gemm64_tiles_n(q.d);
@@ -83,11 +85,14 @@ int make_plan(const covspec_params* p, Plan* pl) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t B = q.B, N = q.N, d = q.d, T = q.T, BT = B * T, BN = B * N;
+  q.wqT = q.wkT = q.Eq = q.qn2 = 0;
+  q.Eq3 = q.G3raw = q.G3 = q.vn2p = q.logits = q.Ev = q.S = q.stats = 0;
+  // the random-selection ablation uses no scores; covspec_score with that mode still works on its own
+  // workspace request, so the score buffers are always part of the plan
   q.wqT = take(d * d * q.esz);
   q.wkT = take(d * d * q.esz);
   q.Eq = take(BT * d * fsz);
   q.qn2 = take(BT * fsz);
-  q.Eq3 = q.G3raw = q.G3 = q.vn2p = q.logits = q.Ev = q.S = q.stats = 0;
   if (q.rel == COVSPEC_REL_COSINE_MAX) {
     if (q.dtype == COVSPEC_BF16) q.Eq3 = take(3 * BT * d * 2);
     q.G3raw = take((size_t)q.planes * BT * d * fsz);
@@ -103,18 +108,23 @@ int make_plan(const covspec_params* p, Plan* pl) {
   q.sa = take(BN * 4);
   q.sf = take(BN * 4);
   q.idxm = take(B * M * 4);
-  q.Awork = take(B * (size_t)q.nP * q.nP * 8);
-  q.ctl = take(jacobi_ctl_bytes(q.B));
-  q.lam = take(B * q.nP * 8);
-  q.c = take(B * M * 4);
-  q.P = (q.lr == COVSPEC_LR_ENERGY_TOPK) ? subspace_block(M, r) : 0;
-  q.sub = take(subspace_workspace_bytes(q.B, M, q.nP, q.P));
-  q.ok = take(B * 4);
-  q.Lt = q.order = q.resid = 0;
+  q.Awork = q.ctl = q.lam = q.c = q.sub = q.ok = 0;
+  q.P = 0;
+  if (lowrank) {
+    q.Awork = take(B * (size_t)q.nP * q.nP * 8);
+    q.ctl = take(jacobi_ctl_bytes(q.B));
+    q.lam = take(B * q.nP * 8);
+    q.c = take(B * M * 4);
+    q.P = (q.lr == COVSPEC_LR_ENERGY_TOPK) ? subspace_block(M, r) : 0;
+    q.sub = take(subspace_workspace_bytes(q.B, M, q.nP, q.P));
+    q.ok = take(B * 4);
+  }
+  q.Lt = q.order = q.resid = q.gscr = 0;
   if (q.lr == COVSPEC_LR_GREEDY_RESIDUAL) {
     q.Lt = take(B * (size_t)k * q.nP * 8);
     q.order = take(B * k * 4);
     q.resid = take(B * k * 4);
+    q.gscr = take(greedy_scratch_bytes(q.B, q.nP));
   }
   q.total = off;
   return COVSPEC_OK;
@@ -264,6 +274,24 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
                int32_t* pick_order_out, float* resid_out, void* ws, hipStream_t st, StageMarks& marks) {
   const long N = q.N, d = q.d;
   marks.mark(COVSPEC_STAGE_PRESELECT);
+  if (q.lr == COVSPEC_LR_SCORE_TOPK || q.lr == COVSPEC_LR_RANDOM) {
+    // selector ablations (Table II; Sec. III-A.3, first sentence): one ranking, no low-rank stage
+    const float* rank_by = s_fused;
+    if (q.lr == COVSPEC_LR_RANDOM) {
+      float* u = at<float>(ws, q.sf);   // the fused-score buffer is free: this mode uses no scores
+      HIPCHK(launch_random_scores(u, q.B, q.N, q.seed, st));
+      rank_by = u;
+    } else if (idx_m_out) {
+      HIPCHK(launch_select_top(s_fused, q.B, q.N, q.M, nullptr, idx_m_out, st));
+    }
+    marks.mark(COVSPEC_STAGE_GRAM);
+    marks.mark(COVSPEC_STAGE_LOWRANK);
+    marks.mark(COVSPEC_STAGE_KEEP);
+    HIPCHK(launch_select_top(rank_by, q.B, q.N, q.k, nullptr, idx_out, st));
+    marks.mark(COVSPEC_PROBE_BEGIN);
+    marks.mark(COVSPEC_PROBE_END);
+    return COVSPEC_OK;
+  }
   int32_t* idxm = idx_m_out ? idx_m_out : at<int32_t>(ws, q.idxm);
   HIPCHK(launch_select_top(s_fused, q.B, q.N, q.M, nullptr, idxm, st));
 
@@ -310,7 +338,7 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
     int32_t* order = at<int32_t>(ws, q.order);
     float* resid = resid_out ? resid_out : at<float>(ws, q.resid);
     marks.mark(COVSPEC_STAGE_LOWRANK);
-    HIPCHK(launch_greedy(A, q.B, q.M, q.nP, q.k, at<double>(ws, q.Lt), order, resid, st));
+    HIPCHK(launch_greedy(A, q.B, q.M, q.nP, q.k, at<double>(ws, q.Lt), order, resid, at<void>(ws, q.gscr), st));
     marks.mark(COVSPEC_STAGE_KEEP);
     HIPCHK(launch_greedy_finish(order, idxm, q.B, q.M, q.k, idx_out, pick_order_out, st));
   }
@@ -359,7 +387,7 @@ int covspec_select(const covspec_params* p, const void* X, const float* s_fused,
   Plan pl;
   int st = make_plan(p, &pl);
   if (st != COVSPEC_OK) return st;
-  if (!X || !s_fused || !idx_out) return COVSPEC_INVALID_ARG;
+  if (!X || !idx_out || (!s_fused && pl.lr != COVSPEC_LR_RANDOM)) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
   StageMarks none;
   return run_select(pl, X, s_fused, idx_out, c_out, idx_m_out, pick_order_out, resid_out, workspace, (hipStream_t)stream, none);
@@ -374,8 +402,12 @@ static int reduce_impl(const covspec_params* p, const void* X, const void* hidde
   if (!X || !Q || !idx_out || !tokens_out) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
   float* sf = at<float>(workspace, pl.sf);
-  st = run_score(pl, X, hidden, Q, Wq, Wk, nullptr, nullptr, sf, workspace, s, marks);
-  if (st != COVSPEC_OK) return st;
+  if (pl.lr == COVSPEC_LR_RANDOM) {
+    for (int e = COVSPEC_STAGE_QUERY_SIDE; e <= COVSPEC_STAGE_FUSE; ++e) marks.mark(e);   // no scores in this mode
+  } else {
+    st = run_score(pl, X, hidden, Q, Wq, Wk, nullptr, nullptr, sf, workspace, s, marks);
+    if (st != COVSPEC_OK) return st;
+  }
   st = run_select(pl, X, sf, idx_out, nullptr, nullptr, nullptr, nullptr, workspace, s, marks);
   if (st != COVSPEC_OK) return st;
   marks.mark(COVSPEC_STAGE_GATHER);

@@ -37,10 +37,10 @@ constexpr int kMaxSweeps = 30;
 
 struct JacobiCtl {
   unsigned long long maxoff[kMaxSweeps + 2];  // per sweep: bits of the largest admixture weight seen (see below)
-  unsigned int arrived;       // barrier counter of the image's workgroups (monotonic)
+  ImageBarrier bar;           // barrier of the image's workgroups; bar.failed: a wait ran into its time limit,
+                              // the result is invalid (the rows are set to NaN)
   unsigned int ticket;        // ctl[0] only: next (image, slot) to hand to a starting workgroup
   int done;
-  int failed;                 // a barrier wait ran into its time limit: the result is invalid (rows are set to NaN)
   int sweeps;
   double floor2;              // rows with squared norm below this are treated as zero
   double long2;               // squared length of the r-th longest row after the previous sweep
@@ -56,7 +56,6 @@ struct JacobiCtl {
 // measures it also reduces it, so 3e-7 leaves the energies converged to well below their last bit.
 constexpr double kRotEps = 1e-15;   // rotations below this relative size are skipped
 constexpr double kConvTol = 3e-7;
-constexpr long long kBarrierLimitTicks = 200000000LL;   // 2 s of the 100 MHz wall clock per barrier wait
 
 __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restrict__ A, int n, int nP, JacobiCtl* ctl,
                                                              const int* __restrict__ preset_done) {
@@ -71,10 +70,10 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restri
   if (threadIdx.x == 0) {
     double t = red[0] + red[1] + red[2] + red[3];
     for (int k = 0; k < kMaxSweeps + 2; ++k) ctl[b].maxoff[k] = 0ull;
-    ctl[b].arrived = 0u;
+    ctl[b].bar.arrived = 0u;
+    ctl[b].bar.failed = 0;
     ctl[b].ticket = 0u;
     ctl[b].done = preset_done ? preset_done[b] : 0;
-    ctl[b].failed = 0;
     ctl[b].sweeps = 0;
     double f = 1e-13 * t;
     ctl[b].floor2 = f * f;
@@ -91,33 +90,6 @@ __device__ __forceinline__ void tournament_pair(int np, int rd, int m, int& p, i
 constexpr int SB = 32;        // rows per super-block
 constexpr int PR = 2 * SB;    // rows per workgroup
 constexpr int HP = PR + 1;    // LDS pitch (doubles)
-
-// Barrier over the `npairs` workgroups of one image: `target` is the value cb->arrived reaches when all of
-// them have arrived (the counter only grows).  Every thread's earlier global writes are visible to every
-// thread of the image behind it.  Returns false when the wait hit its time limit or another workgroup of
-// the image reported that (cb->failed); the caller then gives up on the image.
-__device__ __forceinline__ bool image_barrier(JacobiCtl* cb, unsigned int target, int* s_flag) {
-  __threadfence();   // release at device scope (write back what the other XCDs' L2s cannot see)
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int ok = 1;
-    __hip_atomic_fetch_add(&cb->arrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    const long long t0 = wall_clock64();
-    while (__hip_atomic_load(&cb->arrived, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      if (__hip_atomic_load(&cb->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
-          wall_clock64() - t0 > kBarrierLimitTicks) {
-        ok = 0;
-        break;
-      }
-      __builtin_amdgcn_s_sleep(4);
-    }
-    if (!ok) __hip_atomic_store(&cb->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *s_flag = ok;
-  }
-  __syncthreads();
-  __threadfence();   // acquire: no stale lines when the other workgroups' rows are read
-  return *s_flag != 0;
-}
 
 // LDS of the solve kernel (file scope: shared by the kernel and the visit function below).
 __shared__ double Hs[PR * HP];
@@ -375,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
       const double meas = jacobi_visit(Ab, len2b, nP, I, J, round == 0, floor2, long2);
       if (tid == 0 && meas > 0.0) atomicMax(&cb->maxoff[sweep], (unsigned long long)__double_as_longlong(sqrt(meas)));
       target += npairs;
-      alive = image_barrier(cb, target, &s_flag);
+      alive = image_barrier_wait(&cb->bar, target, &s_flag);
     }
     if (!alive) break;
     // ---- end of the sweep: slot 0 decides convergence and finds the squared length of the r-th longest row
@@ -399,7 +371,7 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
       }
     }
     target += npairs;
-    alive = image_barrier(cb, target, &s_flag);
+    alive = image_barrier_wait(&cb->bar, target, &s_flag);
     if (alive && __hip_atomic_load(&cb->done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
   }
   if (!alive) {

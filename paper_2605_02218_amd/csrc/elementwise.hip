@@ -267,6 +267,17 @@ __global__ void fill_zero_kernel(u32x4_t* p, long n16) {
 
 inline unsigned blocks_for(long n, int per) { return (unsigned)((n + per - 1) / per); }
 
+__global__ __launch_bounds__(256) void random_scores_kernel(float* __restrict__ out, int B, int N, uint32_t seed) {
+  const long e = (long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long)B * N) return;
+  const unsigned long long b = (unsigned long long)(e / N), i = (unsigned long long)(e - (long)b * N);
+  unsigned long long z = (unsigned long long)seed * 0x9E3779B97F4A7C15ull + ((b << 32) | i) + 0x632BE59BD9B4E019ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  out[e] = (float)(unsigned int)(z >> 40) * 0x1p-24f;
+}
+
 }  // namespace
 
 hipError_t launch_transpose(const void* in, void* out, int rows, int cols, int dtype, hipStream_t st) {
@@ -339,6 +350,13 @@ hipError_t launch_fuse(const float* s_query, const float* s_act, float* s_fused,
 hipError_t launch_gather_rows(const void* X, const int32_t* idx, void* out, int B, int N, int k, long row_bytes, hipStream_t st) {
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((long)B * k)), dim3(256), 0, st, (const unsigned char*)X, idx,
                      (unsigned char*)out, N, k, row_bytes);
+  return hipGetLastError();
+}
+
+hipError_t launch_random_scores(float* out, int B, int N, uint32_t seed, hipStream_t stream) {
+  const long total = (long)B * N;
+  if (total <= 0) return hipSuccess;
+  hipLaunchKernelGGL(random_scores_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, out, B, N, seed);
   return hipGetLastError();
 }
 

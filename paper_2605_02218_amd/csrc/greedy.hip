@@ -5,8 +5,16 @@
 // norm of token i after projecting out the picked tokens is rho_i; each step picks
 // argmax rho (decided on the fp32-rounded value, ties -> lower index), forms the new
 // Cholesky column l = (G[:,p] - L L[p,:]^T) / sqrt(rho_p) and updates rho -= l^2.
-// One 1024-thread workgroup per image; L is kept transposed (Lt[t][i]) so that the
-// step-t dot products read it with unit stride across threads.
+//
+// The k steps are dependent, but inside a step the rows are independent, so an image is
+// spread over nP/64 workgroups of 64 rows each: a workgroup keeps rho of its rows in
+// registers, posts its best (key, rho) per step, all workgroups of the image meet at a
+// barrier in global memory (one per step), read the posts, agree on the pivot p, fetch
+// the pivot's Cholesky row L[p, 0..t) and extend their own 64 rows of L.  L is stored
+// transposed (Lt[t][i]) so that a workgroup's part of a column is one 512-byte run.
+// Inside a workgroup lanes are rows and the four waves split the dot product over t.
+// Workgroups take (image, slot) from a ticket counter, so the resident ones always form
+// whole images plus one partial image that is next in the dispatch order.
 #include "common.h"
 #include "kernels.h"
 
@@ -14,10 +22,120 @@ namespace covspec {
 
 namespace {
 
-constexpr int TPB = 1024;
+constexpr int TPB = 1024;   // finish kernel
+constexpr int GR = 64;      // rows per workgroup
+constexpr int GT = 256;     // threads per workgroup
+
+struct GreedyCtl {
+  ImageBarrier bar;
+  unsigned int ticket;   // ctl[0] only
+  unsigned int pad;
+};
+
+__global__ void greedy_init_kernel(GreedyCtl* ctl, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) { ctl[b].bar.arrived = 0u; ctl[b].bar.failed = 0; ctl[b].ticket = 0u; ctl[b].pad = 0u; }
+}
+
+// posts: per image [2][W] keys (u64) then [2][W] rho (fp64), double-buffered by step parity
+__global__ __launch_bounds__(GT) void greedy_kernel(const double* __restrict__ G, int n, int nP, int k, double* Lt, int32_t* __restrict__ order,
+                                                     float* __restrict__ resid, GreedyCtl* ctl, unsigned long long* posts) {
+  __shared__ double Lp[4096];
+  __shared__ double part[4][GR];
+  __shared__ unsigned long long sh_key;
+  __shared__ double sh_rho;
+  __shared__ int s_flag;
+  const int W = nP / GR;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid == 0) s_flag = (int)atomicAdd(&ctl[0].ticket, 1u);
+  __syncthreads();
+  const int ticket = s_flag;
+  __syncthreads();
+  const int b = ticket / W, slot = ticket - b * W;
+  GreedyCtl* cb = ctl + b;
+  const double* Gb = G + (long)b * nP * nP;
+  double* Ltb = Lt + (long)b * k * nP;
+  unsigned long long* keys = posts + (long)b * 4 * W;       // [2][W]
+  double* rhos = (double*)(keys + 2 * W);                   // [2][W]
+  const int i = slot * GR + lane;                           // this lane's row (all four waves hold a copy)
+
+  double rho = (i < n) ? Gb[(long)i * nP + i] : 0.0;
+  bool picked = !(i < n);
+  unsigned int target = 0;
+  bool alive = true;
+
+  for (int t = 0; t < k && alive; ++t) {
+    // ---- local argmax of float(rho) over the unpicked rows, lowest index on ties (wave 0 suffices)
+    if (w == 0) {
+      unsigned long long key = 0ull;
+      if (!picked) key = ((unsigned long long)float_order_key((float)rho) << 32) | (0xFFFFFFFFu - (uint32_t)i);
+      const unsigned long long best = wave_max(key);
+      const unsigned long long bal = __ballot(key == best && key != 0ull);
+      if (best != 0ull && lane == (int)__ffsll((long long)bal) - 1) {
+        keys[(t & 1) * W + slot] = best;
+        rhos[(t & 1) * W + slot] = rho;
+      }
+      if (best == 0ull && lane == 0) keys[(t & 1) * W + slot] = 0ull;
+    }
+    target += (unsigned int)W;
+    alive = image_barrier_wait(&cb->bar, target, &s_flag);
+    if (!alive) break;
+    // ---- global argmax over the posts
+    if (w == 0) {
+      unsigned long long key = 0ull;
+      double r = 0.0;
+      for (int q = lane; q < W; q += 64) {
+        const unsigned long long kq = keys[(t & 1) * W + q];
+        if (kq > key) { key = kq; r = rhos[(t & 1) * W + q]; }
+      }
+      const unsigned long long best = wave_max(key);
+      const unsigned long long bal = __ballot(key == best);
+      if (lane == (int)__ffsll((long long)bal) - 1) { sh_key = best; sh_rho = r; }
+    }
+    __syncthreads();
+    const int p = (int)(0xFFFFFFFFu - (uint32_t)(sh_key & 0xFFFFFFFFull));
+    const double rp = sh_rho;
+    if ((unsigned)p >= (unsigned)n) {   // cannot happen with consistent posts; never index with it
+      if (tid == 0) __hip_atomic_store(&cb->bar.failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      alive = false;
+      break;
+    }
+    if (p == i) picked = true;
+    for (int q = tid; q < t; q += GT) Lp[q] = Ltb[(long)q * nP + p];
+    __syncthreads();
+    // ---- dot products: wave w takes q = w, w+4, ...
+    double d0 = 0.0, d1 = 0.0;
+    {
+      const double* col = Ltb + i;
+      int q = w;
+      for (; q + 4 < t; q += 8) {
+        d0 = fma(col[(long)q * nP], Lp[q], d0);
+        d1 = fma(col[(long)(q + 4) * nP], Lp[q + 4], d1);
+      }
+      if (q < t) d0 = fma(col[(long)q * nP], Lp[q], d0);
+    }
+    part[w][lane] = d0 + d1;
+    __syncthreads();
+    const double piv = rp > 0.0 ? rp : 0.0;
+    const double root = sqrt(piv);
+    const double dot = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+    const double colv = (piv > 0.0 && i < n) ? (Gb[(long)p * nP + i] - dot) / root : 0.0;
+    if (w == 0) Ltb[(long)t * nP + i] = colv;
+    rho -= colv * colv;
+    if (slot == 0 && tid == 0) { order[(long)b * k + t] = p; resid[(long)b * k + t] = (float)rp; }
+  }
+  if (!alive && slot == 0) {
+    // a wait ran out: leave valid (distinct) positions and poisoned residuals behind
+    const float qnan = __uint_as_float(0x7fc00000u);
+    for (int t = tid; t < k; t += GT) { order[(long)b * k + t] = t; resid[(long)b * k + t] = qnan; }
+  }
+}
+
+// One 1024-thread workgroup per image (no barriers between workgroups): the better choice when the batch
+// alone fills the device.
 constexpr int RPT = 4;  // rows per thread: n <= 4096
 
-__global__ __launch_bounds__(TPB) void greedy_kernel(const double* __restrict__ G, int n, int nP, int k,
+__global__ __launch_bounds__(TPB) void greedy_single_kernel(const double* __restrict__ G, int n, int nP, int k,
                                                       double* __restrict__ Lt, int32_t* __restrict__ order,
                                                       float* __restrict__ resid) {
   __shared__ double Lp[4096];
@@ -116,9 +234,36 @@ __global__ __launch_bounds__(TPB) void greedy_finish_kernel(const int32_t* __res
 
 }  // namespace
 
-hipError_t launch_greedy(const double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, hipStream_t st) {
-  if (n > TPB * RPT || k > n || k > 4096) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(greedy_kernel, dim3(B), dim3(TPB), 0, st, G, n, nP, k, Lt, order, resid);
+size_t greedy_scratch_bytes(int B, int nP) {
+  return (size_t)B * sizeof(GreedyCtl) + 256 + (size_t)B * 4 * (nP / GR) * 8;
+}
+
+hipError_t launch_greedy(const double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
+                         hipStream_t st) {
+  if (nP % GR != 0 || n > nP || n > 4096 || k > n || k > 4096) return hipErrorInvalidValue;
+  const int W = nP / GR;
+  // Spreading an image over W workgroups costs a device-scope barrier per step; it pays while the batch
+  // leaves most of the device idle (measured: B = 4 and 8 gain 3-7x, B = 64 loses 2.5x).
+  if ((long)B * W > 256) {
+    hipLaunchKernelGGL(greedy_single_kernel, dim3(B), dim3(TPB), 0, st, G, n, nP, k, Lt, order, resid);
+    return hipGetLastError();
+  }
+  // the workgroups of one image wait for one another, so one image has to fit the device
+  static int capacity = 0;
+  if (capacity == 0) {
+    int dev = 0, per_cu = 0, cus = 0;
+    hipError_t e;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, greedy_kernel, GT, 0)) != hipSuccess) return e;
+    if (per_cu < 1 || cus < 1) return hipErrorInvalidValue;
+    capacity = per_cu * cus;
+  }
+  if (W > capacity) return hipErrorInvalidValue;
+  GreedyCtl* ctl = (GreedyCtl*)scratch;
+  unsigned long long* posts = (unsigned long long*)((char*)scratch + (((size_t)B * sizeof(GreedyCtl) + 255) / 256) * 256);
+  hipLaunchKernelGGL(greedy_init_kernel, dim3((B + 255) / 256), dim3(256), 0, st, ctl, B);
+  hipLaunchKernelGGL(greedy_kernel, dim3((unsigned)(B * W)), dim3(GT), 0, st, G, n, nP, k, Lt, order, resid, ctl, posts);
   return hipGetLastError();
 }
 

@@ -95,6 +95,10 @@ hipError_t launch_gather_rows(const void* X, const int32_t* idx, void* out, int 
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 
+// Reproducible uniform scores for the random-selection ablation: out[b, i] = top 24 bits of
+// mix64(seed * 0x9E3779B97F4A7C15 + (b << 32 | i) + 0x632BE59BD9B4E019) times 2^-24 (mix64 = SplitMix64 output function).
+hipError_t launch_random_scores(float* out, int B, int N, uint32_t seed, hipStream_t stream);
+
 // ---------------------------------------------------------------- select.hip
 // Per image: positions of the m largest of scores[b, 0..n) (ties -> lower position), ascending.
 // out[b,j] = map ? map[b*n + pos] : pos.   n <= 16384.
@@ -134,7 +138,9 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
 // ---------------------------------------------------------------- greedy.hip
 // Greedy residual picks (variant): pivoted Cholesky of G[b] (fp64, pitch nP).  Lt is scratch [B][k][nP] fp64.
 // order[b,t] = local position picked at step t, resid[b,t] = residual squared norm at that pick.
-hipError_t launch_greedy(const double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid,
+// nP % 64 == 0; `scratch` holds greedy_scratch_bytes(B, nP) bytes (barrier counters and per-step posts).
+size_t greedy_scratch_bytes(int B, int nP);
+hipError_t launch_greedy(const double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
                          hipStream_t stream);
 // idx_out[b,:] = sort ascending of idx_m[b, order[b,:]];  pick_out[b,t] = idx_m[b, order[b,t]] (optional).
 hipError_t launch_greedy_finish(const int32_t* order, const int32_t* idx_m, int B, int M, int k, int32_t* idx_out,

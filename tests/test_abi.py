@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_params_struct_layout_matches_header():
-    assert ctypes.sizeof(Bd.CovspecParams) == 14 * 4
+    assert ctypes.sizeof(Bd.CovspecParams) == 15 * 4
 
 
 def _p(**kw):
@@ -46,7 +46,7 @@ def test_resolve_defaults():
 
 @pytest.mark.parametrize("kw,status", [
     (dict(batch=0), Bd.INVALID_ARG), (dict(n_query=0), Bd.INVALID_ARG), (dict(n_heads=3), Bd.INVALID_ARG),
-    (dict(dtype=2), Bd.INVALID_ARG), (dict(rel_mode=2), Bd.INVALID_ARG), (dict(lr_mode=-1), Bd.INVALID_ARG),
+    (dict(dtype=2), Bd.INVALID_ARG), (dict(rel_mode=2), Bd.INVALID_ARG), (dict(lr_mode=-1), Bd.INVALID_ARG), (dict(lr_mode=4), Bd.INVALID_ARG),
     (dict(lam=1.5), Bd.INVALID_ARG), (dict(lam=float("nan")), Bd.INVALID_ARG),
     (dict(keep_k=200), Bd.INVALID_ARG),                       # k > M
     (dict(preselect_m=600), Bd.INVALID_ARG),                  # M > N
@@ -70,6 +70,14 @@ def test_invalid_params_are_rejected_on_the_host(kw, status):
 
 def test_greedy_mode_does_not_need_a_rank():
     assert C.workspace_size(_p(lr_mode=C.LR_GREEDY_RESIDUAL, rank_r=128)) > 0
+
+
+def test_ablation_selectors_need_no_rank_and_no_preselection_limit():
+    assert C.workspace_size(_p(lr_mode=C.LR_SCORE_TOPK, rank_r=128)) > 0
+    assert C.workspace_size(_p(lr_mode=C.LR_RANDOM, rank_r=128, seed=7)) > 0
+    big = dict(n_tokens=16384, keep_k=4097, preselect_m=8194, rank_r=8)
+    assert C.workspace_size(_p(lr_mode=C.LR_SCORE_TOPK, **big)) > 0
+    assert C.workspace_size(_p(lr_mode=C.LR_SCORE_TOPK)) < C.workspace_size(_p())   # no low-rank buffers
 
 
 def test_entry_points_reject_null_pointers_and_small_workspaces_before_any_launch():

@@ -138,10 +138,72 @@ def test_keep_everything_is_identity(C):
     w = SMALL["bf16-ragged"]
     batch = U.gen_batch(w)
     dev = U.upload(batch, w.dtype)
-    for lr in (0, 1):
+    for lr in (0, 1, 2, 3):   # full-token drafting, whatever the selector
         p = U.lib_params(C, w, w.batch, lr_mode=lr, keep_k=w.n_tokens, preselect_m=w.n_tokens, rank_r=5)
         idx, _ = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
         np.testing.assert_array_equal(_cpu(idx), np.tile(np.arange(w.n_tokens, dtype=np.int32), (w.batch, 1)))
+
+
+@pytest.mark.parametrize("name", ["fp32-ragged", "bf16-ragged"])
+def test_selector_ablations_match_oracle(C, name):
+    # the selector ablations of Table II / Sec. III-A.3: score-only top-k and seeded random selection
+    import torch
+    w = SMALL[name]
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    X = batch["X"].view(np.int16) if w.dtype == I.BF16 else batch["X"]
+    tdt = {I.BF16: torch.int16, I.FP32: torch.float32}[w.dtype]
+    for lr, extra in ((C.LR_SCORE_TOPK, {}), (C.LR_RANDOM, dict(seed=20260502)), (C.LR_RANDOM, dict(seed=7))):
+        p = U.lib_params(C, w, w.batch, lr_mode=lr, **extra)
+        idx, tok = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+        idx, tok = _cpu(idx), tok.view(tdt).cpu().numpy()
+        for b in range(w.batch):
+            ref = U.oracle_image(w, batch, b, U.oracle_params(w, lr_mode=lr, **extra))
+            np.testing.assert_array_equal(idx[b], ref["idx"], err_msg="lr_mode %d %r image %d" % (lr, extra, b))
+            np.testing.assert_array_equal(tok[b], X[b][idx[b]])
+        if lr == C.LR_RANDOM:
+            out = C.select(p, dev["X"], None)                        # needs no scores
+            np.testing.assert_array_equal(_cpu(out["idx"]), idx)
+            assert not np.array_equal(idx[0], idx[1])                # images draw independently
+        else:
+            sf32 = np.stack([O.decision_values(U.oracle_image(w, batch, b, U.oracle_params(w))["s_fused"]) for b in range(w.batch)])
+            out = C.select(p, dev["X"], torch.from_numpy(sf32).cuda())
+            for b in range(w.batch):
+                np.testing.assert_array_equal(_cpu(out["idx"])[b], O.top_indices(sf32[b], w.keep_k))
+                np.testing.assert_array_equal(_cpu(out["idx_m"])[b], O.top_indices(sf32[b], w.preselect_m))
+
+
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+def test_activity_only_and_query_only_fusion(C, lam):
+    w = SMALL["bf16-ragged"]
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    p = U.lib_params(C, w, w.batch, lam=lam)
+    _, _, sf = C.score(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    idx, _ = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    for b in range(w.batch):
+        ref = U.oracle_image(w, batch, b, U.oracle_params(w, lam=lam))
+        U.assert_scores_close(_cpu(sf)[b], ref["s_fused"], w.dtype, "s_fused lambda %g" % lam)
+        np.testing.assert_array_equal(_cpu(idx)[b], ref["idx"])
+
+
+def test_flat_spectrum_takes_the_full_eigen_solve(C):
+    # Features that are mostly white noise: the eigenvalues of the Gram matrix barely decay past the few factor
+    # directions, so the block iteration of the low-rank stage cannot converge in its fixed number of steps, its
+    # residual check fails and the image is solved by the full Jacobi iteration instead.  Same bars as elsewhere.
+    w = I.small_workload(cid=15, name="flat", batch=2, n_tokens=400, d_model=256, dtype=I.BF16, n_query=4, n_heads=2,
+                         keep_k=100, preselect_m=320, rank_r=60, factor_rank=16, n_act_layers=1, noise_std=1.0)
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    import torch
+    op = U.oracle_params(w)
+    refs = [U.oracle_image(w, batch, b, op) for b in range(w.batch)]
+    sf32 = np.stack([O.decision_values(r["s_fused"]) for r in refs])
+    out = C.select(U.lib_params(C, w, w.batch), dev["X"], torch.from_numpy(sf32).cuda())
+    for b, ref in enumerate(refs):
+        assert ref["sigma_gap"] > 1e-3, "workload has no usable gap at r: %r" % ref["sigma_gap"]
+        U.assert_scores_close(_cpu(out["c"])[b], ref["c"], w.dtype, "flat c[%d]" % b, tol=1e-4)
+        np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"], err_msg="margin_topk=%r" % ref["margin_topk"])
 
 
 def test_select_ties_and_exact_duplicates(C):

@@ -352,3 +352,58 @@ def test_low_rank_stage_uses_raw_features_not_embeddings():
     b = O.reduce(X, None, Q, None, 5.0 * Wk, p)
     np.testing.assert_array_equal(a["idx"], b["idx"])
     np.testing.assert_allclose(a["c"], b["c"], rtol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# selector ablations (Table II rows "full-token" / "random-token"; Sec. III-A.3 "the M highest-scoring tokens")
+# --------------------------------------------------------------------------
+def test_mix64_reproduces_the_published_splitmix64_outputs():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "splitmix64_seed0.txt")
+    want = [int(l, 16) for l in open(path) if l.strip() and not l.startswith("#")]
+    gamma = 0x9E3779B97F4A7C15
+    got = [O.mix64(((i + 1) * gamma) & ((1 << 64) - 1)) for i in range(len(want))]
+    assert got == want
+
+
+def test_random_scores_are_24_bit_uniforms_keyed_by_seed_image_and_token():
+    u = O.random_scores(3, 5, 4096)
+    assert np.all((u >= 0) & (u < 1)) and np.all(u * 2 ** 24 == np.floor(u * 2 ** 24))
+    assert np.array_equal(u.astype(np.float32).astype(np.float64), u)          # exact in float32
+    # the word construction, restated: seed * gamma + (image << 32 | token) + constant, top 24 bits of the mix
+    word = (3 * 0x9E3779B97F4A7C15 + ((5 << 32) | 17) + 0x632BE59BD9B4E019) % (1 << 64)
+    assert u[17] == (O.mix64(word) >> 40) / 2.0 ** 24
+    # different seed / image / token give different streams; same arguments give the same stream
+    assert np.array_equal(u, O.random_scores(3, 5, 4096))
+    assert not np.array_equal(u, O.random_scores(4, 5, 4096)) and not np.array_equal(u, O.random_scores(3, 6, 4096))
+    # uniformity: mean and variance of U(0,1), and a coarse chi-square over 16 bins (dof 15, 99.9 % point 37.7)
+    big = O.random_scores(11, 0, 1 << 16)
+    assert abs(big.mean() - 0.5) < 5e-3 and abs(big.var() - 1 / 12) < 2e-3
+    counts = np.bincount((big * 16).astype(int), minlength=16)
+    assert ((counts - 4096.0) ** 2 / 4096.0).sum() < 37.7
+
+
+def test_random_selection_is_a_uniform_draw_without_replacement():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((64, 8))
+    hits = np.zeros(64)
+    for seed in range(400):
+        out = O.select(X, None, O.Params(lr_mode=O.LR_RANDOM, keep_k=16, preselect_m=32, seed=seed), image=2)
+        idx = out["idx"]
+        assert idx.dtype == np.int32 and len(idx) == 16 and np.all(np.diff(idx) > 0)
+        assert np.array_equal(idx, O.top_indices(O.random_scores(seed, 2, 64), 16))
+        hits[idx] += 1
+    # every token is kept with probability k/N = 1/4: 400 draws -> mean 100, sd 8.7
+    assert abs(hits.mean() - 100) < 1e-9 and hits.min() > 60 and hits.max() < 140
+
+
+def test_score_only_selection_keeps_the_k_highest_fused_scores():
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((50, 6))
+    s = rng.standard_normal(50)
+    out = O.select(X, s, O.Params(lr_mode=O.LR_SCORE_TOPK, keep_k=7, preselect_m=20))
+    assert set(out["idx"]) == set(np.argsort(-s, kind="stable")[:7]) and np.all(np.diff(out["idx"]) > 0)
+    assert set(out["idx"]) <= set(out["idx_m"]) and len(out["idx_m"]) == 20
+    # the low-rank modes may keep different tokens from the same pre-selection
+    full = O.select(X, s, O.Params(lr_mode=O.LR_ENERGY_TOPK, keep_k=7, preselect_m=20, rank_r=3))
+    assert set(full["idx"]) <= set(out["idx_m"])

@@ -56,7 +56,7 @@ def oracle_image(w: I.Workload, batch: Dict[str, np.ndarray], b: int, p: O.Param
     H = I.as_f64(batch["hidden"][b], w.dtype) if use_hidden else None
     Wq = I.as_f64(batch["Wq"], w.dtype) if use_wq else None
     Wk = I.as_f64(batch["Wk"], w.dtype) if use_wk else None
-    return O.reduce(X, H, Q, Wq, Wk, p)
+    return O.reduce(X, H, Q, Wq, Wk, p, image=b)
 
 
 def assert_scores_close(got: np.ndarray, ref: np.ndarray, dtype: int, what: str, tol: Optional[float] = None):
