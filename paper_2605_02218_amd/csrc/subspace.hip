@@ -49,53 +49,19 @@ __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
 // Pivots are floored at 1e-28 * trace(first block) so that a numerically rank-deficient block cannot
 // produce NaNs (the residual check afterwards decides whether the result is usable).
 // Dynamic LDS: 2 * 64 * 65 doubles.
-struct CholCtl {
-  ImageBarrier bar;
-  unsigned int ticket;   // ctl[0] only; grows over the launches of one solve
-  unsigned int pad;
-};
-
-__global__ void chol_ctl_init_kernel(CholCtl* ctl, int B) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < B) { ctl[b].bar.arrived = 0u; ctl[b].bar.failed = 0; ctl[b].ticket = 0u; ctl[b].pad = 0u; }
-}
-
-__global__ __launch_bounds__(512) void chol_kernel(double* S, double* Dinv, int P, const int* __restrict__ skip, int W, CholCtl* ctl,
-                                                    unsigned int base_ticket, unsigned int base_target) {
+__global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, const int* __restrict__ skip) {
   extern __shared__ double lds[];
-  __shared__ int s_flag;
   double* a = lds;                  // [64][65] diagonal block, later the inverse of its factor
   double* fac = lds + NB * NBP;     // [64][65] the factor (lower triangle) and scratch (upper triangle)
-  int b = blockIdx.x, slot = 0;
-  if (W > 1) {   // (image, slot) by ticket, see the header
-    if (threadIdx.x == 0) s_flag = (int)(atomicAdd(&ctl[0].ticket, 1u) - base_ticket);
-    __syncthreads();
-    const int ticket = s_flag;
-    __syncthreads();
-    b = ticket / W;
-    slot = ticket - b * W;
-  }
+  const int b = blockIdx.x;
   if (skip && skip[b]) return;
-  unsigned int target = base_target;
-  // all workgroups of the image: __syncthreads() when there is one, the global-memory barrier otherwise
-  auto sync_image = [&]() -> bool {
-    if (W == 1) { __syncthreads(); return true; }
-    target += (unsigned int)W;
-    return image_barrier_wait(&ctl[b].bar, target, &s_flag);
-  };
-  const int NW = 8 * W;             // waves that share the image
-
   double* Sb = S + (long)b * P * P;
   const int nblk = P / NB;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i16 = lane & 15, kq = lane >> 4;
-  const int gw = slot * 8 + w;      // this wave among them
   double floor_ = 0.0;
-  bool alive = true;
 
-  for (int J = 0; J < nblk && alive; ++J) {
+  for (int J = 0; J < nblk; ++J) {
     const int j0 = J * NB;
-    double* Db = Dinv + ((long)b * nblk + J) * NB * NB;
-    if (slot == 0) {
     for (int e = tid; e < NB * NB; e += 512) {
       const int i = e >> 6, j = e & 63;
       a[i * NBP + j] = (j <= i) ? Sb[(long)(j0 + i) * P + j0 + j] : 0.0;
@@ -170,17 +136,14 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* Dinv, int 
       }
       __syncthreads();
     }
-    for (int e = tid; e < NB * NB; e += 512) Db[e] = a[(e >> 6) * NBP + (e & 63)];
-    }   // slot == 0
     double* inv = a;
-    if (!(alive = sync_image())) break;
-    if (slot != 0) {   // the other workgroups fetch the inverse that slot 0 published
-      for (int e = tid; e < NB * NB; e += 512) inv[(e >> 6) * NBP + (e & 63)] = Db[e];
-      __syncthreads();
+    {
+      double* Db = Dinv + ((long)b * nblk + J) * NB * NB;
+      for (int e = tid; e < NB * NB; e += 512) Db[e] = inv[(e >> 6) * NBP + (e & 63)];
     }
     // ---- panel: X = S[I,J] inv^T, 16-row tiles dealt to the waves
     const int below = P - j0 - NB;
-    for (int t = gw; t < below / 16; t += NW) {
+    for (int t = w; t < below / 16; t += 8) {
       const long rb = j0 + NB + 16 * t;
       f64x4_t f[4], out[4];
 #pragma unroll
@@ -199,14 +162,14 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* Dinv, int 
 #pragma unroll
         for (int v = 0; v < 4; ++v) Sb[(rb + 4 * v + kq) * P + j0 + 16 * y + i16] = out[y][v];
     }
-    if (!(alive = sync_image())) break;
+    __syncthreads();
     // ---- trailing update, unit = 16 rows of block I x the 64 columns of block I' <= I.  Every wave takes a
     //      contiguous range of units, so consecutive units mostly share I' and its fragments stay in registers;
     //      all loads of a unit are issued before its MFMAs.
     {
       const int nb = below / NB;
       const int units = 2 * nb * (nb + 1);            // 4 * nb (nb + 1) / 2
-      const int u0 = (int)((long)units * gw / NW), u1 = (int)((long)units * (gw + 1) / NW);
+      const int u0 = (int)((long)units * w / 8), u1 = (int)((long)units * (w + 1) / 8);
       // unit u -> pair index u / 4 -> (I, I2) with I (I + 1) / 2 + I2 = pair index
       int I = 0, I2 = 0;
       {
@@ -252,14 +215,7 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* Dinv, int 
         }
       }
     }
-    alive = sync_image();
-  }
-  if (!alive) {
-    // a wait ran out: poison the first inverted block, so that everything derived from this factor is NaN and
-    // the residual check sends the image to the fallback solve
-    const double qnan = __longlong_as_double(0x7ff8000000000000LL);
-    double* D0 = Dinv + (long)b * nblk * NB * NB;
-    for (int e = tid; e < NB * NB; e += 512) D0[e] = qnan;
+    __syncthreads();
   }
 }
 
@@ -365,8 +321,7 @@ int subspace_block(int n, int r) {
 size_t subspace_workspace_bytes(int B, int n, int nP, int P) {
   if (P <= 0) return 0;
   const size_t blk = (size_t)B * P * nP * 8;
-  return 2 * blk + (size_t)P * nP * 8 + 2 * (size_t)B * P * P * 8 + (size_t)B * P * NB * 8 + (size_t)B * P * 8 + 1024 + (size_t)B * 4 +
-         (size_t)B * sizeof(CholCtl) + 256;
+  return 2 * blk + (size_t)P * nP * 8 + 2 * (size_t)B * P * P * 8 + (size_t)B * P * NB * 8 + (size_t)B * P * 8 + 1024 + (size_t)B * 4;
 }
 
 // Runs the iteration on G[b] (n x n, pitch nP, untouched).  On return, for images with ok[b] = 1, rows
@@ -395,21 +350,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   double* H = S + (size_t)B * P * P;
   double* D = H + (size_t)B * P * P;
   double* lam = D + (size_t)B * P * NB;
-  CholCtl* cctl = (CholCtl*)(((uintptr_t)(lam + (size_t)B * P) + 255) & ~(uintptr_t)255);
   const int nblk = P / NB;
-  // Workgroups per image of the Cholesky kernel: its trailing update is bound by the MFMA rate of one CU, so a
-  // small batch spreads an image over several (at the price of three global-memory barriers per panel); a
-  // batch that fills a good part of the device by itself does not.
-  int cholW = 1;
-  if (B <= 32 && nblk >= 3) {
-    cholW = 256 / B;
-    if (cholW > 8) cholW = 8;
-    const int units0 = 2 * (nblk - 1) * nblk;          // units of the first trailing update
-    if (cholW > (units0 + 7) / 8) cholW = (units0 + 7) / 8;
-    if (cholW < 1) cholW = 1;
-  }
-  unsigned int chol_calls = 0;
-  if (cholW > 1) hipLaunchKernelGGL(chol_ctl_init_kernel, dim3((B + 255) / 256), dim3(256), 0, st, cctl, B);
   hipError_t e;
 
   auto gemm_yt_g = [&](const double* X, double* out) {   // out = X G  (P x nP)
@@ -426,9 +367,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     g.epilogue = EPI_STORE_F64;
     g.lower_only = true;
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
-    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)(B * cholW)), dim3(512), kCholLds, st, S, D, P, (const int*)nullptr, cholW, cctl,
-                       chol_calls * (unsigned)(B * cholW), chol_calls * (unsigned)(3 * nblk * cholW));
-    ++chol_calls;
+    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), kCholLds, st, S, D, P, (const int*)nullptr);
     hipLaunchKernelGGL(trsm_kernel, dim3((unsigned)(B * (nP / NB))), dim3(256), 0, st, X, (const double*)S, (const double*)D, P, nP,
                        nP / NB, (const int*)nullptr);
     return hipGetLastError();
