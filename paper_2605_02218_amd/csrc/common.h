@@ -87,10 +87,14 @@ struct ImageBarrier {
 constexpr long long kBarrierLimitTicks = 200000000LL;   // 2 s
 
 __device__ __forceinline__ bool image_barrier_wait(ImageBarrier* bar, unsigned int target, int* s_flag) {
-  __threadfence();
+  // Every wave first waits until its own stores have been acknowledged by the L2 (vmcnt counts loads and
+  // stores on this architecture); the cache maintenance itself acts on the CU's L1 and the XCD's L2, not on a
+  // wave, so one thread issues it for the workgroup: write-back before the arrival, invalidate after the wait.
+  __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
   __syncthreads();
   if (threadIdx.x == 0) {
     int ok = 1;
+    __threadfence();
     __hip_atomic_fetch_add(&bar->arrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     const long long t0 = wall_clock64();
     while (__hip_atomic_load(&bar->arrived, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
@@ -102,10 +106,10 @@ __device__ __forceinline__ bool image_barrier_wait(ImageBarrier* bar, unsigned i
       __builtin_amdgcn_s_sleep(4);
     }
     if (!ok) __hip_atomic_store(&bar->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();
     *s_flag = ok;
   }
   __syncthreads();
-  __threadfence();
   return *s_flag != 0;
 }
 
