@@ -278,6 +278,11 @@ __global__ __launch_bounds__(256) void random_scores_kernel(float* __restrict__ 
   out[e] = (float)(unsigned int)(z >> 40) * 0x1p-24f;
 }
 
+__global__ void fill_int_kernel(int* __restrict__ p, int n, int value) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+
 }  // namespace
 
 hipError_t launch_transpose(const void* in, void* out, int rows, int cols, int dtype, hipStream_t st) {
@@ -357,6 +362,12 @@ hipError_t launch_random_scores(float* out, int B, int N, uint32_t seed, hipStre
   const long total = (long)B * N;
   if (total <= 0) return hipSuccess;
   hipLaunchKernelGGL(random_scores_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, out, B, N, seed);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_int(int* p, int n, int value, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n, value);
   return hipGetLastError();
 }
 

@@ -94,6 +94,7 @@ hipError_t launch_gather_rows(const void* X, const int32_t* idx, void* out, int 
                               hipStream_t stream);
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
+hipError_t launch_fill_int(int* p, int n, int value, hipStream_t stream);
 
 // Reproducible uniform scores for the random-selection ablation: out[b, i] = top 24 bits of
 // mix64(seed * 0x9E3779B97F4A7C15 + (b << 32 | i) + 0x632BE59BD9B4E019) times 2^-24 (mix64 = SplitMix64 output function).

@@ -29,6 +29,7 @@ constexpr int NBP = NB + 1;   // LDS pitch
 // 1e-9 perturbs an energy by at most 1e-9 / (relative gap at r) relative, the same order; converged blocks
 // sit at 1e-11..1e-13, unconverged ones orders above.
 constexpr double kRitzTol = 1e-9;
+constexpr double kSkipCond = 1e3;   // see chol_kernel
 constexpr size_t kCholLds = (size_t)(2 * NB * NBP) * sizeof(double);
 
 __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
@@ -49,13 +50,14 @@ __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
 // Pivots are floored at 1e-28 * trace(first block) so that a numerically rank-deficient block cannot
 // produce NaNs (the residual check afterwards decides whether the result is usable).
 // Dynamic LDS: 2 * 64 * 65 doubles.
-__global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, const int* __restrict__ skip) {
+__global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, int* skip_at, int step, int may_skip_next) {
   extern __shared__ double lds[];
   double* a = lds;                  // [64][65] diagonal block, later the inverse of its factor
   double* fac = lds + NB * NBP;     // [64][65] the factor (lower triangle) and scratch (upper triangle)
   const int b = blockIdx.x;
-  if (skip && skip[b]) return;
+  if (skip_at && skip_at[b] == step) return;   // this image does not orthonormalise at this step
   double* Sb = S + (long)b * P * P;
+  double dmin = 1e300, dmax = 0.0;             // extremes of the factor's diagonal (thread 0)
   const int nblk = P / NB;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i16 = lane & 15, kq = lane >> 4;
   double floor_ = 0.0;
@@ -109,6 +111,8 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
       }
       __syncthreads();
     }
+    if (tid == 0)
+      for (int k = 0; k < NB; ++k) { const double d = fac[k * NBP + k]; dmin = fmin(dmin, d); dmax = fmax(dmax, d); }
     // ---- inverse of the factor into `a`, by doubling: with L = [A 0; C D], inv(L) = [inv(A) 0; -inv(D) C inv(A) inv(D)].
     //      Level s joins the inverses of the s x s diagonal blocks pairwise; the intermediate C inv(A) is parked,
     //      transposed, in the unused upper triangle of `fac`.
@@ -217,6 +221,11 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
     }
     __syncthreads();
   }
+  // The diagonal of L spans about the condition number of the block just factored (rows = Q G with Q
+  // orthonormal, so about lambda_1 / lambda_P).  When it is small, the NEXT step may multiply by G again without
+  // orthonormalising first: the block then has the square of this condition number, and Cholesky-QR stays
+  // accurate up to ~1e7.  skip_at[b] = the step at which this image skips, or -1.
+  if (tid == 0 && skip_at) skip_at[b] = (may_skip_next && dmin > 0.0 && dmax < kSkipCond * dmin) ? step + 1 : -1;
 }
 
 // Yt[b] <- L^-1 Yt[b] (P x nP, pitch nP) by blocked forward substitution with the factor chol_kernel left
@@ -226,9 +235,9 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
 // T comes out of the MFMA in exactly the layout its B operand wants (lane = column, register = k), so the
 // second product takes the accumulator registers as they are.
 __global__ __launch_bounds__(256) void trsm_kernel(double* Yt, const double* __restrict__ S, const double* __restrict__ Dinv,
-                                                    int P, int nP, int wg_per_image, const int* __restrict__ skip) {
+                                                    int P, int nP, int wg_per_image, const int* __restrict__ skip_at, int step) {
   const int b = blockIdx.x / wg_per_image, cw = blockIdx.x - b * wg_per_image;
-  if (skip && skip[b]) return;
+  if (skip_at && skip_at[b] == step) return;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, i16 = lane & 15, kq = lane >> 4;
   const int col = cw * 64 + w * 16 + i16;    // nP % 64 == 0, so every column exists
   const int nblk = P / NB;
@@ -321,7 +330,8 @@ int subspace_block(int n, int r) {
 size_t subspace_workspace_bytes(int B, int n, int nP, int P) {
   if (P <= 0) return 0;
   const size_t blk = (size_t)B * P * nP * 8;
-  return 2 * blk + (size_t)P * nP * 8 + 2 * (size_t)B * P * P * 8 + (size_t)B * P * NB * 8 + (size_t)B * P * 8 + 1024 + (size_t)B * 4;
+  return 2 * blk + (size_t)P * nP * 8 + 2 * (size_t)B * P * P * 8 + (size_t)B * P * NB * 8 + (size_t)B * P * 8 + 1024 + (size_t)B * 4 +
+         (size_t)B * 4 + 256;
 }
 
 // Runs the iteration on G[b] (n x n, pitch nP, untouched).  On return, for images with ok[b] = 1, rows
@@ -350,6 +360,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   double* H = S + (size_t)B * P * P;
   double* D = H + (size_t)B * P * P;
   double* lam = D + (size_t)B * P * NB;
+  int* skip_at = (int*)(((uintptr_t)(lam + (size_t)B * P) + 255) & ~(uintptr_t)255);   // [B]
   const int nblk = P / NB;
   hipError_t e;
 
@@ -360,16 +371,20 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     g.epilogue = EPI_STORE_F64;
     return launch_gemm64_nt(g, true, true, st);
   };
-  auto cholqr = [&](double* X) -> hipError_t {           // X <- L^-1 X with X X^T = L L^T
+  // X <- L^-1 X with X X^T = L L^T.  step >= 0: images with skip_at[b] == step leave X alone, and the factorisation
+  // may schedule the skip of step + 1 (may_skip_next); step < 0: unconditional.
+  auto cholqr = [&](double* X, int step, bool may_skip_next) -> hipError_t {
     GemmArgs g;
     g.A = X; g.B = X; g.C = S; g.M = P; g.N = P; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = P;
     g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)P * nP; g.strideC = (long)P * P;
     g.epilogue = EPI_STORE_F64;
     g.lower_only = true;
+    if (step >= 0) { g.skip = skip_at; g.skip_if = step; }
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
-    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), kCholLds, st, S, D, P, (const int*)nullptr);
+    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), kCholLds, st, S, D, P, step >= 0 ? skip_at : (int*)nullptr, step,
+                       may_skip_next ? 1 : 0);
     hipLaunchKernelGGL(trsm_kernel, dim3((unsigned)(B * (nP / NB))), dim3(256), 0, st, X, (const double*)S, (const double*)D, P, nP,
-                       nP / NB, (const int*)nullptr);
+                       nP / NB, step >= 0 ? (const int*)skip_at : (const int*)nullptr, step);
     return hipGetLastError();
   };
 
@@ -386,9 +401,16 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   if (probe_end && (e = hipEventRecord(probe_end, st)) != hipSuccess) return e;
   double* cur = Yt;
   double* oth = Zt;
+  if ((e = launch_fill_int(skip_at, B, -1, st)) != hipSuccess) return e;
   for (int it = 0; it < iters; ++it) {
-    if ((e = cholqr(cur)) != hipSuccess) return e;
-    if (it + 1 == iters && (e = cholqr(cur)) != hipSuccess) return e;   // second pass: orthonormal to rounding
+    if (it + 1 < iters) {
+      // the start block is not (orthonormal) x G, so its factor says nothing about the next step: no skip after it = 0;
+      // the last step always orthonormalises
+      if ((e = cholqr(cur, it, it >= 1 && it + 2 < iters)) != hipSuccess) return e;
+    } else {
+      if ((e = cholqr(cur, -1, false)) != hipSuccess) return e;
+      if ((e = cholqr(cur, -1, false)) != hipSuccess) return e;          // second pass: orthonormal to rounding
+    }
     if ((e = gemm_yt_g(cur, oth)) != hipSuccess) return e;               // oth = Q^T G
     double* t = cur; cur = oth; oth = t;
   }
