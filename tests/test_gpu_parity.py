@@ -187,6 +187,49 @@ def test_activity_only_and_query_only_fusion(C, lam):
         np.testing.assert_array_equal(_cpu(idx)[b], ref["idx"])
 
 
+EDGE = {
+    # one keyword, one act layer, tiny width; M spans less than one 64-row pair of the eigen-solve
+    "tiny-bf16": dict(batch=3, n_tokens=50, d_model=16, dtype=I.BF16, n_query=1, n_heads=1, keep_k=5, preselect_m=20,
+                      rank_r=3, factor_rank=8, n_act_layers=1),
+    # the most act layers the kernels take, keep everything but one token, rank 1
+    "k8-bf16": dict(batch=2, n_tokens=64, d_model=8, dtype=I.BF16, n_query=2, n_heads=2, keep_k=63, preselect_m=64,
+                    rank_r=1, factor_rank=4, n_act_layers=8),
+    # fp32, width not a multiple of 8, keep a single token
+    "one-fp32": dict(batch=2, n_tokens=40, d_model=12, dtype=I.FP32, n_query=3, n_heads=3, keep_k=1, preselect_m=2,
+                     rank_r=1, factor_rank=6, n_act_layers=2),
+    # M just above two row blocks (padded order 192), rank close to M: full Jacobi on three pairs
+    "pad-bf16": dict(batch=2, n_tokens=130, d_model=264, dtype=I.BF16, n_query=9, n_heads=3, keep_k=30, preselect_m=129,
+                     rank_r=28, factor_rank=64, n_act_layers=1),
+    # no pre-selection (M = N), block iteration with the smallest block
+    "m-eq-n": dict(batch=2, n_tokens=200, d_model=96, dtype=I.BF16, n_query=4, n_heads=4, keep_k=100, preselect_m=200,
+                   rank_r=40, factor_rank=80, n_act_layers=1),
+}
+
+
+@pytest.mark.parametrize("name", list(EDGE))
+def test_edge_shapes_match_oracle(C, name):
+    import torch
+    w = I.small_workload(cid=20 + list(EDGE).index(name), name=name, **EDGE[name])
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    X = batch["X"].view(np.int16) if w.dtype == I.BF16 else batch["X"]
+    tdt = {I.BF16: torch.int16, I.FP32: torch.float32}[w.dtype]
+    for modes in ((0, 0), (1, 1)):
+        # greedy picks beyond the rank of the features (at most d) are decided by rounding noise: keep k <= d / 2 there
+        over = dict(keep_k=min(w.keep_k, w.d_model // 2)) if modes[1] == 1 else {}
+        p = U.lib_params(C, w, w.batch, rel_mode=modes[0], lr_mode=modes[1], **over)
+        sq, sa, sf = C.score(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+        idx, tok = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+        idx, tok = _cpu(idx), tok.view(tdt).cpu().numpy()
+        for b in range(w.batch):
+            ref = U.oracle_image(w, batch, b, U.oracle_params(w, rel_mode=modes[0], lr_mode=modes[1], **over))
+            U.assert_scores_close(_cpu(sq)[b], ref["s_query"], w.dtype, "%s s_query[%d] modes %r" % (name, b, modes))
+            U.assert_scores_close(_cpu(sf)[b], ref["s_fused"], w.dtype, "%s s_fused[%d] modes %r" % (name, b, modes))
+            np.testing.assert_array_equal(idx[b], ref["idx"], err_msg="%s image %d modes %r margins %r %r" % (
+                name, b, modes, ref.get("margin_topm"), ref.get("margin_topk")))
+            np.testing.assert_array_equal(tok[b], X[b][idx[b]])
+
+
 def test_flat_spectrum_takes_the_full_eigen_solve(C):
     # Features that are mostly white noise: the eigenvalues of the Gram matrix barely decay past the few factor
     # directions, so the block iteration of the low-rank stage cannot converge in its fixed number of steps, its
