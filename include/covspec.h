@@ -171,6 +171,47 @@ int covspec_reduce_staged(const covspec_params* p, const void* X, const void* hi
  */
 int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols, int32_t* inner);
 
+/*
+ * Speculative verification over the vocabulary (paper Sec. II-A: the softmax distributions of the
+ * draft and the target model, the acceptance probability of a drafted token, and the residual
+ * distribution a correction is drawn from after the first rejection).  For each of n_seq sequences
+ * with n_draft drafted positions tau = 0..n_draft-1 and vocabulary width vocab:
+ *   p_t = softmax(z_target[s, tau, :]), p_d = softmax(z_draft[s, tau, :]);
+ *   alpha[s, tau] = min(1, p_t(y) / p_d(y)) at the drafted token y = tokens[s, tau];
+ *   position tau is accepted iff u_accept[s, tau] < alpha[s, tau] (both fp32);
+ *   n_accept[s] = number of accepted positions before the first rejection;
+ *   if n_accept[s] < n_draft: correction[s] = the smallest word w whose cumulative residual mass
+ *   sum_{v <= w} max(p_t(v) - p_d(v), 0) at tau = n_accept[s] exceeds u_resample[s] times the total
+ *   (inverse CDF in vocabulary order; argmax p_t, lowest index, if the total is zero);
+ *   otherwise correction[s] = -1 (the bonus token needs target logits of one more position).
+ * The random numbers are inputs: uniforms in [0, 1) drawn by the caller.
+ *
+ * All pointers are DEVICE pointers, dense row-major, 16-byte aligned:
+ *   z_target, z_draft [n_seq, n_draft, vocab]  dtype (fp32 or bf16 bit patterns)
+ *   tokens            [n_seq, n_draft] int32 in [0, vocab); a value outside is clamped into the range
+ *   u_accept          [n_seq, n_draft] fp32;  u_resample [n_seq] fp32
+ *   n_accept_out      [n_seq] int32 (required);  correction_out [n_seq] int32 (required)
+ *   alpha_out         [n_seq, n_draft] fp32 (or NULL)
+ * Limits: vocab a multiple of 8 (bf16) or 4 (fp32), 2 <= vocab, n_seq * n_draft <= 65535, else
+ * COVSPEC_UNSUPPORTED.  The workspace (covspec_verify_workspace_size bytes, 256-byte aligned, owned
+ * by the caller, contents undefined between calls) holds per-chunk partial sums.  Work is enqueued on
+ * `stream`; the call does not synchronise and allocates nothing.  Returns a covspec_status.
+ */
+typedef struct covspec_verify_params {
+  int32_t n_seq;    /* S: sequences verified in one call                    */
+  int32_t n_draft;  /* L: drafted positions per sequence                    */
+  int32_t vocab;    /* V: vocabulary width                                  */
+  int32_t dtype;    /* covspec_dtype of the logits                          */
+} covspec_verify_params;
+
+/* Bytes of workspace covspec_verify needs (0 if the parameters are invalid or unsupported). */
+size_t covspec_verify_workspace_size(const covspec_verify_params* p);
+
+int covspec_verify(const covspec_verify_params* p, const void* z_target, const void* z_draft,
+                   const int32_t* tokens, const float* u_accept, const float* u_resample,
+                   int32_t* n_accept_out, int32_t* correction_out, float* alpha_out,
+                   void* workspace, size_t workspace_bytes, covspec_stream_t stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* covspec_status_string(int status);
 

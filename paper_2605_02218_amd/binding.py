@@ -21,7 +21,8 @@ LR_ENERGY_TOPK, LR_GREEDY_RESIDUAL, LR_SCORE_TOPK, LR_RANDOM = 0, 1, 2, 3
 OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
 
 EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
-           "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string")
+           "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string",
+           "covspec_verify_workspace_size", "covspec_verify")
 
 
 class CovspecParams(ctypes.Structure):
@@ -29,6 +30,10 @@ class CovspecParams(ctypes.Structure):
         "batch", "n_tokens", "d_model", "n_query", "n_heads", "n_act_layers", "dtype",
         "rel_mode", "lr_mode", "preselect_m", "rank_r", "keep_k")] + [
         ("keep_ratio", ctypes.c_float), ("lambda_", ctypes.c_float), ("seed", ctypes.c_uint32)]
+
+
+class CovspecVerifyParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_seq", "n_draft", "vocab", "dtype")]
 
 
 class CovspecError(RuntimeError):
@@ -64,6 +69,11 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_reduce_staged.argtypes = [pp] + [vp] * 7 + [vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
     lib.covspec_probe_launches.restype = ctypes.c_int
     lib.covspec_probe_launches.argtypes = [pp] + [ctypes.POINTER(ctypes.c_int32)] * 3
+    vpp = ctypes.POINTER(CovspecVerifyParams)
+    lib.covspec_verify_workspace_size.restype = ctypes.c_size_t
+    lib.covspec_verify_workspace_size.argtypes = [vpp]
+    lib.covspec_verify.restype = ctypes.c_int
+    lib.covspec_verify.argtypes = [vpp] + [vp] * 8 + [vp, ctypes.c_size_t, vp]
     lib.covspec_status_string.restype = ctypes.c_char_p
     lib.covspec_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -238,3 +248,40 @@ def reduce(p: Params, X, hidden, Q, Wq, Wk, workspace=None, idx_out=None, tokens
     if st != OK:
         raise CovspecError(st, "covspec_reduce")
     return idx, tok
+
+
+@dataclass
+class VerifyParams:
+    n_seq: int
+    n_draft: int
+    vocab: int
+    dtype: int = BF16
+
+    def c_struct(self) -> CovspecVerifyParams:
+        return CovspecVerifyParams(self.n_seq, self.n_draft, self.vocab, self.dtype)
+
+
+def verify_workspace_size(p: VerifyParams) -> int:
+    cs = p.c_struct()
+    return int(load_library().covspec_verify_workspace_size(ctypes.byref(cs)))
+
+
+def verify(p: VerifyParams, z_target, z_draft, tokens, u_accept, u_resample, workspace=None, want_alpha=True):
+    """covspec_verify: returns (n_accept [S] int32, correction [S] int32, alpha [S, L] fp32 or None)."""
+    import torch
+    dev = z_target.device
+    if workspace is None:
+        n = verify_workspace_size(p)
+        if n == 0:
+            raise CovspecError(INVALID_ARG, "covspec_verify_workspace_size")
+        workspace = torch.empty(n + 256, dtype=torch.uint8, device=dev)
+    n_acc = torch.empty(p.n_seq, dtype=torch.int32, device=dev)
+    corr = torch.empty(p.n_seq, dtype=torch.int32, device=dev)
+    alpha = torch.empty(p.n_seq, p.n_draft, dtype=torch.float32, device=dev) if want_alpha else None
+    wp, wb = _ws_args(workspace)
+    cs = p.c_struct()
+    st = load_library().covspec_verify(ctypes.byref(cs), _ptr(z_target), _ptr(z_draft), _ptr(tokens), _ptr(u_accept),
+                                       _ptr(u_resample), _ptr(n_acc), _ptr(corr), _ptr(alpha), wp, wb, _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_verify")
+    return n_acc, corr, alpha

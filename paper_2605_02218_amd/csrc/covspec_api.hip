@@ -445,6 +445,35 @@ int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols
   return subspace_product_launches(kSubspaceIters);
 }
 
+static int verify_check(const covspec_verify_params* p) {
+  if (!p) return COVSPEC_INVALID_ARG;
+  if (p->n_seq < 1 || p->n_draft < 1 || p->vocab < 2) return COVSPEC_INVALID_ARG;
+  if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16) return COVSPEC_INVALID_ARG;
+  if ((long)p->n_seq * p->n_draft > 65535) return COVSPEC_UNSUPPORTED;
+  if (p->vocab % (p->dtype == COVSPEC_BF16 ? 8 : 4) != 0) return COVSPEC_UNSUPPORTED;
+  return COVSPEC_OK;
+}
+
+size_t covspec_verify_workspace_size(const covspec_verify_params* p) {
+  if (verify_check(p) != COVSPEC_OK) return 0;
+  return verify_workspace_bytes(p->n_seq, p->n_draft, p->vocab, p->dtype);
+}
+
+int covspec_verify(const covspec_verify_params* p, const void* z_target, const void* z_draft, const int32_t* tokens,
+                   const float* u_accept, const float* u_resample, int32_t* n_accept_out, int32_t* correction_out,
+                   float* alpha_out, void* workspace, size_t workspace_bytes, covspec_stream_t stream) {
+  const int st = verify_check(p);
+  if (st != COVSPEC_OK) return st;
+  if (!z_target || !z_draft || !tokens || !u_accept || !u_resample || !n_accept_out || !correction_out || !workspace)
+    return COVSPEC_INVALID_ARG;
+  if (((uintptr_t)z_target | (uintptr_t)z_draft) & 15) return COVSPEC_INVALID_ARG;
+  if ((uintptr_t)workspace & 255) return COVSPEC_INVALID_ARG;
+  if (workspace_bytes < verify_workspace_bytes(p->n_seq, p->n_draft, p->vocab, p->dtype)) return COVSPEC_WORKSPACE_TOO_SMALL;
+  const hipError_t e = launch_verify(z_target, z_draft, tokens, u_accept, u_resample, p->n_seq, p->n_draft, p->vocab, p->dtype,
+                                     n_accept_out, correction_out, alpha_out, workspace, (hipStream_t)stream);
+  return e == hipSuccess ? COVSPEC_OK : COVSPEC_HIP_ERROR;
+}
+
 const char* covspec_status_string(int status) {
   switch (status) {
     case COVSPEC_OK: return "ok";

@@ -147,4 +147,12 @@ hipError_t launch_greedy(const double* G, int B, int n, int nP, int k, double* L
 hipError_t launch_greedy_finish(const int32_t* order, const int32_t* idx_m, int B, int M, int k, int32_t* idx_out,
                                 int32_t* pick_out, hipStream_t stream);
 
+// ---------------------------------------------------------------- verify.hip
+// Speculative verification over the vocabulary (paper Sec. II-A): zt, zd [S, L, V] target / draft logits,
+// tok [S, L] drafted tokens, u_acc [S, L], u_res [S] uniforms.  n_acc[s] = accepted positions before the first
+// rejection, corr[s] = correction drawn from the residual distribution there (-1 if none), alpha [S, L] optional.
+size_t verify_workspace_bytes(int S, int L, int V, int dtype);
+hipError_t launch_verify(const void* zt, const void* zd, const int32_t* tok, const float* u_acc, const float* u_res, int S, int L,
+                         int V, int dtype, int32_t* n_acc, int32_t* corr, float* alpha, void* ws, hipStream_t stream);
+
 }  // namespace covspec

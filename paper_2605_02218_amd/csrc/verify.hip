@@ -1,0 +1,380 @@
+// Speculative verification over the vocabulary (paper Sec. II-A: softmax of the draft and target logits,
+// acceptance probability of each drafted token, residual distribution after the first rejection).
+//
+// Per sequence s and drafted position tau the two logit rows z_t, z_d [V] are read ONCE by the statistics
+// pass (row maximum and sum of exponentials of both, fp32 exponentials, partial results per chunk so that a
+// few rows still fill the device); the acceptance pass combines them in fp64, evaluates
+// alpha = min(1, p_t(y)/p_d(y)) at the drafted token, finds the first rejection and notes that row's
+// statistics; only that one row per sequence is read again, twice, in fp64: chunk sums of
+// max(p_t - p_d, 0), then the inverse-CDF search of the correction inside the chunk that holds
+// u_res * (total residual mass).  Everything is HBM-bound streaming except the fp64 exponentials of the
+// residual passes (2 per word, one row per sequence).
+#include "common.h"
+#include "kernels.h"
+
+namespace covspec {
+
+namespace {
+
+constexpr int VT = 256;            // threads of the streaming kernels
+
+template <int DT> struct LogitVec;
+template <> struct LogitVec<DT_BF16> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[8]) {
+    const u32x4_t w = *(const u32x4_t*)((const bf16_t*)p + i);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[2 * e] = bf16lo_to_f32(w[e]); v[2 * e + 1] = bf16hi_to_f32(w[e]); }
+  }
+  static __device__ __forceinline__ double at(const void* p, long i) { return (double)bf16_to_f32(((const bf16_t*)p)[i]); }
+};
+template <> struct LogitVec<DT_F32> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[4]) {
+    const f32x4_t w = *(const f32x4_t*)((const float*)p + i);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = w[e];
+  }
+  static __device__ __forceinline__ double at(const void* p, long i) { return (double)((const float*)p)[i]; }
+};
+
+// running (max, sum of exp(x - max)) of one thread, extended by a vector of N values: N + 1 exponentials
+template <int N>
+__device__ __forceinline__ void online_add(float& m, float& s, const float (&v)[N]) {
+  float vm = v[0];
+#pragma unroll
+  for (int e = 1; e < N; ++e) vm = fmaxf(vm, v[e]);
+  const float mx = fmaxf(m, vm);
+  const float mn = mx == -INFINITY ? 0.f : mx;   // only masked (-inf) words so far: any finite reference gives zeros
+  float acc = s * __expf(m - mn);     // m = -inf at the start: exp(-inf) = 0
+#pragma unroll
+  for (int e = 0; e < N; ++e) acc += __expf(v[e] - mn);
+  m = mx;
+  s = acc;
+}
+
+// block-wide combine of (max, sum) pairs; result valid in thread 0
+__device__ __forceinline__ void combine_pair(double& m, double& s, double m2, double s2) {
+  const double mn = fmax(m, m2);
+  s = (m == mn ? s : s * exp(m - mn)) + (m2 == mn ? s2 : s2 * exp(m2 - mn));
+  m = mn;
+}
+
+// stats[(row * chunks + c) * 4 + {0,1,2,3}] = max_t, sum_t, max_d, sum_d over words [c*clen, min(V, (c+1)*clen))
+template <int DT>
+__global__ __launch_bounds__(VT) void verify_stats_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int V, int clen,
+                                                          int chunks, double* __restrict__ stats) {
+  constexpr int N = LogitVec<DT>::N;
+  __shared__ double red[4][VT / 64][2];
+  const long row = blockIdx.y;
+  const int c = blockIdx.x;
+  const int w0 = c * clen, w1 = min(V, w0 + clen);
+  const long base = row * (long)V;
+  float mt = -INFINITY, st = 0.f, md = -INFINITY, sd = 0.f;
+  for (int w = w0 + threadIdx.x * N; w < w1; w += VT * N) {   // V, clen % N == 0: whole vectors only
+    float a[N], b[N];
+    LogitVec<DT>::load(zt, base + w, a);
+    LogitVec<DT>::load(zd, base + w, b);
+    online_add<N>(mt, st, a);
+    online_add<N>(md, sd, b);
+  }
+  // wave, then block combine in fp64
+  double m[2] = {(double)mt, (double)md}, s[2] = {(double)st, (double)sd};
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const double m2 = __shfl_xor(m[q], o, 64), s2 = __shfl_xor(s[q], o, 64);
+      if (s2 > 0.0) {
+        if (s[q] > 0.0) combine_pair(m[q], s[q], m2, s2);
+        else { m[q] = m2; s[q] = s2; }
+      }
+    }
+  }
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  if (lane == 0) { red[0][wv][0] = m[0]; red[0][wv][1] = s[0]; red[1][wv][0] = m[1]; red[1][wv][1] = s[1]; }
+  __syncthreads();
+  if (threadIdx.x < 2) {
+    const int q = threadIdx.x;
+    double mm = red[q][0][0], ss = red[q][0][1];
+    for (int k = 1; k < VT / 64; ++k) {
+      const double m2 = red[q][k][0], s2 = red[q][k][1];
+      if (s2 > 0.0) {
+        if (ss > 0.0) combine_pair(mm, ss, m2, s2);
+        else { mm = m2; ss = s2; }
+      }
+    }
+    double* o = stats + (row * chunks + c) * 4 + 2 * q;
+    o[0] = mm;
+    o[1] = ss;
+  }
+}
+
+// One thread per sequence: row statistics from the chunk partials, alpha at the drafted tokens, first rejection.
+template <int DT>
+__global__ void verify_accept_kernel(const void* __restrict__ zt, const void* __restrict__ zd, const int32_t* __restrict__ tok,
+                                     const float* __restrict__ u_acc, int S, int L, int V, int chunks,
+                                     const double* __restrict__ stats, int32_t* __restrict__ n_acc, float* __restrict__ alpha_out) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= S) return;
+  int first = L;
+  for (int t = 0; t < L; ++t) {
+    const long row = (long)s * L + t;
+    double m[2] = {0.0, 0.0}, sum[2] = {0.0, 0.0};
+    for (int q = 0; q < 2; ++q)
+      for (int c = 0; c < chunks; ++c) {
+        const double m2 = stats[(row * chunks + c) * 4 + 2 * q], s2 = stats[(row * chunks + c) * 4 + 2 * q + 1];
+        if (s2 > 0.0) {
+          if (sum[q] > 0.0) combine_pair(m[q], sum[q], m2, s2);
+          else { m[q] = m2; sum[q] = s2; }
+        }
+      }
+    int y = tok[row];
+    y = y < 0 ? 0 : (y >= V ? V - 1 : y);     // validated on the host where possible; never index outside the row
+    const double pt = exp(LogitVec<DT>::at(zt, row * V + y) - m[0]) / sum[0];
+    const double pd = exp(LogitVec<DT>::at(zd, row * V + y) - m[1]) / sum[1];
+    const double a = pd > 0.0 ? fmin(1.0, pt / pd) : 1.0;
+    const float af = (float)a;
+    if (alpha_out) alpha_out[row] = af;
+    if (first == L && !(u_acc[row] < af)) first = t;
+  }
+  n_acc[s] = first;
+}
+
+// fp64 (max, sum of exponentials) of both logit rows at the rejected position, per chunk: the residual is a
+// difference of the two distributions, and the fp32 sums of the first pass (good to ~1e-6) would move its
+// cumulative sums by more than a flat residual's single words.  st64[(s * chunks + c) * 4 + ..] as above.
+template <int DT>
+__global__ __launch_bounds__(VT) void verify_rowstat64_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
+                                                              int clen, int chunks, const int32_t* __restrict__ n_acc,
+                                                              double* __restrict__ st64) {
+  __shared__ double red[2][VT / 64][2];
+  const int s = blockIdx.y, c = blockIdx.x;
+  const int t = n_acc[s];
+  if (t >= L) return;
+  const long base = ((long)s * L + t) * V;
+  const int w0 = c * clen, w1 = min(V, w0 + clen);
+  double m[2] = {-INFINITY, -INFINITY}, sm[2] = {0.0, 0.0};
+  for (int w = w0 + threadIdx.x; w < w1; w += VT) m[0] = fmax(m[0], LogitVec<DT>::at(zt, base + w)), m[1] = fmax(m[1], LogitVec<DT>::at(zd, base + w));
+#pragma unroll
+  for (int q = 0; q < 2; ++q) m[q] = wave_max(m[q]);
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  if (lane == 0) { red[0][wv][0] = m[0]; red[1][wv][0] = m[1]; }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    m[q] = red[q][0][0];
+    for (int k = 1; k < VT / 64; ++k) m[q] = fmax(m[q], red[q][k][0]);
+    if (m[q] == -INFINITY) m[q] = 0.0;     // a chunk of masked words only: sum 0, skipped by the combine
+  }
+  for (int w = w0 + threadIdx.x; w < w1; w += VT) {
+    sm[0] += exp(LogitVec<DT>::at(zt, base + w) - m[0]);
+    sm[1] += exp(LogitVec<DT>::at(zd, base + w) - m[1]);
+  }
+#pragma unroll
+  for (int q = 0; q < 2; ++q) sm[q] = wave_sum(sm[q]);
+  if (lane == 0) { red[0][wv][1] = sm[0]; red[1][wv][1] = sm[1]; }
+  __syncthreads();
+  if (threadIdx.x < 2) {
+    const int q = threadIdx.x;
+    double tot = 0.0;
+    for (int k = 0; k < VT / 64; ++k) tot += red[q][k][1];
+    double* o = st64 + ((long)s * chunks + c) * 4 + 2 * q;
+    o[0] = m[q];
+    o[1] = tot;
+  }
+}
+
+// thread 0 of a workgroup: the row's (max_t, 1/sum_t, max_d, 1/sum_d) from the chunk partials, into LDS
+__device__ __forceinline__ void combine_rowstat(const double* __restrict__ st64, int s, int chunks, double* sh4) {
+  double m[2] = {0.0, 0.0}, sum[2] = {0.0, 0.0};
+  for (int q = 0; q < 2; ++q)
+    for (int c = 0; c < chunks; ++c) {
+      const double m2 = st64[((long)s * chunks + c) * 4 + 2 * q], s2 = st64[((long)s * chunks + c) * 4 + 2 * q + 1];
+      if (s2 > 0.0) {
+        if (sum[q] > 0.0) combine_pair(m[q], sum[q], m2, s2);
+        else { m[q] = m2; sum[q] = s2; }
+      }
+    }
+  sh4[0] = m[0]; sh4[1] = 1.0 / sum[0]; sh4[2] = m[1]; sh4[3] = 1.0 / sum[1];
+}
+
+template <int DT>
+__device__ __forceinline__ double residual_at(const void* zt, const void* zd, long i, double mt, double ist, double md, double isd) {
+  // each product rounded on its own: contracted into a fused multiply-add the difference of two EQUAL
+  // probabilities would come out as rounding noise instead of zero
+#pragma clang fp contract(off)
+  const double a = exp(LogitVec<DT>::at(zt, i) - mt) * ist;
+  const double b = exp(LogitVec<DT>::at(zd, i) - md) * isd;
+  const double d = a - b;
+  return d > 0.0 ? d : 0.0;
+}
+
+// part[s * chunks + c] = sum over the chunk of max(p_t - p_d, 0) at the rejected row (0 when nothing was rejected)
+template <int DT>
+__global__ __launch_bounds__(VT) void verify_residual_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
+                                                             int clen, int chunks, const int32_t* __restrict__ n_acc,
+                                                             const double* __restrict__ rowstat, double* __restrict__ part) {
+  __shared__ double red[VT / 64];
+  __shared__ double sh4[4];
+  const int s = blockIdx.y, c = blockIdx.x;
+  const int t = n_acc[s];
+  if (t >= L) { if (threadIdx.x == 0) part[(long)s * chunks + c] = 0.0; return; }
+  const long base = ((long)s * L + t) * V;
+  if (threadIdx.x == 0) combine_rowstat(rowstat, s, chunks, sh4);
+  __syncthreads();
+  const double mt = sh4[0], ist = sh4[1], md = sh4[2], isd = sh4[3];
+  const int w0 = c * clen, w1 = min(V, w0 + clen);
+  double acc = 0.0;
+  for (int w = w0 + threadIdx.x; w < w1; w += VT) acc += residual_at<DT>(zt, zd, base + w, mt, ist, md, isd);
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int k = 0; k < VT / 64; ++k) tot += red[k];
+    part[(long)s * chunks + c] = tot;
+  }
+}
+
+// One 1024-thread workgroup per sequence: inverse CDF of the residual in vocabulary order.
+template <int DT>
+__global__ __launch_bounds__(1024) void verify_sample_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
+                                                             int clen, int chunks, const int32_t* __restrict__ n_acc,
+                                                             const double* __restrict__ rowstat, const double* __restrict__ part,
+                                                             const float* __restrict__ u_res, int32_t* __restrict__ corr) {
+  __shared__ double wsum[16];
+  __shared__ double sh_prefix, sh_target;
+  __shared__ int sh_chunk, sh_found, sh_last;
+  __shared__ unsigned long long sh_best;
+  const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int t = n_acc[s];
+  if (t >= L) { if (tid == 0) corr[s] = -1; return; }
+  const long base = ((long)s * L + t) * V;
+  __shared__ double sh4[4];
+  if (tid == 0) combine_rowstat(rowstat, s, chunks, sh4);
+  __syncthreads();
+  const double mt = sh4[0], ist = sh4[1], md = sh4[2], isd = sh4[3];
+  if (tid == 0) {
+    double R = 0.0;
+    for (int c = 0; c < chunks; ++c) R += part[(long)s * chunks + c];
+    const double target = (double)u_res[s] * R;
+    int cs = -1;
+    double pre = 0.0;
+    if (R > 0.0) {
+      for (int c = 0; c < chunks; ++c) {
+        const double p = part[(long)s * chunks + c];
+        if (pre + p > target) { cs = c; break; }
+        pre += p;
+      }
+      if (cs < 0) {   // target within rounding of the total: the last chunk with mass
+        pre = 0.0;
+        for (int c = 0; c < chunks; ++c) { if (part[(long)s * chunks + c] > 0.0) cs = c; }
+        for (int c = 0; c < cs; ++c) pre += part[(long)s * chunks + c];
+      }
+    }
+    sh_chunk = cs; sh_prefix = pre; sh_target = target; sh_found = 0x7fffffff; sh_last = -1; sh_best = 0ull;
+  }
+  __syncthreads();
+  const int cs = sh_chunk;
+  if (cs < 0) {
+    // no residual mass (p_t == p_d): argmax p_t, lowest index on ties
+    unsigned long long best = 0ull;
+    for (int w = tid; w < V; w += 1024) {
+      const float z = (float)LogitVec<DT>::at(zt, base + w);   // logits are stored in at most fp32: exact
+      const unsigned long long key = ((unsigned long long)float_order_key(z) << 32) | (0xFFFFFFFFu - (uint32_t)w);
+      best = key > best ? key : best;
+    }
+    best = wave_max(best);
+    if (lane == 0) atomicMax(&sh_best, best);
+    __syncthreads();
+    if (tid == 0) corr[s] = (int)(0xFFFFFFFFu - (uint32_t)(sh_best & 0xFFFFFFFFull));
+    return;
+  }
+  // inside the chunk: thread `tid` owns the contiguous words [w0 + tid*per, w0 + (tid+1)*per)
+  const int w0 = cs * clen, w1 = min(V, w0 + clen);
+  const int per = (w1 - w0 + 1023) / 1024;
+  const int a0 = w0 + tid * per, a1 = min(w1, a0 + per);
+  double mine = 0.0;
+  for (int w = a0; w < a1; ++w) mine += residual_at<DT>(zt, zd, base + w, mt, ist, md, isd);
+  // exclusive prefix over the threads (fp64): wave scan, then the 16 wave totals
+  double inc = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double v = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += v;
+  }
+  if (lane == 63) wsum[wv] = inc;
+  __syncthreads();
+  double before = sh_prefix;
+  for (int k = 0; k < wv; ++k) before += wsum[k];
+  before += inc - mine;
+  // second pass over the own words: the first word at which the running sum passes the target, and the last
+  // word with any mass.  A thread that starts beyond the target reports its first word; the minimum over all
+  // threads is the crossing.  If rounding leaves the target just past the chunk, the last word with mass is it.
+  const double target = sh_target;
+  double run = before;
+  int hit = 0x7fffffff, last = -1;
+  for (int w = a0; w < a1; ++w) {
+    const double r = residual_at<DT>(zt, zd, base + w, mt, ist, md, isd);
+    if (r > 0.0) last = w;
+    run += r;
+    if (hit == 0x7fffffff && run > target && r > 0.0) hit = w;
+  }
+  if (hit != 0x7fffffff) atomicMin(&sh_found, hit);
+  if (last >= 0) atomicMax(&sh_last, last);
+  __syncthreads();
+  if (tid == 0) corr[s] = sh_found != 0x7fffffff ? sh_found : (sh_last >= 0 ? sh_last : w1 - 1);
+}
+
+}  // namespace
+
+void verify_plan(int S, int L, int V, int dtype, int* clen, int* chunks) {
+  // chunks per row so that even a few rows give the streaming kernels ~1024 workgroups; chunk length a
+  // multiple of what one pass of the workgroup covers
+  const int vec = dtype == DT_BF16 ? 8 : 4;
+  const int step = VT * vec;
+  long rows = (long)S * L;
+  int want = (int)((1024 + rows - 1) / rows);
+  if (want < 1) want = 1;
+  if (want > 64) want = 64;
+  int len = (V + want - 1) / want;
+  len = (len + step - 1) / step * step;
+  *clen = len;
+  *chunks = (V + len - 1) / len;
+}
+
+size_t verify_workspace_bytes(int S, int L, int V, int dtype) {
+  int clen, chunks;
+  verify_plan(S, L, V, dtype, &clen, &chunks);
+  return ((size_t)S * L * chunks * 4 + (size_t)S * chunks * 4 + (size_t)S * chunks) * sizeof(double) + 512;
+}
+
+template <int DT>
+static hipError_t launch_verify_t(const void* zt, const void* zd, const int32_t* tok, const float* u_acc, const float* u_res, int S,
+                                  int L, int V, int32_t* n_acc, int32_t* corr, float* alpha, void* ws, hipStream_t st) {
+  int clen, chunks;
+  verify_plan(S, L, V, DT, &clen, &chunks);
+  double* stats = (double*)ws;
+  double* rowstat = stats + (size_t)S * L * chunks * 4;     // [S][chunks][4], fp64 statistics of the rejected rows
+  double* part = rowstat + (size_t)S * chunks * 4;
+  hipLaunchKernelGGL((verify_stats_kernel<DT>), dim3(chunks, S * L), dim3(VT), 0, st, zt, zd, V, clen, chunks, stats);
+  hipLaunchKernelGGL((verify_accept_kernel<DT>), dim3((S + 63) / 64), dim3(64), 0, st, zt, zd, tok, u_acc, S, L, V, chunks,
+                     (const double*)stats, n_acc, alpha);
+  hipLaunchKernelGGL((verify_rowstat64_kernel<DT>), dim3(chunks, S), dim3(VT), 0, st, zt, zd, L, V, clen, chunks, (const int32_t*)n_acc,
+                     rowstat);
+  hipLaunchKernelGGL((verify_residual_kernel<DT>), dim3(chunks, S), dim3(VT), 0, st, zt, zd, L, V, clen, chunks, (const int32_t*)n_acc,
+                     (const double*)rowstat, part);
+  hipLaunchKernelGGL((verify_sample_kernel<DT>), dim3(S), dim3(1024), 0, st, zt, zd, L, V, clen, chunks, (const int32_t*)n_acc,
+                     (const double*)rowstat, (const double*)part, u_res, corr);
+  return hipGetLastError();
+}
+
+hipError_t launch_verify(const void* zt, const void* zd, const int32_t* tok, const float* u_acc, const float* u_res, int S, int L,
+                         int V, int dtype, int32_t* n_acc, int32_t* corr, float* alpha, void* ws, hipStream_t st) {
+  if (S < 1 || L < 1 || V < 2 || (long)S * L > 65535 || S > 65535) return hipErrorInvalidValue;
+  return dtype == DT_BF16 ? launch_verify_t<DT_BF16>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st)
+                          : launch_verify_t<DT_F32>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st);
+}
+
+}  // namespace covspec
