@@ -168,6 +168,61 @@ def cpu_baseline(w, batch, rel, lr, budget_s=20.0):
                       % (done, w.batch, dt)}
 
 
+def verify_bench(a):
+    """--verify: the speculative verification step (paper Sec. II-A) over a full vocabulary, its own JSON line.
+
+    A step is one covspec_verify call: 64 sequences x 8 drafted positions x 151,936 words, bf16 logits resident in
+    HBM.  Algorithmic bytes per call = both logit tensors read once (2 S L V e) plus the small per-position
+    inputs and outputs; `achieved` is that figure over the WHOLE call's time (five kernels), so it understates
+    the streaming kernel's own rate.
+    """
+    import numpy as np
+    import torch
+    import covspec_inputs as I
+    import paper_2605_02218_amd as C
+    C.load_library()
+    torch.cuda.set_device(0)
+    S, L, V, dtype = 64, 8, I.VERIFY_VOCAB, I.BF16
+    d = I.make_verify_batch(S, L, V, dtype, seed=2024, copy_rows=2)
+    zt = torch.from_numpy(d["zt"].view(np.int16)).cuda().view(torch.bfloat16)
+    zd = torch.from_numpy(d["zd"].view(np.int16)).cuda().view(torch.bfloat16)
+    tok, ua, ur = (torch.from_numpy(d[k]).cuda() for k in ("tok", "u_acc", "u_res"))
+    p = C.VerifyParams(S, L, V, dtype)
+    ws = torch.empty(C.verify_workspace_size(p) + 256, dtype=torch.uint8, device="cuda")
+    for _ in range(a.warmup):
+        C.verify(p, zt, zd, tok, ua, ur, workspace=ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(a.steps):
+        C.verify(p, zt, zd, tok, ua, ur, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    ms = e0.elapsed_time(e1) / a.steps
+    alg = 2.0 * S * L * V * 2 + S * L * 12 + S * 12
+    line = {"metric": "drafted positions verified/sec (softmax, acceptance, residual draw over the vocabulary)",
+            "value": round(S * L / max(ms, wall_ms) * 1e3, 1), "unit": "positions/s", "n_gpus": 1, "steps": a.steps,
+            "warmup": a.warmup, "ms_per_step": round(max(ms, wall_ms), 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "verify S=%d L=%d V=%d" % (S, L, V), "entry_point": "covspec_verify"},
+            "roofline": {"bound": "hbm", "achieved": round(alg / (ms * 1e-3) / 1e9, 1), "peak": PEAK["hbm_GBps"], "unit": "GB/s",
+                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": None,
+                         "kernel": "whole call (verify_stats_kernel streams the logits)", "device_ms": round(ms, 4)}}
+    if not a.no_cpu_baseline:
+        from oracle import verify_oracle as VO
+        t0 = time.perf_counter()
+        n = 0
+        while n < S and time.perf_counter() - t0 < 10.0:
+            VO.verify(I.as_f64(d["zt"][n], dtype), I.as_f64(d["zd"][n], dtype), d["tok"][n], d["u_acc"][n], d["u_res"][n])
+            n += 1
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": round(n * L / dt, 2), "unit": "positions/s", "cores": 1, "kind": "oracle",
+                                "sample": "%d of the %d sequences of the same batch" % (n, S)}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -177,6 +232,7 @@ def main():
     ap.add_argument("--pipeline", choices=["paper", "variant"], default="paper")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other workloads and pipeline (extra keys)")
+    ap.add_argument("--verify", action="store_true", help="time the speculative verification step instead (own JSON line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 1 GiB device copies and exit (reference reading for the HBM byte counters)")
     a = ap.parse_args()
@@ -194,6 +250,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 3}), flush=True)
+        return
+    if a.verify:
+        verify_bench(a)
         return
     import covspec_inputs as I
     import paper_2605_02218_amd as C

@@ -38,29 +38,37 @@ template <> struct LogitVec<DT_F32> {
   static __device__ __forceinline__ double at(const void* p, long i) { return (double)((const float*)p)[i]; }
 };
 
-// running (max, sum of exp(x - max)) of one thread, extended by a vector of N values: N + 1 exponentials
+// The streaming pass works in the base-2 domain: y = x * kLog2e (kLog2e the fp32 constant below, also used as
+// the exact same number in the fp64 steps), terms 2^(y - c) against a reference c that is the largest y seen so
+// far rounded to fp32.  One fused multiply-add forms y - c with a single rounding, so a term costs fma + exp2 +
+// add.  The reference need not be the exact maximum: (c, sum) pairs combine exactly whatever c is.  kLog2e
+// differs from log2(e) by 1.3e-8 relative, i.e. a temperature of 1 + 1.3e-8: below 1e-6 in any probability
+// ratio for logits within +-50 of each other.
+constexpr float kLog2e = 1.44269502f;
+
+// running (reference, sum of 2^(y - reference)) of one thread, extended by a vector of N values
 template <int N>
-__device__ __forceinline__ void online_add(float& m, float& s, const float (&v)[N]) {
+__device__ __forceinline__ void online_add(float& c, float& s, const float (&v)[N]) {
   float vm = v[0];
 #pragma unroll
   for (int e = 1; e < N; ++e) vm = fmaxf(vm, v[e]);
-  const float mx = fmaxf(m, vm);
-  const float mn = mx == -INFINITY ? 0.f : mx;   // only masked (-inf) words so far: any finite reference gives zeros
-  float acc = s * __expf(m - mn);     // m = -inf at the start: exp(-inf) = 0
+  const float cx = fmaxf(c, vm * kLog2e);
+  const float cn = cx == -INFINITY ? 0.f : cx;   // only masked (-inf) words so far: any finite reference gives zeros
+  float acc = s * __builtin_amdgcn_exp2f(c - cn);   // c = -inf at the start: 2^-inf = 0
 #pragma unroll
-  for (int e = 0; e < N; ++e) acc += __expf(v[e] - mn);
-  m = mx;
+  for (int e = 0; e < N; ++e) acc += __builtin_amdgcn_exp2f(__builtin_fmaf(v[e], kLog2e, -cn));
+  c = cx;
   s = acc;
 }
 
-// block-wide combine of (max, sum) pairs; result valid in thread 0
+// combine of two (reference, sum) pairs of the base-2 domain
 __device__ __forceinline__ void combine_pair(double& m, double& s, double m2, double s2) {
   const double mn = fmax(m, m2);
-  s = (m == mn ? s : s * exp(m - mn)) + (m2 == mn ? s2 : s2 * exp(m2 - mn));
+  s = (m == mn ? s : s * exp2(m - mn)) + (m2 == mn ? s2 : s2 * exp2(m2 - mn));
   m = mn;
 }
 
-// stats[(row * chunks + c) * 4 + {0,1,2,3}] = max_t, sum_t, max_d, sum_d over words [c*clen, min(V, (c+1)*clen))
+// stats[(row * chunks + c) * 4 + {0,1,2,3}] = ref_t, sum_t, ref_d, sum_d (base-2 domain) over words [c*clen, min(V, (c+1)*clen))
 template <int DT>
 __global__ __launch_bounds__(VT) void verify_stats_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int V, int clen,
                                                           int chunks, double* __restrict__ stats) {
@@ -71,7 +79,9 @@ __global__ __launch_bounds__(VT) void verify_stats_kernel(const void* __restrict
   const int w0 = c * clen, w1 = min(V, w0 + clen);
   const long base = row * (long)V;
   float mt = -INFINITY, st = 0.f, md = -INFINITY, sd = 0.f;
-  for (int w = w0 + threadIdx.x * N; w < w1; w += VT * N) {   // V, clen % N == 0: whole vectors only
+  // V, clen % N == 0: whole vectors only.  (Two vectors per trip with all loads issued first, and twice the
+  // workgroups, both measured slower: the pass runs at the rate the memory system gives one resident round.)
+  for (int w = w0 + threadIdx.x * N; w < w1; w += VT * N) {
     float a[N], b[N];
     LogitVec<DT>::load(zt, base + w, a);
     LogitVec<DT>::load(zd, base + w, b);
@@ -110,93 +120,94 @@ __global__ __launch_bounds__(VT) void verify_stats_kernel(const void* __restrict
   }
 }
 
-// One thread per sequence: row statistics from the chunk partials, alpha at the drafted tokens, first rejection.
+// One wave per sequence, one lane per drafted position: row statistics from the chunk partials, alpha at the
+// drafted token, first rejection.  rowmax[s * 2 + {0,1}] = the rejected row's references brought back to the
+// natural domain, i.e. its maximum logits to within rounding: the shift the fp64 passes below use (any value
+// near the maximum serves, as long as every pass uses the same); untouched when nothing is rejected.
 template <int DT>
-__global__ void verify_accept_kernel(const void* __restrict__ zt, const void* __restrict__ zd, const int32_t* __restrict__ tok,
-                                     const float* __restrict__ u_acc, int S, int L, int V, int chunks,
-                                     const double* __restrict__ stats, int32_t* __restrict__ n_acc, float* __restrict__ alpha_out) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= S) return;
+__global__ __launch_bounds__(64) void verify_accept_kernel(const void* __restrict__ zt, const void* __restrict__ zd,
+                                                           const int32_t* __restrict__ tok, const float* __restrict__ u_acc, int L,
+                                                           int V, int chunks, const double* __restrict__ stats,
+                                                           int32_t* __restrict__ n_acc, float* __restrict__ alpha_out,
+                                                           double* __restrict__ rowmax) {
+  const int s = blockIdx.x, lane = threadIdx.x;
   int first = L;
-  for (int t = 0; t < L; ++t) {
-    const long row = (long)s * L + t;
+  for (int t0 = 0; t0 < L; t0 += 64) {
+    const int t = t0 + lane;
+    bool rejected = false;
     double m[2] = {0.0, 0.0}, sum[2] = {0.0, 0.0};
-    for (int q = 0; q < 2; ++q)
-      for (int c = 0; c < chunks; ++c) {
-        const double m2 = stats[(row * chunks + c) * 4 + 2 * q], s2 = stats[(row * chunks + c) * 4 + 2 * q + 1];
-        if (s2 > 0.0) {
-          if (sum[q] > 0.0) combine_pair(m[q], sum[q], m2, s2);
-          else { m[q] = m2; sum[q] = s2; }
+    if (t < L) {
+      const long row = (long)s * L + t;
+      for (int q = 0; q < 2; ++q)
+        for (int c = 0; c < chunks; ++c) {
+          const double m2 = stats[(row * chunks + c) * 4 + 2 * q], s2 = stats[(row * chunks + c) * 4 + 2 * q + 1];
+          if (s2 > 0.0) {
+            if (sum[q] > 0.0) combine_pair(m[q], sum[q], m2, s2);
+            else { m[q] = m2; sum[q] = s2; }
+          }
         }
-      }
-    int y = tok[row];
-    y = y < 0 ? 0 : (y >= V ? V - 1 : y);     // validated on the host where possible; never index outside the row
-    const double pt = exp(LogitVec<DT>::at(zt, row * V + y) - m[0]) / sum[0];
-    const double pd = exp(LogitVec<DT>::at(zd, row * V + y) - m[1]) / sum[1];
-    const double a = pd > 0.0 ? fmin(1.0, pt / pd) : 1.0;
-    const float af = (float)a;
-    if (alpha_out) alpha_out[row] = af;
-    if (first == L && !(u_acc[row] < af)) first = t;
+      int y = tok[row];
+      y = y < 0 ? 0 : (y >= V ? V - 1 : y);     // never index outside the row
+      const double pt = exp2(LogitVec<DT>::at(zt, row * V + y) * (double)kLog2e - m[0]) / sum[0];
+      const double pd = exp2(LogitVec<DT>::at(zd, row * V + y) * (double)kLog2e - m[1]) / sum[1];
+      const double a = pd > 0.0 ? fmin(1.0, pt / pd) : 1.0;
+      const float af = (float)a;
+      if (alpha_out) alpha_out[row] = af;
+      rejected = !(u_acc[row] < af);
+    }
+    const unsigned long long mask = __ballot(rejected);
+    if (mask != 0ull) {
+      const int fl = __ffsll((long long)mask) - 1;
+      first = t0 + fl;
+      if (lane == fl) { rowmax[s * 2] = m[0] / (double)kLog2e; rowmax[s * 2 + 1] = m[1] / (double)kLog2e; }
+      break;      // uniform: the ballot is the same in every lane
+    }
   }
-  n_acc[s] = first;
+  if (lane == 0) n_acc[s] = first;
 }
 
-// fp64 (max, sum of exponentials) of both logit rows at the rejected position, per chunk: the residual is a
-// difference of the two distributions, and the fp32 sums of the first pass (good to ~1e-6) would move its
-// cumulative sums by more than a flat residual's single words.  st64[(s * chunks + c) * 4 + ..] as above.
+// fp64 sums of exponentials of both logit rows at the rejected position, per chunk: the residual is a
+// difference of the two distributions, and the fp32 sums of the first pass (good to ~1e-7) would move its
+// cumulative sums by more than a flat residual's single words.  rowsum[(s * rchunks + c) * 2 + {0,1}].
 template <int DT>
-__global__ __launch_bounds__(VT) void verify_rowstat64_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
-                                                              int clen, int chunks, const int32_t* __restrict__ n_acc,
-                                                              double* __restrict__ st64) {
-  __shared__ double red[2][VT / 64][2];
+__global__ __launch_bounds__(VT) void verify_rowsum64_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
+                                                             int rlen, int rchunks, const int32_t* __restrict__ n_acc,
+                                                             const double* __restrict__ rowmax, double* __restrict__ rowsum) {
+  __shared__ double red[2][VT / 64];
   const int s = blockIdx.y, c = blockIdx.x;
   const int t = n_acc[s];
   if (t >= L) return;
   const long base = ((long)s * L + t) * V;
-  const int w0 = c * clen, w1 = min(V, w0 + clen);
-  double m[2] = {-INFINITY, -INFINITY}, sm[2] = {0.0, 0.0};
-  for (int w = w0 + threadIdx.x; w < w1; w += VT) m[0] = fmax(m[0], LogitVec<DT>::at(zt, base + w)), m[1] = fmax(m[1], LogitVec<DT>::at(zd, base + w));
-#pragma unroll
-  for (int q = 0; q < 2; ++q) m[q] = wave_max(m[q]);
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  if (lane == 0) { red[0][wv][0] = m[0]; red[1][wv][0] = m[1]; }
-  __syncthreads();
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    m[q] = red[q][0][0];
-    for (int k = 1; k < VT / 64; ++k) m[q] = fmax(m[q], red[q][k][0]);
-    if (m[q] == -INFINITY) m[q] = 0.0;     // a chunk of masked words only: sum 0, skipped by the combine
-  }
+  const int w0 = c * rlen, w1 = min(V, w0 + rlen);
+  const double mt = rowmax[s * 2], md = rowmax[s * 2 + 1];
+  double sm[2] = {0.0, 0.0};
   for (int w = w0 + threadIdx.x; w < w1; w += VT) {
-    sm[0] += exp(LogitVec<DT>::at(zt, base + w) - m[0]);
-    sm[1] += exp(LogitVec<DT>::at(zd, base + w) - m[1]);
+    sm[0] += exp(LogitVec<DT>::at(zt, base + w) - mt);
+    sm[1] += exp(LogitVec<DT>::at(zd, base + w) - md);
   }
 #pragma unroll
   for (int q = 0; q < 2; ++q) sm[q] = wave_sum(sm[q]);
-  if (lane == 0) { red[0][wv][1] = sm[0]; red[1][wv][1] = sm[1]; }
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  if (lane == 0) { red[0][wv] = sm[0]; red[1][wv] = sm[1]; }
   __syncthreads();
   if (threadIdx.x < 2) {
     const int q = threadIdx.x;
     double tot = 0.0;
-    for (int k = 0; k < VT / 64; ++k) tot += red[q][k][1];
-    double* o = st64 + ((long)s * chunks + c) * 4 + 2 * q;
-    o[0] = m[q];
-    o[1] = tot;
+    for (int k = 0; k < VT / 64; ++k) tot += red[q][k];
+    rowsum[((long)s * rchunks + c) * 2 + q] = tot;
   }
 }
 
-// thread 0 of a workgroup: the row's (max_t, 1/sum_t, max_d, 1/sum_d) from the chunk partials, into LDS
-__device__ __forceinline__ void combine_rowstat(const double* __restrict__ st64, int s, int chunks, double* sh4) {
-  double m[2] = {0.0, 0.0}, sum[2] = {0.0, 0.0};
-  for (int q = 0; q < 2; ++q)
-    for (int c = 0; c < chunks; ++c) {
-      const double m2 = st64[((long)s * chunks + c) * 4 + 2 * q], s2 = st64[((long)s * chunks + c) * 4 + 2 * q + 1];
-      if (s2 > 0.0) {
-        if (sum[q] > 0.0) combine_pair(m[q], sum[q], m2, s2);
-        else { m[q] = m2; sum[q] = s2; }
-      }
-    }
-  sh4[0] = m[0]; sh4[1] = 1.0 / sum[0]; sh4[2] = m[1]; sh4[3] = 1.0 / sum[1];
+// wave 0 of a workgroup (all 64 lanes): the row's (max_t, 1/sum_t, max_d, 1/sum_d) from the chunk sums, into
+// LDS.  rchunks <= 64: lane c holds chunk c, butterfly sums (the same order wherever this is called).
+__device__ __forceinline__ void combine_rowstat(const double* __restrict__ rowmax, const double* __restrict__ rowsum, int s, int rchunks,
+                                                double* sh4) {
+  const int lane = threadIdx.x & 63;
+  double st = lane < rchunks ? rowsum[((long)s * rchunks + lane) * 2] : 0.0;
+  double sd = lane < rchunks ? rowsum[((long)s * rchunks + lane) * 2 + 1] : 0.0;
+  st = wave_sum(st);
+  sd = wave_sum(sd);
+  if (lane == 0) { sh4[0] = rowmax[s * 2]; sh4[1] = 1.0 / st; sh4[2] = rowmax[s * 2 + 1]; sh4[3] = 1.0 / sd; }
 }
 
 template <int DT>
@@ -214,14 +225,15 @@ __device__ __forceinline__ double residual_at(const void* zt, const void* zd, lo
 template <int DT>
 __global__ __launch_bounds__(VT) void verify_residual_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
                                                              int clen, int chunks, const int32_t* __restrict__ n_acc,
-                                                             const double* __restrict__ rowstat, double* __restrict__ part) {
+                                                             const double* __restrict__ rowmax, const double* __restrict__ rowsum,
+                                                             double* __restrict__ part) {
   __shared__ double red[VT / 64];
   __shared__ double sh4[4];
   const int s = blockIdx.y, c = blockIdx.x;
   const int t = n_acc[s];
   if (t >= L) { if (threadIdx.x == 0) part[(long)s * chunks + c] = 0.0; return; }
   const long base = ((long)s * L + t) * V;
-  if (threadIdx.x == 0) combine_rowstat(rowstat, s, chunks, sh4);
+  if (threadIdx.x < 64) combine_rowstat(rowmax, rowsum, s, chunks, sh4);
   __syncthreads();
   const double mt = sh4[0], ist = sh4[1], md = sh4[2], isd = sh4[3];
   const int w0 = c * clen, w1 = min(V, w0 + clen);
@@ -241,7 +253,8 @@ __global__ __launch_bounds__(VT) void verify_residual_kernel(const void* __restr
 template <int DT>
 __global__ __launch_bounds__(1024) void verify_sample_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
                                                              int clen, int chunks, const int32_t* __restrict__ n_acc,
-                                                             const double* __restrict__ rowstat, const double* __restrict__ part,
+                                                             const double* __restrict__ rowmax, const double* __restrict__ rowsum,
+                                                             const double* __restrict__ part,
                                                              const float* __restrict__ u_res, int32_t* __restrict__ corr) {
   __shared__ double wsum[16];
   __shared__ double sh_prefix, sh_target;
@@ -252,28 +265,29 @@ __global__ __launch_bounds__(1024) void verify_sample_kernel(const void* __restr
   if (t >= L) { if (tid == 0) corr[s] = -1; return; }
   const long base = ((long)s * L + t) * V;
   __shared__ double sh4[4];
-  if (tid == 0) combine_rowstat(rowstat, s, chunks, sh4);
+  if (tid < 64) combine_rowstat(rowmax, rowsum, s, chunks, sh4);
   __syncthreads();
   const double mt = sh4[0], ist = sh4[1], md = sh4[2], isd = sh4[3];
-  if (tid == 0) {
-    double R = 0.0;
-    for (int c = 0; c < chunks; ++c) R += part[(long)s * chunks + c];
-    const double target = (double)u_res[s] * R;
-    int cs = -1;
-    double pre = 0.0;
-    if (R > 0.0) {
-      for (int c = 0; c < chunks; ++c) {
-        const double p = part[(long)s * chunks + c];
-        if (pre + p > target) { cs = c; break; }
-        pre += p;
-      }
-      if (cs < 0) {   // target within rounding of the total: the last chunk with mass
-        pre = 0.0;
-        for (int c = 0; c < chunks; ++c) { if (part[(long)s * chunks + c] > 0.0) cs = c; }
-        for (int c = 0; c < cs; ++c) pre += part[(long)s * chunks + c];
-      }
+  if (tid < 64) {
+    // lane c holds chunk c's residual mass; inclusive scan in lane order, total in lane 63
+    const double pc = lane < chunks ? part[(long)s * chunks + lane] : 0.0;
+    double inc = pc;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double v = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += v;
     }
-    sh_chunk = cs; sh_prefix = pre; sh_target = target; sh_found = 0x7fffffff; sh_last = -1; sh_best = 0ull;
+    const double R = __shfl(inc, 63, 64);
+    const double target = (double)u_res[s] * R;
+    // the first chunk whose cumulative mass passes the target; if rounding leaves the target at the total,
+    // the last chunk with any mass
+    const unsigned long long over = __ballot(pc > 0.0 && inc > target);
+    const unsigned long long mass = __ballot(pc > 0.0);
+    int cs = -1;
+    if (R > 0.0) cs = over ? __ffsll((long long)over) - 1 : 63 - __clzll((long long)mass);
+    if (lane == (cs < 0 ? 0 : cs)) {
+      sh_chunk = cs; sh_prefix = inc - pc; sh_target = target; sh_found = 0x7fffffff; sh_last = -1; sh_best = 0ull;
+    }
   }
   __syncthreads();
   const int cs = sh_chunk;
@@ -330,7 +344,7 @@ __global__ __launch_bounds__(1024) void verify_sample_kernel(const void* __restr
 }  // namespace
 
 void verify_plan(int S, int L, int V, int dtype, int* clen, int* chunks) {
-  // chunks per row so that even a few rows give the streaming kernels ~1024 workgroups; chunk length a
+  // chunks per row so that even a few rows give the streaming kernel ~1024 workgroups; chunk length a
   // multiple of what one pass of the workgroup covers
   const int vec = dtype == DT_BF16 ? 8 : 4;
   const int step = VT * vec;
@@ -344,35 +358,49 @@ void verify_plan(int S, int L, int V, int dtype, int* clen, int* chunks) {
   *chunks = (V + len - 1) / len;
 }
 
+// the fp64 passes read one row per sequence: their own, finer split (~2048 workgroups, at most 64 chunks a row)
+static void residual_plan(int S, int V, int* rlen, int* rchunks) {
+  int want = (2048 + S - 1) / S;
+  if (want < 1) want = 1;
+  if (want > 64) want = 64;
+  int len = (V + want - 1) / want;
+  len = (len + VT - 1) / VT * VT;
+  *rlen = len;
+  *rchunks = (V + len - 1) / len;
+}
+
 size_t verify_workspace_bytes(int S, int L, int V, int dtype) {
-  int clen, chunks;
+  int clen, chunks, rlen, rchunks;
   verify_plan(S, L, V, dtype, &clen, &chunks);
-  return ((size_t)S * L * chunks * 4 + (size_t)S * chunks * 4 + (size_t)S * chunks) * sizeof(double) + 512;
+  residual_plan(S, V, &rlen, &rchunks);
+  return ((size_t)S * L * chunks * 4 + (size_t)S * 2 + (size_t)S * rchunks * 3) * sizeof(double) + 512;
 }
 
 template <int DT>
 static hipError_t launch_verify_t(const void* zt, const void* zd, const int32_t* tok, const float* u_acc, const float* u_res, int S,
                                   int L, int V, int32_t* n_acc, int32_t* corr, float* alpha, void* ws, hipStream_t st) {
-  int clen, chunks;
+  int clen, chunks, rlen, rchunks;
   verify_plan(S, L, V, DT, &clen, &chunks);
-  double* stats = (double*)ws;
-  double* rowstat = stats + (size_t)S * L * chunks * 4;     // [S][chunks][4], fp64 statistics of the rejected rows
-  double* part = rowstat + (size_t)S * chunks * 4;
+  residual_plan(S, V, &rlen, &rchunks);
+  double* stats = (double*)ws;                               // [S*L][chunks][4]
+  double* rowmax = stats + (size_t)S * L * chunks * 4;       // [S][2]
+  double* rowsum = rowmax + (size_t)S * 2;                   // [S][rchunks][2]
+  double* part = rowsum + (size_t)S * rchunks * 2;           // [S][rchunks]
   hipLaunchKernelGGL((verify_stats_kernel<DT>), dim3(chunks, S * L), dim3(VT), 0, st, zt, zd, V, clen, chunks, stats);
-  hipLaunchKernelGGL((verify_accept_kernel<DT>), dim3((S + 63) / 64), dim3(64), 0, st, zt, zd, tok, u_acc, S, L, V, chunks,
-                     (const double*)stats, n_acc, alpha);
-  hipLaunchKernelGGL((verify_rowstat64_kernel<DT>), dim3(chunks, S), dim3(VT), 0, st, zt, zd, L, V, clen, chunks, (const int32_t*)n_acc,
-                     rowstat);
-  hipLaunchKernelGGL((verify_residual_kernel<DT>), dim3(chunks, S), dim3(VT), 0, st, zt, zd, L, V, clen, chunks, (const int32_t*)n_acc,
-                     (const double*)rowstat, part);
-  hipLaunchKernelGGL((verify_sample_kernel<DT>), dim3(S), dim3(1024), 0, st, zt, zd, L, V, clen, chunks, (const int32_t*)n_acc,
-                     (const double*)rowstat, (const double*)part, u_res, corr);
+  hipLaunchKernelGGL((verify_accept_kernel<DT>), dim3(S), dim3(64), 0, st, zt, zd, tok, u_acc, L, V, chunks, (const double*)stats, n_acc,
+                     alpha, rowmax);
+  hipLaunchKernelGGL((verify_rowsum64_kernel<DT>), dim3(rchunks, S), dim3(VT), 0, st, zt, zd, L, V, rlen, rchunks, (const int32_t*)n_acc,
+                     (const double*)rowmax, rowsum);
+  hipLaunchKernelGGL((verify_residual_kernel<DT>), dim3(rchunks, S), dim3(VT), 0, st, zt, zd, L, V, rlen, rchunks, (const int32_t*)n_acc,
+                     (const double*)rowmax, (const double*)rowsum, part);
+  hipLaunchKernelGGL((verify_sample_kernel<DT>), dim3(S), dim3(1024), 0, st, zt, zd, L, V, rlen, rchunks, (const int32_t*)n_acc,
+                     (const double*)rowmax, (const double*)rowsum, (const double*)part, u_res, corr);
   return hipGetLastError();
 }
 
 hipError_t launch_verify(const void* zt, const void* zd, const int32_t* tok, const float* u_acc, const float* u_res, int S, int L,
                          int V, int dtype, int32_t* n_acc, int32_t* corr, float* alpha, void* ws, hipStream_t st) {
-  if (S < 1 || L < 1 || V < 2 || (long)S * L > 65535 || S > 65535) return hipErrorInvalidValue;
+  if (S < 1 || L < 1 || V < 2 || (long)S * L > 65535) return hipErrorInvalidValue;
   return dtype == DT_BF16 ? launch_verify_t<DT_BF16>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st)
                           : launch_verify_t<DT_F32>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st);
 }
