@@ -209,25 +209,31 @@ VERIFY_VOCAB = 151936      # vocabulary width of the stand-in workload (a curren
 
 
 def make_verify_batch(n_seq: int, n_draft: int, vocab: int, dtype: int = BF16, seed: int = 0,
-                      disagreement: float = 0.6, peak: float = 9.0, copy_rows: int = 0) -> Dict[str, np.ndarray]:
+                      disagreement: float = 0.6, peak: Optional[float] = None, copy_rows: int = 0) -> Dict[str, np.ndarray]:
     """Draft/target logits, drafted tokens and uniforms for ``n_seq`` sequences of ``n_draft`` positions.
 
     The paper measures on the logits of InternVL2.5 models; these stand in for them with the structure the
     verification step reacts to.  Target logits are N(0, 2^2) over the vocabulary with a handful of boosted
     words per row (+``peak`` on one word, +``peak``/2 on three more), so that each row's distribution is peaked
-    like a language model's; draft logits are the target's plus N(0, ``disagreement``^2) noise, so that the two
+    like a language model's.  With ``peak=None`` every row draws its own boost, ln(V) + 2 + N(0, 2^2): the top
+    word then holds anything from a few percent to nearly all of the mass (the N(0, 2^2) body of V words weighs
+    about V e^2), so confident and uncertain positions both occur.  Draft logits are the target's plus N(0, ``disagreement``^2) noise, so that the two
     models mostly agree.  In the first ``copy_rows`` sequences the draft row equals the target row exactly
     (acceptance probability one, empty residual).  The drafted token is a draw from the draft's distribution,
     taken as the argmax of draft logits plus Gumbel noise, which needs no normalisation.  Uniforms are float32
     in [0, 1).  Logits are rounded once to the storage dtype BEFORE the drafted token is drawn.
-    Streams are drawn in the fixed order target, boosts, noise, Gumbel, uniforms.
+    Streams are drawn in the fixed order target, boosted words, boosts, noise, Gumbel, uniforms.
     """
     rng = np.random.default_rng(BASE_SEED + 500000 + seed)
     S, L, V = n_seq, n_draft, vocab
     zt = 2.0 * rng.standard_normal((S, L, V), dtype=np.float32)
     hot = rng.integers(0, V, size=(S, L, 4))
+    if peak is None:
+        boost = (np.log(V) + 2.0 + 2.0 * rng.standard_normal((S, L, 1))).astype(np.float32)
+    else:
+        boost = np.full((S, L, 1), peak, dtype=np.float32)
     for j in range(4):
-        np.put_along_axis(zt, hot[:, :, j:j + 1], np.float32(peak if j == 0 else peak / 2) +
+        np.put_along_axis(zt, hot[:, :, j:j + 1], (boost if j == 0 else boost / 2) +
                           np.take_along_axis(zt, hot[:, :, j:j + 1], axis=2), axis=2)
     zd = zt + np.float32(disagreement) * rng.standard_normal((S, L, V), dtype=np.float32)
     zd[:copy_rows] = zt[:copy_rows]

@@ -212,6 +212,43 @@ int covspec_verify(const covspec_verify_params* p, const void* z_target, const v
                    int32_t* n_accept_out, int32_t* correction_out, float* alpha_out,
                    void* workspace, size_t workspace_bytes, covspec_stream_t stream);
 
+/*
+ * Draft-side vocabulary pass: margin gate (paper Sec. III-B, the margin and gating equations) and
+ * bonus-token candidates for parallel branching (Sec. III-C, the fan-out equation and the candidate
+ * rule), from one read of the draft logits.  For each of n_seq sequences and each position
+ * j = 0..n_draft-1 of its drafted segment, with p_d = softmax(z_draft[s, j, :]):
+ *   margin[s, j] = p_(1) - p_(2), the two largest probabilities;
+ *   gate[s, j]   = 0 if margin >= gamma (commit locally), 1 otherwise (verify); compared in fp32;
+ *   F_j          = ceil(fanout0 * rho^j), evaluated on the host in double precision with pow();
+ *   cand[s, j, 0..F_j-1] = the F_j words with the largest draft logits other than tokens[s, j], by
+ *                  descending logit, the lower word first among equal logits; entries from F_j (or from
+ *                  vocab - 1, if smaller) up to fanout0 are -1.
+ * covspec_draft_fanout writes F_0..F_{n_draft-1} to a HOST array.  Other pointers are DEVICE pointers,
+ * dense row-major, z_draft 16-byte aligned:
+ *   z_draft [n_seq, n_draft, vocab] dtype;  tokens [n_seq, n_draft] int32 (a value outside [0, vocab)
+ *   excludes nothing);  margin_out [n_seq, n_draft] fp32 (required);  gate_out [n_seq, n_draft] int32
+ *   (required);  cand_out [n_seq, n_draft, fanout0] int32 (required unless fanout0 == 0).
+ * Limits: 0 <= fanout0 <= 32, 0 < rho <= 1, n_draft <= 64, n_seq * n_draft <= 65535, vocab a multiple of
+ * 8 (bf16) or 4 (fp32) and at most 524288, else COVSPEC_INVALID_ARG / COVSPEC_UNSUPPORTED.  Workspace as
+ * for covspec_verify (covspec_draft_workspace_size bytes, 256-byte aligned).  Enqueues on `stream`,
+ * does not synchronise, allocates nothing.  Returns a covspec_status.
+ */
+typedef struct covspec_draft_params {
+  int32_t n_seq;    /* S                                                    */
+  int32_t n_draft;  /* L: positions per drafted segment                     */
+  int32_t vocab;    /* V                                                    */
+  int32_t dtype;    /* covspec_dtype of the logits                          */
+  int32_t fanout0;  /* F_0: candidates at the first position                */
+  float rho;        /* decay of the fan-out, 0 < rho <= 1                   */
+  float gamma;      /* margin threshold of the gate                         */
+} covspec_draft_params;
+
+int covspec_draft_fanout(const covspec_draft_params* p, int32_t* fanout_out);
+size_t covspec_draft_workspace_size(const covspec_draft_params* p);
+int covspec_draft_gate(const covspec_draft_params* p, const void* z_draft, const int32_t* tokens,
+                       float* margin_out, int32_t* gate_out, int32_t* cand_out,
+                       void* workspace, size_t workspace_bytes, covspec_stream_t stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* covspec_status_string(int status);
 

@@ -22,7 +22,8 @@ OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
 
 EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
            "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string",
-           "covspec_verify_workspace_size", "covspec_verify")
+           "covspec_verify_workspace_size", "covspec_verify", "covspec_draft_fanout", "covspec_draft_workspace_size",
+           "covspec_draft_gate")
 
 
 class CovspecParams(ctypes.Structure):
@@ -34,6 +35,11 @@ class CovspecParams(ctypes.Structure):
 
 class CovspecVerifyParams(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("n_seq", "n_draft", "vocab", "dtype")]
+
+
+class CovspecDraftParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_seq", "n_draft", "vocab", "dtype", "fanout0")] + [
+        ("rho", ctypes.c_float), ("gamma", ctypes.c_float)]
 
 
 class CovspecError(RuntimeError):
@@ -74,6 +80,13 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_verify_workspace_size.argtypes = [vpp]
     lib.covspec_verify.restype = ctypes.c_int
     lib.covspec_verify.argtypes = [vpp] + [vp] * 8 + [vp, ctypes.c_size_t, vp]
+    dpp = ctypes.POINTER(CovspecDraftParams)
+    lib.covspec_draft_fanout.restype = ctypes.c_int
+    lib.covspec_draft_fanout.argtypes = [dpp, ctypes.POINTER(ctypes.c_int32)]
+    lib.covspec_draft_workspace_size.restype = ctypes.c_size_t
+    lib.covspec_draft_workspace_size.argtypes = [dpp]
+    lib.covspec_draft_gate.restype = ctypes.c_int
+    lib.covspec_draft_gate.argtypes = [dpp] + [vp] * 5 + [vp, ctypes.c_size_t, vp]
     lib.covspec_status_string.restype = ctypes.c_char_p
     lib.covspec_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -285,3 +298,53 @@ def verify(p: VerifyParams, z_target, z_draft, tokens, u_accept, u_resample, wor
     if st != OK:
         raise CovspecError(st, "covspec_verify")
     return n_acc, corr, alpha
+
+
+@dataclass
+class DraftParams:
+    n_seq: int
+    n_draft: int
+    vocab: int
+    dtype: int = BF16
+    fanout0: int = 8
+    rho: float = 0.5
+    gamma: float = 0.5
+
+    def c_struct(self) -> CovspecDraftParams:
+        return CovspecDraftParams(self.n_seq, self.n_draft, self.vocab, self.dtype, self.fanout0, self.rho, self.gamma)
+
+
+def draft_fanout(p: DraftParams):
+    """covspec_draft_fanout: [F_0, ..., F_{L-1}]."""
+    cs = p.c_struct()
+    out = (ctypes.c_int32 * max(p.n_draft, 1))()
+    st = load_library().covspec_draft_fanout(ctypes.byref(cs), out)
+    if st != OK:
+        raise CovspecError(st, "covspec_draft_fanout")
+    return list(out)[:p.n_draft]
+
+
+def draft_workspace_size(p: DraftParams) -> int:
+    cs = p.c_struct()
+    return int(load_library().covspec_draft_workspace_size(ctypes.byref(cs)))
+
+
+def draft_gate(p: DraftParams, z_draft, tokens, workspace=None):
+    """covspec_draft_gate: returns (margin [S, L] fp32, gate [S, L] int32, cand [S, L, F0] int32 or None)."""
+    import torch
+    dev = z_draft.device
+    if workspace is None:
+        n = draft_workspace_size(p)
+        if n == 0:
+            raise CovspecError(INVALID_ARG, "covspec_draft_workspace_size")
+        workspace = torch.empty(n + 256, dtype=torch.uint8, device=dev)
+    margin = torch.empty(p.n_seq, p.n_draft, dtype=torch.float32, device=dev)
+    gate = torch.empty(p.n_seq, p.n_draft, dtype=torch.int32, device=dev)
+    cand = torch.empty(p.n_seq, p.n_draft, p.fanout0, dtype=torch.int32, device=dev) if p.fanout0 > 0 else None
+    wp, wb = _ws_args(workspace)
+    cs = p.c_struct()
+    st = load_library().covspec_draft_gate(ctypes.byref(cs), _ptr(z_draft), _ptr(tokens), _ptr(margin), _ptr(gate), _ptr(cand),
+                                           wp, wb, _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_draft_gate")
+    return margin, gate, cand

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcovspec.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["covspec_api.hip", "gemm.hip", "gemm64.hip", "elementwise.hip", "select.hip", "eigen.hip", "subspace.hip", "greedy.hip", "verify.hip"]
+SOURCES = ["covspec_api.hip", "gemm.hip", "gemm64.hip", "elementwise.hip", "select.hip", "eigen.hip", "subspace.hip", "greedy.hip", "verify.hip", "draft.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -40,7 +40,7 @@ def build(verbose: bool = False) -> str:
         src, obj = pair
         return _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
 
-    with ThreadPoolExecutor(max_workers=min(9, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(10, len(SOURCES))) as ex:
         outs = list(ex.map(one, zip(SOURCES, objs)))
     outs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]))
     if verbose:

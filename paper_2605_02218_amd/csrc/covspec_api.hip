@@ -474,6 +474,43 @@ int covspec_verify(const covspec_verify_params* p, const void* z_target, const v
   return e == hipSuccess ? COVSPEC_OK : COVSPEC_HIP_ERROR;
 }
 
+static int draft_check(const covspec_draft_params* p) {
+  if (!p) return COVSPEC_INVALID_ARG;
+  if (p->n_seq < 1 || p->n_draft < 1 || p->vocab < 2 || p->fanout0 < 0) return COVSPEC_INVALID_ARG;
+  if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16) return COVSPEC_INVALID_ARG;
+  if (!(p->rho > 0.f && p->rho <= 1.f) || !(p->gamma == p->gamma)) return COVSPEC_INVALID_ARG;
+  if (p->fanout0 > 32 || p->n_draft > 64 || (long)p->n_seq * p->n_draft > 65535) return COVSPEC_UNSUPPORTED;
+  if (p->vocab % (p->dtype == COVSPEC_BF16 ? 8 : 4) != 0 || p->vocab > draft_max_vocab()) return COVSPEC_UNSUPPORTED;
+  return COVSPEC_OK;
+}
+
+int covspec_draft_fanout(const covspec_draft_params* p, int32_t* fanout_out) {
+  const int st = draft_check(p);
+  if (st != COVSPEC_OK) return st;
+  if (!fanout_out) return COVSPEC_INVALID_ARG;
+  for (int j = 0; j < p->n_draft; ++j) fanout_out[j] = (int32_t)ceil((double)p->fanout0 * pow((double)p->rho, (double)j));
+  return COVSPEC_OK;
+}
+
+size_t covspec_draft_workspace_size(const covspec_draft_params* p) {
+  if (draft_check(p) != COVSPEC_OK) return 0;
+  return draft_workspace_bytes(p->n_seq, p->n_draft, p->vocab);
+}
+
+int covspec_draft_gate(const covspec_draft_params* p, const void* z_draft, const int32_t* tokens, float* margin_out,
+                       int32_t* gate_out, int32_t* cand_out, void* workspace, size_t workspace_bytes, covspec_stream_t stream) {
+  const int st = draft_check(p);
+  if (st != COVSPEC_OK) return st;
+  if (!z_draft || !tokens || !margin_out || !gate_out || !workspace || (p->fanout0 > 0 && !cand_out)) return COVSPEC_INVALID_ARG;
+  if (((uintptr_t)z_draft & 15) || ((uintptr_t)workspace & 255)) return COVSPEC_INVALID_ARG;
+  if (workspace_bytes < draft_workspace_bytes(p->n_seq, p->n_draft, p->vocab)) return COVSPEC_WORKSPACE_TOO_SMALL;
+  int32_t fan[64];
+  covspec_draft_fanout(p, fan);
+  const hipError_t e = launch_draft(z_draft, tokens, p->n_seq, p->n_draft, p->vocab, p->dtype, p->fanout0, fan, p->gamma, margin_out,
+                                    gate_out, cand_out, workspace, (hipStream_t)stream);
+  return e == hipSuccess ? COVSPEC_OK : COVSPEC_HIP_ERROR;
+}
+
 const char* covspec_status_string(int status) {
   switch (status) {
     case COVSPEC_OK: return "ok";

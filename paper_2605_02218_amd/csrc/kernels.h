@@ -155,4 +155,14 @@ size_t verify_workspace_bytes(int S, int L, int V, int dtype);
 hipError_t launch_verify(const void* zt, const void* zd, const int32_t* tok, const float* u_acc, const float* u_res, int S, int L,
                          int V, int dtype, int32_t* n_acc, int32_t* corr, float* alpha, void* ws, hipStream_t stream);
 
+// ---------------------------------------------------------------- draft.hip
+// Draft-side vocabulary pass (paper Sec. III-B margin gate, Sec. III-C bonus-token candidates): zd [S, L, V] draft
+// logits, tok [S, L] drafted tokens, fanout[L] (host) = F_j <= F0 <= 32.  margin, gate [S, L]; cand [S, L, F0]
+// (-1 beyond F_j; may be NULL when F0 == 0).
+int draft_chunks(int V);
+int draft_max_vocab();
+size_t draft_workspace_bytes(int S, int L, int V);
+hipError_t launch_draft(const void* zd, const int32_t* tok, int S, int L, int V, int dtype, int F0, const int* fanout, float gamma,
+                        float* margin, int32_t* gate, int32_t* cand, void* ws, hipStream_t stream);
+
 }  // namespace covspec

@@ -11,62 +11,13 @@
 // residual passes (2 per word, one row per sequence).
 #include "common.h"
 #include "kernels.h"
+#include "vocab.h"
 
 namespace covspec {
 
 namespace {
 
 constexpr int VT = 256;            // threads of the streaming kernels
-
-template <int DT> struct LogitVec;
-template <> struct LogitVec<DT_BF16> {
-  static constexpr int N = 8;
-  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[8]) {
-    const u32x4_t w = *(const u32x4_t*)((const bf16_t*)p + i);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { v[2 * e] = bf16lo_to_f32(w[e]); v[2 * e + 1] = bf16hi_to_f32(w[e]); }
-  }
-  static __device__ __forceinline__ double at(const void* p, long i) { return (double)bf16_to_f32(((const bf16_t*)p)[i]); }
-};
-template <> struct LogitVec<DT_F32> {
-  static constexpr int N = 4;
-  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[4]) {
-    const f32x4_t w = *(const f32x4_t*)((const float*)p + i);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = w[e];
-  }
-  static __device__ __forceinline__ double at(const void* p, long i) { return (double)((const float*)p)[i]; }
-};
-
-// The streaming pass works in the base-2 domain: y = x * kLog2e (kLog2e the fp32 constant below, also used as
-// the exact same number in the fp64 steps), terms 2^(y - c) against a reference c that is the largest y seen so
-// far rounded to fp32.  One fused multiply-add forms y - c with a single rounding, so a term costs fma + exp2 +
-// add.  The reference need not be the exact maximum: (c, sum) pairs combine exactly whatever c is.  kLog2e
-// differs from log2(e) by 1.3e-8 relative, i.e. a temperature of 1 + 1.3e-8: below 1e-6 in any probability
-// ratio for logits within +-50 of each other.
-constexpr float kLog2e = 1.44269502f;
-
-// running (reference, sum of 2^(y - reference)) of one thread, extended by a vector of N values
-template <int N>
-__device__ __forceinline__ void online_add(float& c, float& s, const float (&v)[N]) {
-  float vm = v[0];
-#pragma unroll
-  for (int e = 1; e < N; ++e) vm = fmaxf(vm, v[e]);
-  const float cx = fmaxf(c, vm * kLog2e);
-  const float cn = cx == -INFINITY ? 0.f : cx;   // only masked (-inf) words so far: any finite reference gives zeros
-  float acc = s * __builtin_amdgcn_exp2f(c - cn);   // c = -inf at the start: 2^-inf = 0
-#pragma unroll
-  for (int e = 0; e < N; ++e) acc += __builtin_amdgcn_exp2f(__builtin_fmaf(v[e], kLog2e, -cn));
-  c = cx;
-  s = acc;
-}
-
-// combine of two (reference, sum) pairs of the base-2 domain
-__device__ __forceinline__ void combine_pair(double& m, double& s, double m2, double s2) {
-  const double mn = fmax(m, m2);
-  s = (m == mn ? s : s * exp2(m - mn)) + (m2 == mn ? s2 : s2 * exp2(m2 - mn));
-  m = mn;
-}
 
 // stats[(row * chunks + c) * 4 + {0,1,2,3}] = ref_t, sum_t, ref_d, sum_d (base-2 domain) over words [c*clen, min(V, (c+1)*clen))
 template <int DT>
@@ -90,17 +41,8 @@ __global__ __launch_bounds__(VT) void verify_stats_kernel(const void* __restrict
   }
   // wave, then block combine in fp64
   double m[2] = {(double)mt, (double)md}, s[2] = {(double)st, (double)sd};
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const double m2 = __shfl_xor(m[q], o, 64), s2 = __shfl_xor(s[q], o, 64);
-      if (s2 > 0.0) {
-        if (s[q] > 0.0) combine_pair(m[q], s[q], m2, s2);
-        else { m[q] = m2; s[q] = s2; }
-      }
-    }
-  }
+  wave_combine(m[0], s[0]);
+  wave_combine(m[1], s[1]);
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   if (lane == 0) { red[0][wv][0] = m[0]; red[0][wv][1] = s[0]; red[1][wv][0] = m[1]; red[1][wv][1] = s[1]; }
   __syncthreads();

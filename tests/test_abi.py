@@ -121,3 +121,35 @@ def test_verify_params_are_validated_on_the_host():
     assert lib.covspec_verify(ctypes.byref(cs), fake + 8, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == Bd.INVALID_ARG
     assert lib.covspec_verify(ctypes.byref(cs), fake, fake, fake, fake, fake, fake, fake, None, fake, 16, None) == Bd.WORKSPACE_TOO_SMALL
     assert lib.covspec_verify(None, fake, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == Bd.INVALID_ARG
+
+
+def test_draft_params_validation_and_fanout_match_the_oracle_formula():
+    """covspec_draft_fanout is host arithmetic: F_j = ceil(F_0 rho^j) must agree with the oracle's evaluation for
+    every (F_0, rho) on a grid, exact powers of two included (rho is a float32 in the parameter block)."""
+    import numpy as np
+    from oracle import draft_oracle as DO
+    assert ctypes.sizeof(Bd.CovspecDraftParams) == 7 * 4
+    for f0 in (0, 1, 2, 5, 8, 16, 32):
+        for rho in (0.5, 0.25, 0.6, 0.7, 0.9, 1.0, 1 / 3, 0.999):
+            p = C.DraftParams(n_seq=2, n_draft=12, vocab=4096, fanout0=f0, rho=rho)
+            assert C.draft_fanout(p) == DO.fanout(f0, float(np.float32(rho)), 12), (f0, rho)
+    assert C.draft_fanout(C.DraftParams(1, 6, 4096, fanout0=8, rho=0.5)) == [8, 4, 2, 1, 1, 1]
+    lib = C.load_library()
+    ok = C.DraftParams(4, 8, 8192)
+    assert C.draft_workspace_size(ok) > 0
+    fake = 4096
+    for bad, status in [(C.DraftParams(0, 8, 8192), Bd.INVALID_ARG), (C.DraftParams(4, 8, 8192, rho=0.0), Bd.INVALID_ARG),
+                        (C.DraftParams(4, 8, 8192, rho=1.5), Bd.INVALID_ARG), (C.DraftParams(4, 8, 8192, gamma=float("nan")), Bd.INVALID_ARG),
+                        (C.DraftParams(4, 8, 8192, fanout0=-1), Bd.INVALID_ARG), (C.DraftParams(4, 8, 8192, fanout0=33), Bd.UNSUPPORTED),
+                        (C.DraftParams(4, 65, 8192), Bd.UNSUPPORTED), (C.DraftParams(4, 8, 8196, C.BF16), Bd.UNSUPPORTED),
+                        (C.DraftParams(4, 8, 524288 + 8), Bd.UNSUPPORTED), (C.DraftParams(2000, 64, 8192), Bd.UNSUPPORTED)]:
+        assert C.draft_workspace_size(bad) == 0
+        cs = bad.c_struct()
+        assert lib.covspec_draft_gate(ctypes.byref(cs), fake, fake, fake, fake, fake, fake, 1 << 40, None) == status
+    cs = ok.c_struct()
+    assert lib.covspec_draft_gate(ctypes.byref(cs), None, fake, fake, fake, fake, fake, 1 << 40, None) == Bd.INVALID_ARG
+    assert lib.covspec_draft_gate(ctypes.byref(cs), fake, fake, fake, fake, None, fake, 1 << 40, None) == Bd.INVALID_ARG
+    assert lib.covspec_draft_gate(ctypes.byref(cs), fake, fake, fake, fake, fake, fake, 16, None) == Bd.WORKSPACE_TOO_SMALL
+    assert lib.covspec_draft_gate(ctypes.byref(cs), fake + 4, fake, fake, fake, fake, fake, 1 << 40, None) == Bd.INVALID_ARG
+    cs0 = C.DraftParams(4, 8, 8192, fanout0=0).c_struct()     # margin only: no candidate buffer needed
+    assert lib.covspec_draft_gate(ctypes.byref(cs0), fake, fake, fake, fake, None, fake, 16, None) == Bd.WORKSPACE_TOO_SMALL
