@@ -223,6 +223,60 @@ def verify_bench(a):
     print(json.dumps(line), flush=True)
 
 
+def draft_bench(a):
+    """--draft: the draft-side vocabulary pass (paper Sec. III-B margin gate, Sec. III-C candidates), own JSON line.
+
+    A step is one covspec_draft_gate call: 64 sequences x 8 positions x 151,936 words of bf16 draft logits resident
+    in HBM, F_0 = 8, rho = 1/2.  Algorithmic bytes per call = the logits read once (S L V e) plus the small outputs;
+    `achieved` is that figure over the whole call's time (two kernels).
+    """
+    import numpy as np
+    import torch
+    import covspec_inputs as I
+    import paper_2605_02218_amd as C
+    C.load_library()
+    torch.cuda.set_device(0)
+    S, L, V, dtype, F0, rho, gamma = 64, 8, I.VERIFY_VOCAB, I.BF16, 8, 0.5, 0.5
+    d = I.make_verify_batch(S, L, V, dtype, seed=2024, copy_rows=2)
+    zd = torch.from_numpy(d["zd"].view(np.int16)).cuda().view(torch.bfloat16)
+    tok = torch.from_numpy(d["tok"]).cuda()
+    p = C.DraftParams(S, L, V, dtype, F0, rho, gamma)
+    ws = torch.empty(C.draft_workspace_size(p) + 256, dtype=torch.uint8, device="cuda")
+    for _ in range(a.warmup):
+        C.draft_gate(p, zd, tok, workspace=ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(a.steps):
+        C.draft_gate(p, zd, tok, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    ms = e0.elapsed_time(e1) / a.steps
+    alg = 1.0 * S * L * V * 2 + S * L * (4 + 4 + 4 + 4 * F0)
+    line = {"metric": "drafted positions gated/sec (margin gate and bonus-token candidates over the vocabulary)",
+            "value": round(S * L / max(ms, wall_ms) * 1e3, 1), "unit": "positions/s", "n_gpus": 1, "steps": a.steps,
+            "warmup": a.warmup, "ms_per_step": round(max(ms, wall_ms), 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "draft gate S=%d L=%d V=%d F0=%d rho=%g gamma=%g" % (S, L, V, F0, rho, gamma),
+                       "entry_point": "covspec_draft_gate"},
+            "roofline": {"bound": "hbm", "achieved": round(alg / (ms * 1e-3) / 1e9, 1), "peak": PEAK["hbm_GBps"], "unit": "GB/s",
+                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": None,
+                         "kernel": "whole call (draft_scan_kernel streams the logits)", "device_ms": round(ms, 4)}}
+    if not a.no_cpu_baseline:
+        from oracle import draft_oracle as DO
+        t0 = time.perf_counter()
+        n = 0
+        while n < S and time.perf_counter() - t0 < 10.0:
+            DO.draft_pass(I.as_f64(d["zd"][n], dtype), d["tok"][n], F0, float(np.float32(rho)), float(np.float32(gamma)))
+            n += 1
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": round(n * L / dt, 2), "unit": "positions/s", "cores": 1, "kind": "oracle",
+                                "sample": "%d of the %d sequences of the same batch" % (n, S)}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -233,6 +287,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other workloads and pipeline (extra keys)")
     ap.add_argument("--verify", action="store_true", help="time the speculative verification step instead (own JSON line)")
+    ap.add_argument("--draft", action="store_true", help="time the draft-side margin gate / candidate pass instead (own JSON line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 1 GiB device copies and exit (reference reading for the HBM byte counters)")
     a = ap.parse_args()
@@ -253,6 +308,9 @@ def main():
         return
     if a.verify:
         verify_bench(a)
+        return
+    if a.draft:
+        draft_bench(a)
         return
     import covspec_inputs as I
     import paper_2605_02218_amd as C

@@ -64,8 +64,9 @@ __global__ __launch_bounds__(DTH) void draft_scan_kernel(const void* __restrict_
   const int w0 = c * DCL, w1 = min(V, w0 + DCL);      // V % N == 0: whole vectors only
   const long base = row * (long)V;
 
+  // a slot without a word, or with a NaN logit, compares false against every threshold and is skipped by max
   float v[EPT];
-  uint32_t valid = 0u;
+  uint32_t valid = 0u;                 // whole vectors: bits i*N .. i*N+N-1
   float cref = -INFINITY, sum = 0.f, tmax = -INFINITY;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -74,41 +75,25 @@ __global__ __launch_bounds__(DTH) void draft_scan_kernel(const void* __restrict_
       float t[N];
       LogitVec<DT>::load(zd, base + w, t);
       online_add<N>(cref, sum, t);
+      valid |= ((N == 8 ? 0xFFu : 0xFu) << (i * N));
 #pragma unroll
-      for (int e = 0; e < N; ++e) {
-        v[i * N + e] = t[e];
-        if (t[e] == t[e]) { valid |= 1u << (i * N + e); tmax = fmaxf(tmax, t[e]); }   // a NaN logit is never a candidate
-      }
+      for (int e = 0; e < N; ++e) { v[i * N + e] = t[e]; tmax = fmaxf(tmax, t[e]); }
     } else {
 #pragma unroll
-      for (int e = 0; e < N; ++e) v[i * N + e] = -INFINITY;
+      for (int e = 0; e < N; ++e) v[i * N + e] = __builtin_nanf("");
     }
   }
   auto word_of = [&](int e) { return w0 + ((e / N) * DTH + tid) * N + (e % N); };
 
-  // statistics of the chunk
-  {
-    double m = (double)cref, s = (double)sum;
-    wave_combine(m, s);
-    if (lane == 0) { red[wv][0] = m; red[wv][1] = s; }
-  }
   // quad maxima -> tau
   tmax = fmaxf(tmax, __shfl_xor(tmax, 1, 64));
   tmax = fmaxf(tmax, __shfl_xor(tmax, 2, 64));
   if ((lane & 3) == 0) gkey[tid >> 2] = ((u64)float_order_key(tmax) << 32) | (u64)(63 - (tid >> 2));
   if (tid == 0) sh_cnt = 0;
-  __syncthreads();
-  if (tid == 0) {
-    double mm = red[0][0], ss = red[0][1];
-    for (int k = 1; k < DTH / 64; ++k) {
-      const double m2 = red[k][0], s2 = red[k][1];
-      if (s2 > 0.0) {
-        if (ss > 0.0) combine_pair(mm, ss, m2, s2);
-        else { mm = m2; ss = s2; }
-      }
-    }
-    stats[(row * chunks + c) * 2] = mm;
-    stats[(row * chunks + c) * 2 + 1] = ss;
+  {
+    double mm, ss;
+    block_combine<DTH / 64>(cref, sum, red, mm, ss);      // its barrier also publishes gkey and sh_cnt
+    if (tid == 0) { stats[(row * chunks + c) * 2] = mm; stats[(row * chunks + c) * 2 + 1] = ss; }
   }
   if (wv == 0) {
     const u64 mine = gkey[lane];
@@ -118,7 +103,7 @@ __global__ __launch_bounds__(DTH) void draft_scan_kernel(const void* __restrict_
   const float tau = sh_tau;
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
-    if (((valid >> e) & 1u) && v[e] >= tau) {
+    if (v[e] >= tau) {
       const int pos = atomicAdd(&sh_cnt, 1);
       if (pos < LISTCAP) list[pos] = pack_key(v[e], word_of(e));
     }
@@ -141,7 +126,7 @@ __global__ __launch_bounds__(DTH) void draft_scan_kernel(const void* __restrict_
     u64 best = 0ull;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      if ((alive >> e) & 1u) {
+      if (((alive >> e) & 1u) && v[e] == v[e]) {
         const u64 k = pack_key(v[e], word_of(e));
         best = k > best ? k : best;
       }

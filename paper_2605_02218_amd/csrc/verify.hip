@@ -24,7 +24,7 @@ template <int DT>
 __global__ __launch_bounds__(VT) void verify_stats_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int V, int clen,
                                                           int chunks, double* __restrict__ stats) {
   constexpr int N = LogitVec<DT>::N;
-  __shared__ double red[4][VT / 64][2];
+  __shared__ double red[2][VT / 64][2];
   const long row = blockIdx.y;
   const int c = blockIdx.x;
   const int w0 = c * clen, w1 = min(V, w0 + clen);
@@ -39,27 +39,11 @@ __global__ __launch_bounds__(VT) void verify_stats_kernel(const void* __restrict
     online_add<N>(mt, st, a);
     online_add<N>(md, sd, b);
   }
-  // wave, then block combine in fp64
-  double m[2] = {(double)mt, (double)md}, s[2] = {(double)st, (double)sd};
-  wave_combine(m[0], s[0]);
-  wave_combine(m[1], s[1]);
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  if (lane == 0) { red[0][wv][0] = m[0]; red[0][wv][1] = s[0]; red[1][wv][0] = m[1]; red[1][wv][1] = s[1]; }
-  __syncthreads();
-  if (threadIdx.x < 2) {
-    const int q = threadIdx.x;
-    double mm = red[q][0][0], ss = red[q][0][1];
-    for (int k = 1; k < VT / 64; ++k) {
-      const double m2 = red[q][k][0], s2 = red[q][k][1];
-      if (s2 > 0.0) {
-        if (ss > 0.0) combine_pair(mm, ss, m2, s2);
-        else { mm = m2; ss = s2; }
-      }
-    }
-    double* o = stats + (row * chunks + c) * 4 + 2 * q;
-    o[0] = mm;
-    o[1] = ss;
-  }
+  double mm, ss;
+  block_combine<VT / 64>(mt, st, red[0], mm, ss);
+  if (threadIdx.x == 0) { stats[(row * chunks + c) * 4] = mm; stats[(row * chunks + c) * 4 + 1] = ss; }
+  block_combine<VT / 64>(md, sd, red[1], mm, ss);
+  if (threadIdx.x == 0) { stats[(row * chunks + c) * 4 + 2] = mm; stats[(row * chunks + c) * 4 + 3] = ss; }
 }
 
 // One wave per sequence, one lane per drafted position: row statistics from the chunk partials, alpha at the

@@ -70,4 +70,30 @@ __device__ __forceinline__ void wave_combine(double& m, double& s) {
   }
 }
 
+
+// Workgroup combine of the threads' fp32 (reference, sum) pairs: each wave rescales to its largest reference
+// (one fp32 exp2 per lane, relative error ~1e-7, inside the streaming sums' own), adds in fp64, and thread 0
+// folds the waves the same way.  `red` holds 2 doubles per wave.  Contains a barrier: call uniformly; the
+// result is valid in thread 0 only (sum 0 when every word was masked).
+template <int WAVES>
+__device__ __forceinline__ void block_combine(float c, float s, double (*red)[2], double& ref_out, double& sum_out) {
+  const float cw = wave_max(c);
+  const float f = cw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(c - cw);
+  const double sw = wave_sum((double)(s * f));
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  if (lane == 0) { red[wv][0] = (double)cw; red[wv][1] = sw; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double cb = red[0][0];
+#pragma unroll
+    for (int k = 1; k < WAVES; ++k) cb = fmax(cb, red[k][0]);
+    double tot = 0.0;
+#pragma unroll
+    for (int k = 0; k < WAVES; ++k)
+      if (red[k][1] > 0.0) tot += red[k][1] * (double)__builtin_amdgcn_exp2f((float)(red[k][0] - cb));
+    ref_out = cb;
+    sum_out = tot;
+  }
+}
+
 }  // namespace covspec
