@@ -39,7 +39,15 @@ __device__ __forceinline__ float key_value(u64 k) {
 // lane's rank among the n <= 64 distinct keys of an LDS array: the number of keys greater than its own
 __device__ __forceinline__ int wave_rank(const u64* keys, int n, u64 mine) {
   int rank = 0;
-  for (int j = 0; j < n; ++j) rank += keys[j] > mine ? 1 : 0;
+  int j = 0;
+  for (; j + 8 <= n; j += 8) {        // eight broadcast reads in flight
+    u64 k[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) k[q] = keys[j + q];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) rank += k[q] > mine ? 1 : 0;
+  }
+  for (; j < n; ++j) rank += keys[j] > mine ? 1 : 0;
   return rank;
 }
 
@@ -74,10 +82,10 @@ __global__ __launch_bounds__(DTH) void draft_scan_kernel(const void* __restrict_
     if (w < w1) {
       float t[N];
       LogitVec<DT>::load(zd, base + w, t);
-      online_add<N>(cref, sum, t);
+      tmax = fmaxf(tmax, online_add<N>(cref, sum, t));
       valid |= ((N == 8 ? 0xFFu : 0xFu) << (i * N));
 #pragma unroll
-      for (int e = 0; e < N; ++e) { v[i * N + e] = t[e]; tmax = fmaxf(tmax, t[e]); }
+      for (int e = 0; e < N; ++e) v[i * N + e] = t[e];
     } else {
 #pragma unroll
       for (int e = 0; e < N; ++e) v[i * N + e] = __builtin_nanf("");
@@ -95,7 +103,10 @@ __global__ __launch_bounds__(DTH) void draft_scan_kernel(const void* __restrict_
     block_combine<DTH / 64>(cref, sum, red, mm, ss);      // its barrier also publishes gkey and sh_cnt
     if (tid == 0) { stats[(row * chunks + c) * 2] = mm; stats[(row * chunks + c) * 2 + 1] = ss; }
   }
-  if (wv == 0) {
+  // the two single-wave steps rotate over the waves with the chunk, so that no one SIMD of the compute unit
+  // carries them for every resident workgroup
+  const int rw = (int)((blockIdx.x + blockIdx.y) & 3u);
+  if (wv == rw) {
     const u64 mine = gkey[lane];
     if (wave_rank(gkey, 64, mine) == K - 1) sh_tau = key_value(mine);     // ranks are a permutation of 0..63; K <= 64
   }
@@ -112,7 +123,7 @@ __global__ __launch_bounds__(DTH) void draft_scan_kernel(const void* __restrict_
   const int n = sh_cnt;
   u64* out = top + (row * chunks + c) * KMAX;
   if (n <= LISTCAP) {
-    if (wv == 0) {
+    if (wv == ((rw + 2) & 3)) {
       const u64 mine = lane < n ? list[lane] : 0ull;
       const int rank = wave_rank(list, n, mine);
       if (lane < n && rank < K) out[rank] = mine;

@@ -10,20 +10,22 @@ namespace covspec {
 template <int DT> struct LogitVec;
 template <> struct LogitVec<DT_BF16> {
   static constexpr int N = 8;
-  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[8]) {
-    const u32x4_t w = *(const u32x4_t*)((const bf16_t*)p + i);
+  static __device__ __forceinline__ u32x4_t load_raw(const void* p, long i) { return *(const u32x4_t*)((const bf16_t*)p + i); }
+  static __device__ __forceinline__ void unpack(const u32x4_t& w, float (&v)[8]) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) { v[2 * e] = bf16lo_to_f32(w[e]); v[2 * e + 1] = bf16hi_to_f32(w[e]); }
   }
+  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[8]) { unpack(load_raw(p, i), v); }
   static __device__ __forceinline__ double at(const void* p, long i) { return (double)bf16_to_f32(((const bf16_t*)p)[i]); }
 };
 template <> struct LogitVec<DT_F32> {
   static constexpr int N = 4;
-  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[4]) {
-    const f32x4_t w = *(const f32x4_t*)((const float*)p + i);
+  static __device__ __forceinline__ u32x4_t load_raw(const void* p, long i) { return *(const u32x4_t*)((const float*)p + i); }
+  static __device__ __forceinline__ void unpack(const u32x4_t& w, float (&v)[4]) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = w[e];
+    for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(w[e]);
   }
+  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[4]) { unpack(load_raw(p, i), v); }
   static __device__ __forceinline__ double at(const void* p, long i) { return (double)((const float*)p)[i]; }
 };
 
@@ -36,8 +38,9 @@ template <> struct LogitVec<DT_F32> {
 constexpr float kLog2e = 1.44269502f;
 
 // running (reference, sum of 2^(y - reference)) of one thread, extended by a vector of N values
+// returns the largest of the N values (NaN ignored)
 template <int N>
-__device__ __forceinline__ void online_add(float& c, float& s, const float (&v)[N]) {
+__device__ __forceinline__ float online_add(float& c, float& s, const float (&v)[N]) {
   float vm = v[0];
 #pragma unroll
   for (int e = 1; e < N; ++e) vm = fmaxf(vm, v[e]);
@@ -48,6 +51,7 @@ __device__ __forceinline__ void online_add(float& c, float& s, const float (&v)[
   for (int e = 0; e < N; ++e) acc += __builtin_amdgcn_exp2f(__builtin_fmaf(v[e], kLog2e, -cn));
   c = cx;
   s = acc;
+  return vm;
 }
 
 // combine of two (reference, sum) pairs of the base-2 domain
