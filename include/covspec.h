@@ -252,6 +252,12 @@ int covspec_draft_gate(const covspec_draft_params* p, const void* z_draft, const
 /* Static, NUL-terminated description of a status code. */
 const char* covspec_status_string(int status);
 
+/* After a COVSPEC_HIP_ERROR on this host thread: the HIP error name and the launch step that
+ * reported it (NUL-terminated, thread-local, valid until the thread's next failing call; empty if
+ * none).  An entry point discards any error an earlier runtime call of the thread left pending
+ * before its first launch, so what is reported belongs to the call that returned the status. */
+const char* covspec_last_error(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
 EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
            "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string",
            "covspec_verify_workspace_size", "covspec_verify", "covspec_draft_fanout", "covspec_draft_workspace_size",
-           "covspec_draft_gate")
+           "covspec_draft_gate", "covspec_last_error")
 
 
 class CovspecParams(ctypes.Structure):
@@ -45,7 +45,8 @@ class CovspecDraftParams(ctypes.Structure):
 class CovspecError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+        detail = load_library().covspec_last_error().decode() if status == HIP_ERROR else ""
+        super().__init__("%s: %s (status %d)%s" % (where, status_string(status), status, " [" + detail + "]" if detail else ""))
 
 
 _lib = None
@@ -56,6 +57,11 @@ def load_library() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own copy of the HIP runtime.  It has to be in the process BEFORE this library is opened,
+    # so that both bind to the same runtime: opened first, the library would pull in the system's copy, and its
+    # launches would then run against a runtime that knows nothing of torch's device memory and streams
+    # (every launch fails with hipErrorNoDevice).
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError("%s not found: run `python -m paper_2605_02218_amd.build` (or __graft_entry__.build()) first"
                           % LIB_PATH)
@@ -89,6 +95,8 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_draft_gate.argtypes = [dpp] + [vp] * 5 + [vp, ctypes.c_size_t, vp]
     lib.covspec_status_string.restype = ctypes.c_char_p
     lib.covspec_status_string.argtypes = [ctypes.c_int]
+    lib.covspec_last_error.restype = ctypes.c_char_p
+    lib.covspec_last_error.argtypes = []
     _lib = lib
     return lib
 

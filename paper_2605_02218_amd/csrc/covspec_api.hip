@@ -3,6 +3,7 @@
 // low-rank energy, keep, gather).  No allocation, no synchronisation, no global state.
 #include <hip/hip_runtime.h>
 #include <math.h>
+#include <stdio.h>
 
 #include "../../include/covspec.h"
 #include "kernels.h"
@@ -130,10 +131,25 @@ int make_plan(const covspec_params* p, Plan* pl) {
   return COVSPEC_OK;
 }
 
+// What failed last on this host thread, for covspec_last_error().
+thread_local char g_last_error[256] = "";
+
+inline void note_error(const char* what, hipError_t e) {
+  snprintf(g_last_error, sizeof(g_last_error), "%s: %s", hipGetErrorName(e), what);
+}
+
+// The launchers report through hipGetLastError(), which also returns an error that some EARLIER runtime call
+// of this thread left behind (another library's, a query that answered "not ready").  Every entry point that
+// launches therefore discards what is pending before its first launch.
+inline void discard_pending_error() { (void)hipGetLastError(); }
+
 #define HIPCHK(expr)                                \
   do {                                              \
     hipError_t e__ = (expr);                        \
-    if (e__ != hipSuccess) return COVSPEC_HIP_ERROR; \
+    if (e__ != hipSuccess) {                        \
+      note_error(#expr, e__);                       \
+      return COVSPEC_HIP_ERROR;                     \
+    }                                               \
   } while (0)
 
 template <typename T>
@@ -145,7 +161,9 @@ struct StageMarks {
   hipStream_t st = nullptr;
   bool ok = true;
   void mark(int stage) {
-    if (ev && hipEventRecord(ev[stage], st) != hipSuccess) ok = false;
+    if (!ev) return;
+    const hipError_t e = hipEventRecord(ev[stage], st);
+    if (e != hipSuccess) { ok = false; note_error("hipEventRecord of a stage event", e); }
   }
 };
 
@@ -377,6 +395,7 @@ int covspec_score(const covspec_params* p, const void* X, const void* hidden, co
   if (st != COVSPEC_OK) return st;
   if (!X || !Q) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
+  discard_pending_error();
   StageMarks none;
   return run_score(pl, X, hidden, Q, Wq, Wk, s_query, s_act, s_fused, workspace, (hipStream_t)stream, none);
 }
@@ -389,6 +408,7 @@ int covspec_select(const covspec_params* p, const void* X, const float* s_fused,
   if (st != COVSPEC_OK) return st;
   if (!X || !idx_out || (!s_fused && pl.lr != COVSPEC_LR_RANDOM)) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
+  discard_pending_error();
   StageMarks none;
   return run_select(pl, X, s_fused, idx_out, c_out, idx_m_out, pick_order_out, resid_out, workspace, (hipStream_t)stream, none);
 }
@@ -401,6 +421,7 @@ static int reduce_impl(const covspec_params* p, const void* X, const void* hidde
   if (st != COVSPEC_OK) return st;
   if (!X || !Q || !idx_out || !tokens_out) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
+  discard_pending_error();
   float* sf = at<float>(workspace, pl.sf);
   if (pl.lr == COVSPEC_LR_RANDOM) {
     for (int e = COVSPEC_STAGE_QUERY_SIDE; e <= COVSPEC_STAGE_FUSE; ++e) marks.mark(e);   // no scores in this mode
@@ -469,8 +490,10 @@ int covspec_verify(const covspec_verify_params* p, const void* z_target, const v
   if (((uintptr_t)z_target | (uintptr_t)z_draft) & 15) return COVSPEC_INVALID_ARG;
   if ((uintptr_t)workspace & 255) return COVSPEC_INVALID_ARG;
   if (workspace_bytes < verify_workspace_bytes(p->n_seq, p->n_draft, p->vocab, p->dtype)) return COVSPEC_WORKSPACE_TOO_SMALL;
+  discard_pending_error();
   const hipError_t e = launch_verify(z_target, z_draft, tokens, u_accept, u_resample, p->n_seq, p->n_draft, p->vocab, p->dtype,
                                      n_accept_out, correction_out, alpha_out, workspace, (hipStream_t)stream);
+  if (e != hipSuccess) note_error("launch_verify", e);
   return e == hipSuccess ? COVSPEC_OK : COVSPEC_HIP_ERROR;
 }
 
@@ -506,10 +529,14 @@ int covspec_draft_gate(const covspec_draft_params* p, const void* z_draft, const
   if (workspace_bytes < draft_workspace_bytes(p->n_seq, p->n_draft, p->vocab)) return COVSPEC_WORKSPACE_TOO_SMALL;
   int32_t fan[64];
   covspec_draft_fanout(p, fan);
+  discard_pending_error();
   const hipError_t e = launch_draft(z_draft, tokens, p->n_seq, p->n_draft, p->vocab, p->dtype, p->fanout0, fan, p->gamma, margin_out,
                                     gate_out, cand_out, workspace, (hipStream_t)stream);
+  if (e != hipSuccess) note_error("launch_draft", e);
   return e == hipSuccess ? COVSPEC_OK : COVSPEC_HIP_ERROR;
 }
+
+const char* covspec_last_error(void) { return g_last_error; }
 
 const char* covspec_status_string(int status) {
   switch (status) {
