@@ -277,6 +277,73 @@ def draft_bench(a):
     print(json.dumps(line), flush=True)
 
 
+def ragged_bench(a):
+    """--ragged: covspec_reduce_ragged on a dynamic-resolution batch, own JSON line.
+
+    64 images of workload 5's width and structure (d = 4096, 128 keywords, bf16, keep ratio 1/9) whose token counts
+    are 256 per tile with 4..12 tiles (the tile grids of a dynamic-resolution vision encoder), sorted by size so
+    that equal sizes form runs.  A step is one call over the packed batch; images/sec with the runs on one stream
+    and dealt to four.
+    """
+    from concurrent.futures import ThreadPoolExecutor
+    from dataclasses import replace
+    import numpy as np
+    import torch
+    import covspec_inputs as I
+    import paper_2605_02218_amd as C
+    C.load_library()
+    torch.cuda.set_device(0)
+    base = I.WORKLOADS[5]
+    tiles = sorted([4, 6, 6, 8, 9, 12, 12, 12] * 8)
+    ws_ = [replace(base, batch=1, n_tokens=256 * t, keep_k=0, preselect_m=0, rank_r=0) for t in tiles]
+    with ThreadPoolExecutor(max_workers=16) as ex:
+        per = list(ex.map(lambda bw: I.make_image(bw[1], bw[0]), enumerate(ws_)))
+    wts = I.make_weights(base)
+    d = base.d_model
+
+    def up(x):
+        return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).cuda().view(torch.bfloat16)
+
+    X = up(np.concatenate([p["X"] for p in per]))
+    Q = up(np.concatenate([p["Q"] for p in per]))
+    Hd = up(np.concatenate([p["hidden"].reshape(-1, d) for p in per]))
+    Wq, Wk = up(wts["Wq"]), up(wts["Wk"])
+    del per
+    nt, nq = [w.n_tokens for w in ws_], [w.n_query for w in ws_]
+    p = C.Params(batch=1, n_tokens=1, d_model=d, n_query=1, n_heads=base.n_heads, n_act_layers=base.n_act_layers, dtype=C.BF16,
+                 keep_ratio=1.0 / 9.0, lam=base.lam)
+    ks, runs = C.ragged_resolve(p, nt, nq)
+    idx = torch.empty(sum(ks), dtype=torch.int32, device="cuda")
+    tok = torch.empty(sum(ks), d, dtype=torch.bfloat16, device="cuda")
+    res = {}
+    for ns in (1, 4):
+        streams = [torch.cuda.Stream() for _ in range(ns)]
+        wsb = torch.empty(C.ragged_workspace_size(p, nt, nq, ns) + 256, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+
+        def step():
+            C.reduce_ragged(p, nt, nq, X, Hd, Q, Wq, Wk, streams=streams, workspace=wsb, idx_out=idx, tokens_out=tok, sync=False)
+
+        for _ in range(max(1, a.warmup // 2)):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            step()
+        torch.cuda.synchronize()
+        res[ns] = (time.perf_counter() - t0) * 1e3 / a.steps
+        del wsb
+    best = min(res.values())
+    line = {"metric": "images/sec for visual-token reduction (score+select+gather), ragged batch", "value": round(len(tiles) / best * 1e3, 2),
+            "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(best, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "ragged: 64 images, d=%d T=%d, N = 256 x tiles, tiles 4..12 (%d tokens in all, %d runs), keep 1/9"
+                       % (d, base.n_query, sum(nt), runs), "entry_point": "covspec_reduce_ragged"},
+            "ms_per_step_by_streams": {str(k): round(v, 3) for k, v in res.items()},
+            "tokens_per_s": round(sum(nt) / best * 1e3, 1)}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -288,6 +355,7 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads and pipeline (extra keys)")
     ap.add_argument("--verify", action="store_true", help="time the speculative verification step instead (own JSON line)")
     ap.add_argument("--draft", action="store_true", help="time the draft-side margin gate / candidate pass instead (own JSON line)")
+    ap.add_argument("--ragged", action="store_true", help="time covspec_reduce_ragged on a dynamic-resolution batch (own JSON line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 1 GiB device copies and exit (reference reading for the HBM byte counters)")
     a = ap.parse_args()
@@ -311,6 +379,9 @@ def main():
         return
     if a.draft:
         draft_bench(a)
+        return
+    if a.ragged:
+        ragged_bench(a)
         return
     import covspec_inputs as I
     import paper_2605_02218_amd as C

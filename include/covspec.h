@@ -165,6 +165,42 @@ int covspec_reduce_staged(const covspec_params* p, const void* X, const void* hi
                           void* const* stage_events);
 
 /*
+ * Ragged batches: images of different token and keyword counts in one call (not in the paper, whose
+ * Sec. III-A treats one image; dynamic-resolution serving batches such images).  Image b of the batch
+ * gives exactly the result of covspec_reduce on that image alone, with n_tokens[b] and n_query[b] in
+ * place of the template's n_tokens and n_query, k / M / r resolved for that image (from keep_ratio
+ * unless the template fixes them), and, for COVSPEC_LR_RANDOM, the draw of image b.
+ * `p` is the template: batch, n_tokens and n_query are ignored.  `r` and its arrays are HOST memory.
+ * PACKED layouts, image after image, no padding (device pointers):
+ *   X          [sum N_b, d];   Q [sum T_b, d];
+ *   hidden     image b at element offset (K+1) d sum_{a<b} N_a, shape [K+1, N_b, d]   (or NULL)
+ *   idx_out    [sum k_b] int32: positions inside the own image, ascending per image
+ *   tokens_out [sum k_b, d]
+ * covspec_ragged_resolve writes k_b per image to a host array (output offsets are its prefix sums)
+ * and the number of runs.  Consecutive images of equal (N_b, T_b) form a run that is worked off as
+ * one dense batch; run i is enqueued on streams[i mod n_streams] with its own slice of the workspace
+ * (covspec_ragged_workspace_size bytes for that n_streams, 256-byte aligned).  The caller makes the
+ * inputs visible to every stream before the call and synchronises all of them before reading the
+ * outputs; with n_streams == 1 the call behaves like the other entry points.  Streams are the
+ * caller's (default priority); nothing is created, allocated or synchronised inside.  Errors: as
+ * covspec_reduce for the first run whose parameters are invalid or unsupported; runs enqueued before
+ * a failing one stay enqueued.
+ */
+typedef struct covspec_ragged {
+  int32_t n_images;
+  const int32_t* n_tokens;  /* HOST [n_images]: N_b */
+  const int32_t* n_query;   /* HOST [n_images]: T_b */
+} covspec_ragged;
+
+int covspec_ragged_resolve(const covspec_params* p, const covspec_ragged* r, int32_t* keep_k_out,
+                           int32_t* n_runs_out);
+size_t covspec_ragged_workspace_size(const covspec_params* p, const covspec_ragged* r, int32_t n_streams);
+int covspec_reduce_ragged(const covspec_params* p, const covspec_ragged* r, const void* X,
+                          const void* hidden, const void* Q, const void* Wq, const void* Wk,
+                          int32_t* idx_out, void* tokens_out, void* workspace, size_t workspace_bytes,
+                          const covspec_stream_t* streams, int32_t n_streams);
+
+/*
  * Description of the probed launch for these parameters: number of equal launches per call (0 when
  * nothing is probed) and, if non-NULL, its dimensions: the product is [rows x inner] * [inner x cols]
  * per image in fp64 (2*rows*cols*inner flops per image).

@@ -23,7 +23,8 @@ OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
 EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
            "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string",
            "covspec_verify_workspace_size", "covspec_verify", "covspec_draft_fanout", "covspec_draft_workspace_size",
-           "covspec_draft_gate", "covspec_last_error")
+           "covspec_draft_gate", "covspec_last_error", "covspec_ragged_resolve", "covspec_ragged_workspace_size",
+           "covspec_reduce_ragged")
 
 
 class CovspecParams(ctypes.Structure):
@@ -40,6 +41,11 @@ class CovspecVerifyParams(ctypes.Structure):
 class CovspecDraftParams(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("n_seq", "n_draft", "vocab", "dtype", "fanout0")] + [
         ("rho", ctypes.c_float), ("gamma", ctypes.c_float)]
+
+
+class CovspecRagged(ctypes.Structure):
+    _fields_ = [("n_images", ctypes.c_int32), ("n_tokens", ctypes.POINTER(ctypes.c_int32)),
+                ("n_query", ctypes.POINTER(ctypes.c_int32))]
 
 
 class CovspecError(RuntimeError):
@@ -95,6 +101,13 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_draft_gate.argtypes = [dpp] + [vp] * 5 + [vp, ctypes.c_size_t, vp]
     lib.covspec_status_string.restype = ctypes.c_char_p
     lib.covspec_status_string.argtypes = [ctypes.c_int]
+    rp = ctypes.POINTER(CovspecRagged)
+    lib.covspec_ragged_resolve.restype = ctypes.c_int
+    lib.covspec_ragged_resolve.argtypes = [pp, rp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    lib.covspec_ragged_workspace_size.restype = ctypes.c_size_t
+    lib.covspec_ragged_workspace_size.argtypes = [pp, rp, ctypes.c_int32]
+    lib.covspec_reduce_ragged.restype = ctypes.c_int
+    lib.covspec_reduce_ragged.argtypes = [pp, rp] + [vp] * 7 + [vp, ctypes.c_size_t, ctypes.POINTER(vp), ctypes.c_int32]
     lib.covspec_last_error.restype = ctypes.c_char_p
     lib.covspec_last_error.argtypes = []
     _lib = lib
@@ -356,3 +369,64 @@ def draft_gate(p: DraftParams, z_draft, tokens, workspace=None):
     if st != OK:
         raise CovspecError(st, "covspec_draft_gate")
     return margin, gate, cand
+
+
+def _ragged_desc(n_tokens, n_query):
+    n = len(n_tokens)
+    if n != len(n_query):
+        raise ValueError("n_tokens and n_query must have one entry per image")
+    nt = (ctypes.c_int32 * max(n, 1))(*[int(v) for v in n_tokens])
+    nq = (ctypes.c_int32 * max(n, 1))(*[int(v) for v in n_query])
+    desc = CovspecRagged(n, ctypes.cast(nt, ctypes.POINTER(ctypes.c_int32)), ctypes.cast(nq, ctypes.POINTER(ctypes.c_int32)))
+    return desc, (nt, nq)          # the arrays must outlive the descriptor
+
+
+def ragged_resolve(p: Params, n_tokens, n_query):
+    """covspec_ragged_resolve: (k per image, number of runs)."""
+    desc, keep = _ragged_desc(n_tokens, n_query)
+    cs = p.c_struct()
+    ks = (ctypes.c_int32 * max(desc.n_images, 1))()
+    runs = ctypes.c_int32(0)
+    st = load_library().covspec_ragged_resolve(ctypes.byref(cs), ctypes.byref(desc), ks, ctypes.byref(runs))
+    if st != OK:
+        raise CovspecError(st, "covspec_ragged_resolve")
+    return list(ks)[:desc.n_images], runs.value
+
+
+def ragged_workspace_size(p: Params, n_tokens, n_query, n_streams: int = 1) -> int:
+    desc, keep = _ragged_desc(n_tokens, n_query)
+    cs = p.c_struct()
+    return int(load_library().covspec_ragged_workspace_size(ctypes.byref(cs), ctypes.byref(desc), n_streams))
+
+
+def reduce_ragged(p: Params, n_tokens, n_query, X, hidden, Q, Wq, Wk, streams=None, workspace=None, idx_out=None,
+                  tokens_out=None, sync=True):
+    """covspec_reduce_ragged on packed tensors: returns (idx [sum k_b] int32, tokens [sum k_b, d], k per image).
+
+    `streams`: torch.cuda.Stream objects the runs are dealt to (default: the current stream only).  With several
+    streams the inputs must be visible to all of them; they are synchronised before returning unless
+    `sync=False` (then the caller owns `workspace` and synchronises)."""
+    import torch
+    ks, _ = ragged_resolve(p, n_tokens, n_query)
+    desc, keep = _ragged_desc(n_tokens, n_query)
+    cs = p.c_struct()
+    handles = [s.cuda_stream for s in streams] if streams else [_stream()]
+    ns = len(handles)
+    if workspace is None:
+        if streams and not sync:
+            raise ValueError("sync=False with several streams needs a caller-owned workspace")
+        need = int(load_library().covspec_ragged_workspace_size(ctypes.byref(cs), ctypes.byref(desc), ns))
+        workspace = torch.empty(need + 256, dtype=torch.uint8, device=X.device)
+    total = sum(ks)
+    idx = idx_out if idx_out is not None else torch.empty(total, dtype=torch.int32, device=X.device)
+    tok = tokens_out if tokens_out is not None else torch.empty(total, p.d_model, dtype=X.dtype, device=X.device)
+    wp, wb = _ws_args(workspace)
+    harr = (ctypes.c_void_p * ns)(*handles)
+    st = load_library().covspec_reduce_ragged(ctypes.byref(cs), ctypes.byref(desc), _ptr(X), _ptr(hidden), _ptr(Q), _ptr(Wq),
+                                              _ptr(Wk), _ptr(idx), _ptr(tok), wp, wb, harr, ns)
+    if st != OK:
+        raise CovspecError(st, "covspec_reduce_ragged")
+    if streams and sync:
+        for s in streams:
+            s.synchronize()
+    return idx, tok, ks

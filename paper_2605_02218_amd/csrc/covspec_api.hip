@@ -23,6 +23,7 @@ struct Plan {
   int B, N, d, T, H, K, dtype, rel, lr, M, r, k;
   float lambda;
   uint32_t seed;
+  int image0;     // index of the first image in the caller's batch (ragged batches run as several calls)
   int esz;        // bytes per stored element
   int planes;     // bf16: 3 split planes of the folded query matrix, fp32: 1
   int nparts;     // per-token partial sums of |e(v)|^2 written by the projection GEMM
@@ -76,7 +77,7 @@ int make_plan(const covspec_params* p, Plan* pl) {
 
   Plan& q = *pl;
   q.B = p->batch; q.N = p->n_tokens; q.d = p->d_model; q.T = p->n_query; q.H = p->n_heads; q.K = p->n_act_layers;
-  q.dtype = p->dtype; q.rel = p->rel_mode; q.lr = p->lr_mode; q.M = M; q.r = r; q.k = k; q.lambda = p->lambda; q.seed = p->seed;
+  q.dtype = p->dtype; q.rel = p->rel_mode; q.lr = p->lr_mode; q.M = M; q.r = r; q.k = k; q.lambda = p->lambda; q.seed = p->seed; q.image0 = 0;
   q.esz = p->dtype == COVSPEC_BF16 ? 2 : 4;
   q.planes = p->dtype == COVSPEC_BF16 ? 3 : 1;
   q.nparts = p->dtype == COVSPEC_BF16 ? gemm_tiles_n(q.d) : gemm64_tiles_n(q.d);
@@ -297,7 +298,7 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
     const float* rank_by = s_fused;
     if (q.lr == COVSPEC_LR_RANDOM) {
       float* u = at<float>(ws, q.sf);   // the fused-score buffer is free: this mode uses no scores
-      HIPCHK(launch_random_scores(u, q.B, q.N, q.seed, st));
+      HIPCHK(launch_random_scores(u, q.B, q.N, q.seed, q.image0, st));
       rank_by = u;
     } else if (idx_m_out) {
       HIPCHK(launch_select_top(s_fused, q.B, q.N, q.M, nullptr, idx_m_out, st));
@@ -369,6 +370,37 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
 
 }  // namespace
 
+// A ragged batch is worked off as runs of consecutive images of equal shape, each run one dense call.
+struct RaggedRun { int first, count, N, T; long tok0, qry0, kept0; int k; };
+
+// Walks the runs; fn(run, params of the run) returns a status.  keep_k_out (optional) receives k per image.
+template <typename F>
+static int ragged_walk(const covspec_params* p, const covspec_ragged* r, int32_t* keep_k_out, F fn) {
+  if (!p || !r || r->n_images < 1 || !r->n_tokens || !r->n_query) return COVSPEC_INVALID_ARG;
+  long tok0 = 0, qry0 = 0, kept0 = 0;
+  int b = 0;
+  while (b < r->n_images) {
+    int e = b + 1;
+    while (e < r->n_images && r->n_tokens[e] == r->n_tokens[b] && r->n_query[e] == r->n_query[b]) ++e;
+    covspec_params q = *p;
+    q.batch = e - b;
+    q.n_tokens = r->n_tokens[b];
+    q.n_query = r->n_query[b];
+    Plan pl;
+    int st = make_plan(&q, &pl);
+    if (st != COVSPEC_OK) return st;
+    RaggedRun run = {b, e - b, pl.N, pl.T, tok0, qry0, kept0, pl.k};
+    if (keep_k_out)
+      for (int i = b; i < e; ++i) keep_k_out[i] = pl.k;
+    if ((st = fn(run, q, pl)) != COVSPEC_OK) return st;
+    tok0 += (long)run.count * pl.N;
+    qry0 += (long)run.count * pl.T;
+    kept0 += (long)run.count * pl.k;
+    b = e;
+  }
+  return COVSPEC_OK;
+}
+
 extern "C" {
 
 size_t covspec_workspace_size(const covspec_params* p) {
@@ -415,10 +447,11 @@ int covspec_select(const covspec_params* p, const void* X, const float* s_fused,
 
 static int reduce_impl(const covspec_params* p, const void* X, const void* hidden, const void* Q, const void* Wq,
                        const void* Wk, int32_t* idx_out, void* tokens_out, void* workspace, size_t workspace_bytes,
-                       hipStream_t s, StageMarks& marks) {
+                       hipStream_t s, StageMarks& marks, int image0 = 0) {
   Plan pl;
   int st = make_plan(p, &pl);
   if (st != COVSPEC_OK) return st;
+  pl.image0 = image0;
   if (!X || !Q || !idx_out || !tokens_out) return COVSPEC_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != COVSPEC_OK) return st;
   discard_pending_error();
@@ -454,6 +487,49 @@ int covspec_reduce_staged(const covspec_params* p, const void* X, const void* hi
   marks.ev = (hipEvent_t*)stage_events;
   marks.st = (hipStream_t)stream;
   return reduce_impl(p, X, hidden, Q, Wq, Wk, idx_out, tokens_out, workspace, workspace_bytes, (hipStream_t)stream, marks);
+}
+
+int covspec_ragged_resolve(const covspec_params* p, const covspec_ragged* r, int32_t* keep_k_out, int32_t* n_runs_out) {
+  int runs = 0;
+  const int st = ragged_walk(p, r, keep_k_out, [&](const RaggedRun&, const covspec_params&, const Plan&) { ++runs; return (int)COVSPEC_OK; });
+  if (st == COVSPEC_OK && n_runs_out) *n_runs_out = runs;
+  return st;
+}
+
+size_t covspec_ragged_workspace_size(const covspec_params* p, const covspec_ragged* r, int32_t n_streams) {
+  if (n_streams < 1) return 0;
+  size_t most = 0;
+  const int st = ragged_walk(p, r, nullptr, [&](const RaggedRun&, const covspec_params&, const Plan& pl) {
+    if (pl.total > most) most = pl.total;
+    return (int)COVSPEC_OK;
+  });
+  return st == COVSPEC_OK ? align_up(most, 256) * (size_t)n_streams : 0;
+}
+
+int covspec_reduce_ragged(const covspec_params* p, const covspec_ragged* r, const void* X, const void* hidden, const void* Q,
+                          const void* Wq, const void* Wk, int32_t* idx_out, void* tokens_out, void* workspace,
+                          size_t workspace_bytes, const covspec_stream_t* streams, int32_t n_streams) {
+  if (n_streams < 1 || !streams) return COVSPEC_INVALID_ARG;
+  if (!X || !Q || !idx_out || !tokens_out || !workspace || ((uintptr_t)workspace & 255u)) return COVSPEC_INVALID_ARG;
+  const size_t need = covspec_ragged_workspace_size(p, r, n_streams);
+  if (need == 0) {   // report why
+    const int st = ragged_walk(p, r, nullptr, [](const RaggedRun&, const covspec_params&, const Plan&) { return (int)COVSPEC_OK; });
+    return st != COVSPEC_OK ? st : COVSPEC_INVALID_ARG;
+  }
+  if (workspace_bytes < need) return COVSPEC_WORKSPACE_TOO_SMALL;
+  const size_t slice = need / (size_t)n_streams;
+  const size_t esz = p->dtype == COVSPEC_BF16 ? 2 : 4;
+  const size_t d = (size_t)p->d_model, K1 = (size_t)p->n_act_layers + 1;
+  int run_no = 0;
+  return ragged_walk(p, r, nullptr, [&](const RaggedRun& run, const covspec_params& q, const Plan&) {
+    const int slot = run_no++ % n_streams;
+    StageMarks none;
+    const char* Xr = (const char*)X + (size_t)run.tok0 * d * esz;
+    const char* Hr = hidden ? (const char*)hidden + (size_t)run.tok0 * K1 * d * esz : nullptr;
+    const char* Qr = (const char*)Q + (size_t)run.qry0 * d * esz;
+    return reduce_impl(&q, Xr, Hr, Qr, Wq, Wk, idx_out + run.kept0, (char*)tokens_out + (size_t)run.kept0 * d * esz,
+                       (char*)workspace + (size_t)slot * slice, slice, (hipStream_t)streams[slot], none, run.first);
+  });
 }
 
 int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols, int32_t* inner) {

@@ -267,11 +267,12 @@ __global__ void fill_zero_kernel(u32x4_t* p, long n16) {
 
 inline unsigned blocks_for(long n, int per) { return (unsigned)((n + per - 1) / per); }
 
-__global__ __launch_bounds__(256) void random_scores_kernel(float* __restrict__ out, int B, int N, uint32_t seed) {
+__global__ __launch_bounds__(256) void random_scores_kernel(float* __restrict__ out, int B, int N, uint32_t seed, int image0) {
   const long e = (long)blockIdx.x * 256 + threadIdx.x;
   if (e >= (long)B * N) return;
   const unsigned long long b = (unsigned long long)(e / N), i = (unsigned long long)(e - (long)b * N);
-  unsigned long long z = (unsigned long long)seed * 0x9E3779B97F4A7C15ull + ((b << 32) | i) + 0x632BE59BD9B4E019ull;
+  // image0: index of this call's first image in the caller's batch (a ragged batch is worked off in runs)
+  unsigned long long z = (unsigned long long)seed * 0x9E3779B97F4A7C15ull + (((b + (unsigned long long)image0) << 32) | i) + 0x632BE59BD9B4E019ull;
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
   z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
   z ^= z >> 31;
@@ -358,10 +359,10 @@ hipError_t launch_gather_rows(const void* X, const int32_t* idx, void* out, int 
   return hipGetLastError();
 }
 
-hipError_t launch_random_scores(float* out, int B, int N, uint32_t seed, hipStream_t stream) {
+hipError_t launch_random_scores(float* out, int B, int N, uint32_t seed, int image0, hipStream_t stream) {
   const long total = (long)B * N;
   if (total <= 0) return hipSuccess;
-  hipLaunchKernelGGL(random_scores_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, out, B, N, seed);
+  hipLaunchKernelGGL(random_scores_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, out, B, N, seed, image0);
   return hipGetLastError();
 }
 

@@ -98,7 +98,7 @@ hipError_t launch_fill_int(int* p, int n, int value, hipStream_t stream);
 
 // Reproducible uniform scores for the random-selection ablation: out[b, i] = top 24 bits of
 // mix64(seed * 0x9E3779B97F4A7C15 + (b << 32 | i) + 0x632BE59BD9B4E019) times 2^-24 (mix64 = SplitMix64 output function).
-hipError_t launch_random_scores(float* out, int B, int N, uint32_t seed, hipStream_t stream);
+hipError_t launch_random_scores(float* out, int B, int N, uint32_t seed, int image0, hipStream_t stream);
 
 // ---------------------------------------------------------------- select.hip
 // Per image: positions of the m largest of scores[b, 0..n) (ties -> lower position), ascending.

@@ -153,3 +153,28 @@ def test_draft_params_validation_and_fanout_match_the_oracle_formula():
     assert lib.covspec_draft_gate(ctypes.byref(cs), fake + 4, fake, fake, fake, fake, fake, 1 << 40, None) == Bd.INVALID_ARG
     cs0 = C.DraftParams(4, 8, 8192, fanout0=0).c_struct()     # margin only: no candidate buffer needed
     assert lib.covspec_draft_gate(ctypes.byref(cs0), fake, fake, fake, fake, None, fake, 16, None) == Bd.WORKSPACE_TOO_SMALL
+
+
+def test_ragged_resolution_runs_and_validation():
+    p = _p(keep_k=0, preselect_m=0, rank_r=0, keep_ratio=0.25, d_model=256, n_heads=4)
+    ks, runs = C.ragged_resolve(p, [256, 256, 512, 256, 768, 768, 768], [4, 4, 4, 9, 9, 9, 8])
+    assert ks == [64, 64, 128, 64, 192, 192, 192] and runs == 5          # a run ends when N or T changes
+    assert C.ragged_resolve(p, [300], [1]) == ([75], 1)
+    for bad in ([256, 0], [256, 20000]):
+        with pytest.raises(C.CovspecError):
+            C.ragged_resolve(p, bad, [4, 4])
+    with pytest.raises(ValueError):
+        C.ragged_resolve(p, [256], [4, 4])
+    lib = C.load_library()
+    desc, keep = Bd._ragged_desc([256, 512], [4, 4])
+    cs = p.c_struct()
+    one = lib.covspec_ragged_workspace_size(ctypes.byref(cs), ctypes.byref(desc), 1)
+    assert one > 0 and lib.covspec_ragged_workspace_size(ctypes.byref(cs), ctypes.byref(desc), 3) == 3 * one
+    assert lib.covspec_ragged_workspace_size(ctypes.byref(cs), ctypes.byref(desc), 0) == 0
+    fake = 4096
+    streams = (ctypes.c_void_p * 1)(None)
+    call = lambda *a: lib.covspec_reduce_ragged(ctypes.byref(cs), ctypes.byref(desc), *a)
+    assert call(fake, None, fake, None, None, fake, fake, fake, 16, streams, 1) == Bd.WORKSPACE_TOO_SMALL
+    assert call(None, None, fake, None, None, fake, fake, fake, 1 << 40, streams, 1) == Bd.INVALID_ARG
+    assert call(fake, None, fake, None, None, fake, fake, fake, 1 << 40, None, 1) == Bd.INVALID_ARG
+    assert call(fake, None, fake, None, None, fake, fake, fake, 1 << 40, streams, 0) == Bd.INVALID_ARG
