@@ -283,7 +283,7 @@ def ragged_bench(a):
     64 images of workload 5's width and structure (d = 4096, 128 keywords, bf16, keep ratio 1/9) whose token counts
     are 256 per tile with 4..12 tiles (the tile grids of a dynamic-resolution vision encoder), sorted by size so
     that equal sizes form runs.  A step is one call over the packed batch; images/sec with the runs on one stream
-    and dealt to four.
+    and dealt to two and to five.
     """
     from concurrent.futures import ThreadPoolExecutor
     from dataclasses import replace
@@ -316,7 +316,7 @@ def ragged_bench(a):
     idx = torch.empty(sum(ks), dtype=torch.int32, device="cuda")
     tok = torch.empty(sum(ks), d, dtype=torch.bfloat16, device="cuda")
     res = {}
-    for ns in (1, 4):
+    for ns in (1, 2, 5):
         streams = [torch.cuda.Stream() for _ in range(ns)]
         wsb = torch.empty(C.ragged_workspace_size(p, nt, nq, ns) + 256, dtype=torch.uint8, device="cuda")
         torch.cuda.synchronize()
