@@ -41,6 +41,36 @@ __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
   om[i] = (c < n) ? ((h & 1u) ? 1.0 : -1.0) : 0.0;
 }
 
+// value of `v` in lane `l` (compile-time lane), uniform across the wave
+template <typename = void>
+__device__ __forceinline__ double lane_value(double v, int l) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), l), hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+  return __hiloint2double(hi, lo);
+}
+
+// Factors the 64 x 64 block `a` (LDS, pitch NBP, lower triangle) in one wave: lane i holds row i.  The factor
+// goes to `fac` (lower triangle, zeros above).  Pivots are floored at `floor_`.  Not inlined, so that the 64
+// row registers do not compete with the caller's.
+__device__ __noinline__ void potrf_wave(const double* a, double* fac, double floor_) {
+  const int lane = threadIdx.x & 63;
+  double row[NB];
+#pragma unroll
+  for (int k = 0; k < NB; ++k) row[k] = a[lane * NBP + k];
+#pragma unroll
+  for (int k = 0; k < NB; ++k) {
+    const double akk = fmax(lane_value(row[k], k), floor_);
+    double rs = __builtin_amdgcn_rsq(akk);
+    rs = rs * fma(-0.5 * akk, rs * rs, 1.5);
+    rs = rs * fma(-0.5 * akk, rs * rs, 1.5);
+    const double lk = (lane == k) ? akk * rs : row[k] * rs;
+    row[k] = lk;
+#pragma unroll
+    for (int j = k + 1; j < NB; ++j) row[j] = fma(-lk, lane_value(lk, j), row[j]);
+  }
+#pragma unroll
+  for (int k = 0; k < NB; ++k) fac[lane * NBP + k] = (k <= lane) ? row[k] : 0.0;
+}
+
 // Cholesky factorisation S[b] = L L^T (P x P, pitch P, P % 64 == 0; only the lower triangle is read), one
 // 512-thread workgroup per image, right-looking over 64-wide panels:
 //   diagonal block: factored in LDS, then inverted in LDS; the inverse goes to Dinv[b][J] (64 x 64);
@@ -74,43 +104,13 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
       for (int i = 0; i < NB; ++i) tr += a[i * NBP + i];   // same value in every thread
       floor_ = 1e-300 + 1e-28 * tr;
     }
-    // ---- factor the diagonal block: right-looking, one barrier per column.  The block is updated unscaled
-    //      (a_ij -= a_ik a_jk / a_kk), the scaled column goes to a second buffer, so a step only reads column
-    //      k and writes the columns behind it.  Reciprocals: hardware estimate + two Newton steps.
-    for (int k = 0; k < NB; ++k) {
-      const double akk = fmax(a[k * NBP + k], floor_);
-      if (tid < NB) {
-        double rs = __builtin_amdgcn_rsq(akk);
-        rs = rs * fma(-0.5 * akk, rs * rs, 1.5);
-        rs = rs * fma(-0.5 * akk, rs * rs, 1.5);
-        fac[tid * NBP + k] = (tid < k) ? 0.0 : ((tid == k) ? akk * rs : a[tid * NBP + k] * rs);
-      }
-      const int i = k + 1 + (tid >> 3);
-      if (i < NB) {
-        double rk = __builtin_amdgcn_rcp(akk);
-        rk = rk * fma(-akk, rk, 2.0);
-        rk = rk * fma(-akk, rk, 2.0);
-        const double ci = a[i * NBP + k] * rk;
-        // loads, arithmetic, stores in three batches (the compiler cannot tell that the elements are distinct)
-        double cj[8], v[8];
-        const int jb = k + 1 + (tid & 7);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int j = jb + 8 * u;
-          const bool on = j <= i;
-          cj[u] = on ? a[j * NBP + k] : 0.0;
-          v[u] = on ? a[i * NBP + j] : 0.0;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = fma(-ci, cj[u], v[u]);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int j = jb + 8 * u;
-          if (j <= i) a[i * NBP + j] = v[u];
-        }
-      }
-      __syncthreads();
-    }
+    // ---- factor the diagonal block in ONE wave, row i of the block in the registers of lane i: no barrier and
+    //      no LDS traffic per column (with the whole workgroup a column cost a barrier and a round trip through
+    //      LDS, and the factorisation is a chain of 64 dependent columns).  Column k: pivot from lane k, scaled
+    //      column l_ik = a_ik / sqrt(a_kk), then a_ij -= l_ik l_jk with l_jk read from lane j.  Lanes also carry
+    //      the (unused) entries above the diagonal; they stay finite and never feed an entry below it.
+    if (w == 0) potrf_wave(a, fac, floor_);
+    __syncthreads();
     if (tid == 0)
       for (int k = 0; k < NB; ++k) { const double d = fac[k * NBP + k]; dmin = fmin(dmin, d); dmax = fmax(dmax, d); }
     // ---- inverse of the factor into `a`, by doubling: with L = [A 0; C D], inv(L) = [inv(A) 0; -inv(D) C inv(A) inv(D)].
