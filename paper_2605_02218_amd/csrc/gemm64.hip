@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
   const int tm = pidx / tiles_n, tn = pidx - tm * tiles_n;
   const int row0 = tm * TM, col0 = tn * TN;
   const int bo = bidx / g.batch_inner, bi = bidx - bo * g.batch_inner;
-  if (g.skip && g.skip[bo] == g.skip_if) return;          // uniform per workgroup
+  if (g.skip && g.skip[bo] > g.skip_if) return;           // uniform per workgroup
   if (g.lower_only && col0 > row0 + TM - 1) return;       // tile entirely above the diagonal
   const TA* __restrict__ A = (const TA*)g.A + (long)bo * g.strideA + (long)bi * g.strideA2;
   const TB* __restrict__ B = (const TB*)g.B + (long)bo * g.strideB + (long)bi * g.strideB2;

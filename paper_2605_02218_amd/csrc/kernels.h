@@ -35,7 +35,7 @@ struct GemmArgs {
   // fp64 kernel only:
   bool lower_only = false;                     // tiles entirely above the diagonal of C are not computed
   bool transB = false;                         // B is stored [K][N] (row pitch ldb), i.e. C = A * B
-  const int* skip = nullptr;                   // per outer batch: the work is skipped when skip[b] == skip_if
+  const int* skip = nullptr;                   // per outer batch: the work is skipped while skip[b] > skip_if
   int skip_if = 1;
 };
 int gemm_tiles_n(int N);

@@ -29,8 +29,12 @@ constexpr int NBP = NB + 1;   // LDS pitch
 // 1e-9 perturbs an energy by at most 1e-9 / (relative gap at r) relative, the same order; converged blocks
 // sit at 1e-11..1e-13, unconverged ones orders above.
 constexpr double kRitzTol = 1e-9;
-constexpr double kSkipCond = 1e3;   // see chol_kernel
-constexpr size_t kCholLds = (size_t)(2 * NB * NBP) * sizeof(double);
+// see the end of chol_kernel
+constexpr double kPivotNear = 0.25;   // smallest scaled pivot above this: rows nearly orthogonal, blocks of three steps
+constexpr double kPivotFar = 1e-3;    // above this: blocks of two steps
+constexpr double kGradeDigits = 14.0; // decimal digits a block's grading (lambda_1 / lambda_P)^steps may use up
+constexpr int kMaxBlockSteps = 3;
+constexpr size_t kCholLdsFixed = (size_t)(2 * NB * NBP) * sizeof(double);   // plus P doubles: the diagonal of S
 
 __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -80,17 +84,20 @@ __device__ __noinline__ void potrf_wave(const double* a, double* fac, double flo
 // Pivots are floored at 1e-28 * trace(first block) so that a numerically rank-deficient block cannot
 // produce NaNs (the residual check afterwards decides whether the result is usable).
 // Dynamic LDS: 2 * 64 * 65 doubles.
-__global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, int* skip_at, int step, int may_skip_next) {
+__global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, int* skip_until, int* last_orth, int step,
+                                                   int last_free_step) {
   extern __shared__ double lds[];
   double* a = lds;                  // [64][65] diagonal block, later the inverse of its factor
   double* fac = lds + NB * NBP;     // [64][65] the factor (lower triangle) and scratch (upper triangle)
+  double* diag0 = lds + 2 * NB * NBP;   // [P] the diagonal of S before any update: squared row lengths
   const int b = blockIdx.x;
-  if (skip_at && skip_at[b] == step) return;   // this image does not orthonormalise at this step
+  if (skip_until && skip_until[b] > step) return;   // this image does not orthonormalise at this step
   double* Sb = S + (long)b * P * P;
-  double dmin = 1e300, dmax = 0.0;             // extremes of the factor's diagonal (thread 0)
+  double dmin = 1e300, dmax = 0.0, pmin = 1.0;   // extremes of the factor's diagonal, smallest scaled pivot (thread 0)
   const int nblk = P / NB;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i16 = lane & 15, kq = lane >> 4;
   double floor_ = 0.0;
+  for (int k = tid; k < P; k += 512) diag0[k] = Sb[(long)k * P + k];
 
   for (int J = 0; J < nblk; ++J) {
     const int j0 = J * NB;
@@ -112,7 +119,13 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
     if (w == 0) potrf_wave(a, fac, floor_);
     __syncthreads();
     if (tid == 0)
-      for (int k = 0; k < NB; ++k) { const double d = fac[k * NBP + k]; dmin = fmin(dmin, d); dmax = fmax(dmax, d); }
+      for (int k = 0; k < NB; ++k) {
+        const double d = fac[k * NBP + k];
+        dmin = fmin(dmin, d);
+        dmax = fmax(dmax, d);
+        const double s0 = diag0[j0 + k];
+        if (s0 > 0.0) pmin = fmin(pmin, d * d / s0);
+      }
     // ---- inverse of the factor into `a`, by doubling: with L = [A 0; C D], inv(L) = [inv(A) 0; -inv(D) C inv(A) inv(D)].
     //      Level s joins the inverses of the s x s diagonal blocks pairwise; the intermediate C inv(A) is parked,
     //      transposed, in the unused upper triangle of `fac`.
@@ -221,11 +234,28 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
     }
     __syncthreads();
   }
-  // The diagonal of L spans about the condition number of the block just factored (rows = Q G with Q
-  // orthonormal, so about lambda_1 / lambda_P).  When it is small, the NEXT step may multiply by G again without
-  // orthonormalising first: the block then has the square of this condition number, and Cholesky-QR stays
-  // accurate up to ~1e7.  skip_at[b] = the step at which this image skips, or -1.
-  if (tid == 0 && skip_at) skip_at[b] = (may_skip_next && dmin > 0.0 && dmax < kSkipCond * dmin) ? step + 1 : -1;
+  // How many steps (products with G) the image may take before it orthonormalises again.  Two things limit a
+  // block of m steps.  (1) Cholesky-QR needs the SCALED Gram matrix (unit diagonal) to be well conditioned; the raw
+  // grading lambda_1 / lambda_P of the rows is harmless.  The scaled pivots L_kk^2 / S_kk (squared sine of the
+  // angle between row k and the rows before it) say how close to orthogonal the rows were: the iteration orders
+  // the rows like the eigenvectors, and once it has, they stay nearly orthogonal over several steps.  (2) Within a
+  // row the wanted direction must not drown in rounding noise along the dominant one: (lambda_1 / lambda_P)^m has
+  // to stay well inside the 16 digits; the diagonal of L spans that ratio for the steps of the block just closed.
+  if (tid == 0 && skip_until) {
+    int m = 1;
+    if (step >= 1 && dmin > 0.0) {
+      const int closed = step - last_orth[b];                       // steps in the block just factored (>= 1)
+      const double digits_per_step = log10(fmax(dmax / dmin, 10.0)) / (double)(closed < 1 ? 1 : closed);
+      const int by_grade = (int)(kGradeDigits / digits_per_step);
+      const int by_pivot = pmin > kPivotNear ? kMaxBlockSteps : (pmin > kPivotFar ? 2 : 1);
+      m = by_pivot < by_grade ? by_pivot : by_grade;
+      if (m < 1) m = 1;
+    }
+    int next = step + m;                      // the next step that orthonormalises
+    if (next > last_free_step) next = last_free_step;     // the final step always does
+    skip_until[b] = next;
+    last_orth[b] = step;
+  }
 }
 
 // Yt[b] <- L^-1 Yt[b] (P x nP, pitch nP) by blocked forward substitution with the factor chol_kernel left
@@ -235,9 +265,9 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
 // T comes out of the MFMA in exactly the layout its B operand wants (lane = column, register = k), so the
 // second product takes the accumulator registers as they are.
 __global__ __launch_bounds__(256) void trsm_kernel(double* Yt, const double* __restrict__ S, const double* __restrict__ Dinv,
-                                                    int P, int nP, int wg_per_image, const int* __restrict__ skip_at, int step) {
+                                                    int P, int nP, int wg_per_image, const int* __restrict__ last_orth, int step) {
   const int b = blockIdx.x / wg_per_image, cw = blockIdx.x - b * wg_per_image;
-  if (skip_at && skip_at[b] == step) return;
+  if (last_orth && last_orth[b] != step) return;    // the factorisation of this step did not run for this image
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, i16 = lane & 15, kq = lane >> 4;
   const int col = cw * 64 + w * 16 + i16;    // nP % 64 == 0, so every column exists
   const int nblk = P / NB;
@@ -346,7 +376,8 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   {
     static bool raised = false;
     if (!raised) {
-      if ((e0 = hipFuncSetAttribute((const void*)chol_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kCholLds)) != hipSuccess)
+      if ((e0 = hipFuncSetAttribute((const void*)chol_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(kCholLdsFixed + 4096 * sizeof(double)))) != hipSuccess)
         return e0;
       raised = true;
     }
@@ -360,7 +391,8 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   double* H = S + (size_t)B * P * P;
   double* D = H + (size_t)B * P * P;
   double* lam = D + (size_t)B * P * NB;
-  int* skip_at = (int*)(((uintptr_t)(lam + (size_t)B * P) + 255) & ~(uintptr_t)255);   // [B]
+  int* skip_until = (int*)(((uintptr_t)(lam + (size_t)B * P) + 255) & ~(uintptr_t)255);   // [B] next step that orthonormalises
+  int* last_orth = skip_until + B;                                                          // [B] step of the last one
   const int nblk = P / NB;
   hipError_t e;
 
@@ -371,20 +403,21 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     g.epilogue = EPI_STORE_F64;
     return launch_gemm64_nt(g, true, true, st);
   };
-  // X <- L^-1 X with X X^T = L L^T.  step >= 0: images with skip_at[b] == step leave X alone, and the factorisation
-  // may schedule the skip of step + 1 (may_skip_next); step < 0: unconditional.
-  auto cholqr = [&](double* X, int step, bool may_skip_next) -> hipError_t {
+  // X <- L^-1 X with X X^T = L L^T.  step >= 0: images with skip_until[b] > step leave X alone, and the factorisation
+  // decides how many steps the image takes before the next one (never beyond last_free_step); step < 0: unconditional.
+  const size_t chol_lds = kCholLdsFixed + (size_t)P * sizeof(double);
+  auto cholqr = [&](double* X, int step, int last_free_step) -> hipError_t {
     GemmArgs g;
     g.A = X; g.B = X; g.C = S; g.M = P; g.N = P; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = P;
     g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)P * nP; g.strideC = (long)P * P;
     g.epilogue = EPI_STORE_F64;
     g.lower_only = true;
-    if (step >= 0) { g.skip = skip_at; g.skip_if = step; }
+    if (step >= 0) { g.skip = skip_until; g.skip_if = step; }
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
-    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), kCholLds, st, S, D, P, step >= 0 ? skip_at : (int*)nullptr, step,
-                       may_skip_next ? 1 : 0);
+    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), chol_lds, st, S, D, P, step >= 0 ? skip_until : (int*)nullptr,
+                       last_orth, step, last_free_step);
     hipLaunchKernelGGL(trsm_kernel, dim3((unsigned)(B * (nP / NB))), dim3(256), 0, st, X, (const double*)S, (const double*)D, P, nP,
-                       nP / NB, step >= 0 ? (const int*)skip_at : (const int*)nullptr, step);
+                       nP / NB, step >= 0 ? (const int*)last_orth : (const int*)nullptr, step);
     return hipGetLastError();
   };
 
@@ -401,15 +434,15 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   if (probe_end && (e = hipEventRecord(probe_end, st)) != hipSuccess) return e;
   double* cur = Yt;
   double* oth = Zt;
-  if ((e = launch_fill_int(skip_at, B, -1, st)) != hipSuccess) return e;
+  if ((e = launch_fill_int(skip_until, 2 * B, -1, st)) != hipSuccess) return e;
   for (int it = 0; it < iters; ++it) {
     if (it + 1 < iters) {
-      // the start block is not (orthonormal) x G, so its factor says nothing about the next step: no skip after it = 0;
-      // the last step always orthonormalises
-      if ((e = cholqr(cur, it, it >= 1 && it + 2 < iters)) != hipSuccess) return e;
+      // the start block is not (orthonormal) x G, so its factor says nothing about the next step (the kernel takes
+      // one step after it = 0); the last step always orthonormalises
+      if ((e = cholqr(cur, it, iters - 1)) != hipSuccess) return e;
     } else {
-      if ((e = cholqr(cur, -1, false)) != hipSuccess) return e;
-      if ((e = cholqr(cur, -1, false)) != hipSuccess) return e;          // second pass: orthonormal to rounding
+      if ((e = cholqr(cur, -1, 0)) != hipSuccess) return e;
+      if ((e = cholqr(cur, -1, 0)) != hipSuccess) return e;              // second pass: orthonormal to rounding
     }
     if ((e = gemm_yt_g(cur, oth)) != hipSuccess) return e;               // oth = Q^T G
     double* t = cur; cur = oth; oth = t;
