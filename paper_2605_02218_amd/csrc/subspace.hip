@@ -34,6 +34,7 @@ constexpr double kPivotNear = 0.25;   // smallest scaled pivot above this: rows 
 constexpr double kPivotFar = 1e-3;    // above this: blocks of two steps
 constexpr double kGradeDigits = 14.0; // decimal digits a block's grading (lambda_1 / lambda_P)^steps may use up
 constexpr int kMaxBlockSteps = 3;
+constexpr double kPivotOnePass = 0.01; // final step: above this one Cholesky-QR pass leaves the rows orthonormal to ~1e-14
 constexpr size_t kCholLdsFixed = (size_t)(2 * NB * NBP) * sizeof(double);   // plus P doubles: the diagonal of S
 
 __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
@@ -253,6 +254,9 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
     }
     int next = step + m;                      // the next step that orthonormalises
     if (next > last_free_step) next = last_free_step;     // the final step always does
+    // The final step is followed by a second pass (step + 1) that makes the rows orthonormal to rounding; the
+    // error of one pass is about 1e-16 times the scaled condition number, so with large pivots it is not needed.
+    if (step == last_free_step) next = pmin > kPivotOnePass ? step + 2 : step + 1;
     skip_until[b] = next;
     last_orth[b] = step;
   }
@@ -441,8 +445,8 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
       // one step after it = 0); the last step always orthonormalises
       if ((e = cholqr(cur, it, iters - 1)) != hipSuccess) return e;
     } else {
-      if ((e = cholqr(cur, -1, 0)) != hipSuccess) return e;
-      if ((e = cholqr(cur, -1, 0)) != hipSuccess) return e;              // second pass: orthonormal to rounding
+      if ((e = cholqr(cur, it, iters - 1)) != hipSuccess) return e;      // runs for every image (no block reaches past it)
+      if ((e = cholqr(cur, it + 1, iters - 1)) != hipSuccess) return e;  // second pass, where the first one asks for it
     }
     if ((e = gemm_yt_g(cur, oth)) != hipSuccess) return e;               // oth = Q^T G
     double* t = cur; cur = oth; oth = t;
