@@ -15,7 +15,8 @@ namespace {
 constexpr int kMaxTokens = 16384;
 constexpr int kMaxPreselect = 4096;
 constexpr int kMaxActLayers = 8;
-constexpr int kSubspaceIters = 14;
+constexpr int kSubspaceIters = 12;       // steps before the first residual check (the workloads pass it with a factor >= 10 to spare)
+constexpr int kSubspaceMoreIters = 4;    // further steps for the images that fail it, before the full solve
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -339,7 +340,7 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
       // the full Jacobi solve (which leaves the others untouched)
       int* ok = at<int>(ws, q.ok);
       const double* Ut = nullptr;
-      HIPCHK(launch_subspace_eigen(A, q.B, q.M, q.nP, q.r, q.P, kSubspaceIters, at<void>(ws, q.sub), at<void>(ws, q.ctl),
+      HIPCHK(launch_subspace_eigen(A, q.B, q.M, q.nP, q.r, q.P, kSubspaceIters, kSubspaceMoreIters, at<void>(ws, q.sub), at<void>(ws, q.ctl),
                                    at<double>(ws, q.lam), ok, &Ut, marks.ev ? marks.ev[COVSPEC_PROBE_BEGIN] : nullptr,
                                    marks.ev ? marks.ev[COVSPEC_PROBE_END] : nullptr, st));
       probed = true;

@@ -132,7 +132,7 @@ size_t subspace_workspace_bytes(int B, int n, int nP, int P);
 // probe_begin / probe_end (optional): recorded around the first of the subspace_product_launches(iters)
 // equal launches of the product Yt G (P x nP x nP per image).
 int subspace_product_launches(int iters);
-hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, void* ws, void* jacobi_ctl,
+hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, int more_iters, void* ws, void* jacobi_ctl,
                                  double* jacobi_len2, int* ok, const double** ut, hipEvent_t probe_begin, hipEvent_t probe_end,
                                  hipStream_t stream);
 

@@ -316,16 +316,25 @@ __global__ __launch_bounds__(256) void trsm_kernel(double* Yt, const double* __r
   }
 }
 
+// skip_until[b] = ok[b] ? INT_MAX : -1 (images that passed take no further part), last_orth[b] = -1
+__global__ void mask_passed_kernel(const int* __restrict__ ok, int* __restrict__ skip_until, int* __restrict__ last_orth, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  skip_until[b] = ok[b] ? 0x7fffffff : -1;
+  last_orth[b] = -1;
+}
+
 // Residual check of the r dominant Ritz pairs.  Ut rows are theta_k u_k^T, Rt = Ut G.  ok[b] = 1 when
 // |Rt_k - theta_k Ut_k| <= tol * theta_k^2 for each of them (theta_k = |Ut_k|, so this is the relative
 // residual |G u - theta u| / theta).
 __global__ __launch_bounds__(256) void ritz_check_kernel(const double* __restrict__ Ut, const double* __restrict__ Rt,
                                                           const double* __restrict__ lam, int P, int n, int nP, int r,
-                                                          double tol, int* __restrict__ ok) {
+                                                          double tol, int* ok, int only_failed) {
   __shared__ double slam[4096];
   __shared__ unsigned char sel[4096];
   __shared__ int bad;
   const int b = blockIdx.x, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (only_failed && ok[b]) return;      // passed an earlier check; its rows were not touched since (uniform)
   const double* lb = lam + (long)b * P;
   for (int k = threadIdx.x; k < P; k += 256) slam[k] = lb[k];
   if (threadIdx.x == 0) bad = 0;
@@ -372,11 +381,12 @@ size_t subspace_workspace_bytes(int B, int n, int nP, int P) {
 // k of (*ut)[b] (P rows, pitch nP, inside ws) are theta_k u_k^T with the r longest rows converged.
 int subspace_product_launches(int iters) { return iters + 2; }   // start block, one per iteration, residuals
 
-hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, void* ws_, void* jacobi_ctl,
+hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, int more_iters, void* ws_, void* jacobi_ctl,
                                  double* jacobi_len2, int* ok, const double** ut, hipEvent_t probe_begin, hipEvent_t probe_end,
                                  hipStream_t st) {
   hipError_t e0;
   if (P <= 0 || P % NB != 0 || P > n || P > 4096 || nP % NB != 0) return hipErrorInvalidValue;
+  if (iters < 2 || more_iters < 2 || (iters & 1) || (more_iters & 1)) return hipErrorInvalidValue;   // the two blocks swap roles per step
   {
     static bool raised = false;
     if (!raised) {
@@ -400,15 +410,22 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   const int nblk = P / NB;
   hipError_t e;
 
+  // Second pass: images that passed the first check take no further part; the kernels see them as skip_until ==
+  // INT_MAX (never reached by a step counter), which is what `masked` switches on for the plain products.
+  bool masked = false;
+  auto mask = [&](GemmArgs& g) {
+    if (masked) { g.skip = skip_until; g.skip_if = 0x7ffffffe; }
+  };
   auto gemm_yt_g = [&](const double* X, double* out) {   // out = X G  (P x nP)
     GemmArgs g;
     g.A = X; g.B = G; g.C = out; g.M = P; g.N = nP; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = nP;
     g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)nP * nP; g.strideC = (long)P * nP;
     g.epilogue = EPI_STORE_F64;
+    mask(g);
     return launch_gemm64_nt(g, true, true, st);
   };
-  // X <- L^-1 X with X X^T = L L^T.  step >= 0: images with skip_until[b] > step leave X alone, and the factorisation
-  // decides how many steps the image takes before the next one (never beyond last_free_step); step < 0: unconditional.
+  // X <- L^-1 X with X X^T = L L^T.  Images with skip_until[b] > step leave X alone, and the factorisation decides
+  // how many steps the image takes before the next one (never beyond last_free_step).
   const size_t chol_lds = kCholLdsFixed + (size_t)P * sizeof(double);
   auto cholqr = [&](double* X, int step, int last_free_step) -> hipError_t {
     GemmArgs g;
@@ -416,12 +433,50 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)P * nP; g.strideC = (long)P * P;
     g.epilogue = EPI_STORE_F64;
     g.lower_only = true;
-    if (step >= 0) { g.skip = skip_until; g.skip_if = step; }
+    g.skip = skip_until;
+    g.skip_if = step;
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
-    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), chol_lds, st, S, D, P, step >= 0 ? skip_until : (int*)nullptr,
-                       last_orth, step, last_free_step);
+    hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), chol_lds, st, S, D, P, skip_until, last_orth, step, last_free_step);
     hipLaunchKernelGGL(trsm_kernel, dim3((unsigned)(B * (nP / NB))), dim3(256), 0, st, X, (const double*)S, (const double*)D, P, nP,
-                       nP / NB, step >= 0 ? (const int*)last_orth : (const int*)nullptr, step);
+                       nP / NB, (const int*)last_orth, step);
+    return hipGetLastError();
+  };
+  double* cur = Yt;
+  double* oth = Zt;
+  // `steps` products from the block in `cur` (each preceded by an orthonormalisation where the image's schedule
+  // asks for one), then Rayleigh-Ritz and the residual check.  steps is even, so `cur` is the same buffer after it.
+  auto pass = [&](int steps) -> hipError_t {
+    for (int it = 0; it < steps; ++it) {
+      // the block of step 0 is not (orthonormal) x G, so its factor says nothing about the next step (the kernel
+      // takes one step after it); the last step always orthonormalises, twice where its pivots ask for it
+      if ((e = cholqr(cur, it, steps - 1)) != hipSuccess) return e;
+      if (it + 1 == steps && (e = cholqr(cur, it + 1, steps - 1)) != hipSuccess) return e;
+      if ((e = gemm_yt_g(cur, oth)) != hipSuccess) return e;               // oth = Q^T G
+      double* t = cur; cur = oth; oth = t;
+    }
+    // now oth = Q^T (orthonormal rows), cur = Q^T G.  Rayleigh-Ritz: H = (Q^T G) Q
+    {
+      GemmArgs g;
+      g.A = cur; g.B = oth; g.C = H; g.M = P; g.N = P; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = P;
+      g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)P * nP; g.strideC = (long)P * P;
+      g.epilogue = EPI_STORE_F64;
+      mask(g);
+      if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
+    }
+    if ((e = launch_jacobi_eigen(H, B, P, P, r, jacobi_ctl, jacobi_len2, masked ? (const int*)ok : nullptr, st)) != hipSuccess) return e;
+    // rows of H are now theta_k w_k^T; Ut = H Q^T has rows theta_k u_k^T
+    {
+      GemmArgs g;
+      g.A = H; g.B = oth; g.C = cur; g.M = P; g.N = nP; g.K = P; g.lda = P; g.ldb = nP; g.ldc = nP; g.transB = true;
+      g.batch = B; g.strideA = (long)P * P; g.strideB = (long)P * nP; g.strideC = (long)P * nP;
+      g.epilogue = EPI_STORE_F64;
+      mask(g);
+      if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
+    }
+    // residuals: Rt = Ut G
+    if ((e = gemm_yt_g(cur, oth)) != hipSuccess) return e;
+    if ((e = launch_row_lengths(cur, B, P, nP, (long)P * nP, lam, st)) != hipSuccess) return e;
+    hipLaunchKernelGGL(ritz_check_kernel, dim3(B), dim3(256), 0, st, cur, oth, lam, P, n, nP, r, kRitzTol, ok, masked ? 1 : 0);
     return hipGetLastError();
   };
 
@@ -436,42 +491,13 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
   }
   if (probe_end && (e = hipEventRecord(probe_end, st)) != hipSuccess) return e;
-  double* cur = Yt;
-  double* oth = Zt;
   if ((e = launch_fill_int(skip_until, 2 * B, -1, st)) != hipSuccess) return e;
-  for (int it = 0; it < iters; ++it) {
-    if (it + 1 < iters) {
-      // the start block is not (orthonormal) x G, so its factor says nothing about the next step (the kernel takes
-      // one step after it = 0); the last step always orthonormalises
-      if ((e = cholqr(cur, it, iters - 1)) != hipSuccess) return e;
-    } else {
-      if ((e = cholqr(cur, it, iters - 1)) != hipSuccess) return e;      // runs for every image (no block reaches past it)
-      if ((e = cholqr(cur, it + 1, iters - 1)) != hipSuccess) return e;  // second pass, where the first one asks for it
-    }
-    if ((e = gemm_yt_g(cur, oth)) != hipSuccess) return e;               // oth = Q^T G
-    double* t = cur; cur = oth; oth = t;
-  }
-  // now oth = Q^T (orthonormal rows), cur = Q^T G.  Rayleigh-Ritz: H = (Q^T G) Q
-  {
-    GemmArgs g;
-    g.A = cur; g.B = oth; g.C = H; g.M = P; g.N = P; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = P;
-    g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)P * nP; g.strideC = (long)P * P;
-    g.epilogue = EPI_STORE_F64;
-    if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
-  }
-  if ((e = launch_jacobi_eigen(H, B, P, P, r, jacobi_ctl, jacobi_len2, nullptr, st)) != hipSuccess) return e;
-  // rows of H are now theta_k w_k^T; Ut = H Q^T has rows theta_k u_k^T
-  {
-    GemmArgs g;
-    g.A = H; g.B = oth; g.C = cur; g.M = P; g.N = nP; g.K = P; g.lda = P; g.ldb = nP; g.ldc = nP; g.transB = true;
-    g.batch = B; g.strideA = (long)P * P; g.strideB = (long)P * nP; g.strideC = (long)P * nP;
-    g.epilogue = EPI_STORE_F64;
-    if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
-  }
-  // residuals: Rt = Ut G
-  if ((e = gemm_yt_g(cur, oth)) != hipSuccess) return e;
-  if ((e = launch_row_lengths(cur, B, P, nP, (long)P * nP, lam, st)) != hipSuccess) return e;
-  hipLaunchKernelGGL(ritz_check_kernel, dim3(B), dim3(256), 0, st, cur, oth, lam, P, n, nP, r, kRitzTol, ok);
+  if ((e = pass(iters)) != hipSuccess) return e;
+  // images whose Ritz pairs are not there yet (slower spectral decay than the first pass allows for) go on from
+  // their Ritz vectors for a few more steps; for the others every kernel of this pass returns at once
+  masked = true;
+  hipLaunchKernelGGL(mask_passed_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, (const int*)ok, skip_until, last_orth, B);
+  if ((e = pass(more_iters)) != hipSuccess) return e;
   *ut = cur;
   return hipGetLastError();
 }
