@@ -28,6 +28,9 @@ PEAK = {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0, "mfma_fp64_TFLOPs": 78.6
 TRAFFIC = {
     (5, "gemm_nt_dma_kernel<rownorm2>"): 4424852 * 1024 * 2.0 + 23040 * 1024 * 1.0,
     (5, "activity_kernel"): 3686457 * 1024 * 2.0 + 1994 * 1024 * 1.0,
+    # whole calls of the vocabulary passes at 64 x 8 x 151,936 bf16 (profiles/verify_draft_s64_l8_v151936_hbm_counters.txt)
+    ("verify", "whole call"): 180664 * 1024 * 2.0 + 150 * 1024 * 1.0,
+    ("draft", "whole call"): 77174 * 1024 * 2.0 + 1264 * 1024 * 1.0,
 }
 
 
@@ -208,7 +211,7 @@ def verify_bench(a):
             "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "verify S=%d L=%d V=%d" % (S, L, V), "entry_point": "covspec_verify"},
             "roofline": {"bound": "hbm", "achieved": round(alg / (ms * 1e-3) / 1e9, 1), "peak": PEAK["hbm_GBps"], "unit": "GB/s",
-                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": None,
+                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": TRAFFIC[("verify", "whole call")],
                          "kernel": "whole call (verify_stats_kernel streams the logits)", "device_ms": round(ms, 4)}}
     if not a.no_cpu_baseline:
         from oracle import verify_oracle as VO
@@ -262,7 +265,7 @@ def draft_bench(a):
             "config": {"workload": "draft gate S=%d L=%d V=%d F0=%d rho=%g gamma=%g" % (S, L, V, F0, rho, gamma),
                        "entry_point": "covspec_draft_gate"},
             "roofline": {"bound": "hbm", "achieved": round(alg / (ms * 1e-3) / 1e9, 1), "peak": PEAK["hbm_GBps"], "unit": "GB/s",
-                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": None,
+                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": TRAFFIC[("draft", "whole call")],
                          "kernel": "whole call (draft_scan_kernel streams the logits)", "device_ms": round(ms, 4)}}
     if not a.no_cpu_baseline:
         from oracle import draft_oracle as DO
