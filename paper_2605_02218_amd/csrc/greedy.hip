@@ -185,12 +185,35 @@ __global__ __launch_bounds__(TPB) void greedy_single_kernel(const double* __rest
     double dot[RPT];
 #pragma unroll
     for (int s = 0; s < RPT; ++s) dot[s] = 0.0;
-    for (int q = 0; q < t; ++q) {
-      const double lp = Lp[q];
-      const double* row = Ltb + (long)q * nP + tid;
+    // The columns picked so far are re-read from L2 / the memory-side cache at every step; the step lives on the
+    // latency of those loads, so sixteen of them are issued before the first is used.
+    {
+      constexpr int UQ = 16;
+      int q = 0;
+      for (; q + UQ <= t; q += UQ) {
 #pragma unroll
-      for (int s = 0; s < RPT; ++s)
-        if (tid + TPB * s < n) dot[s] = fma(row[TPB * s], lp, dot[s]);
+        for (int s = 0; s < RPT; ++s) {
+          if (tid + TPB * s < n) {
+            double v[UQ];
+#pragma unroll
+            for (int u = 0; u < UQ; ++u) v[u] = Ltb[(long)(q + u) * nP + tid + TPB * s];
+            double d0 = 0.0, d1 = 0.0;
+#pragma unroll
+            for (int u = 0; u < UQ; u += 2) {
+              d0 = fma(v[u], Lp[q + u], d0);
+              d1 = fma(v[u + 1], Lp[q + u + 1], d1);
+            }
+            dot[s] += d0 + d1;
+          }
+        }
+      }
+      for (; q < t; ++q) {
+        const double lp = Lp[q];
+        const double* row = Ltb + (long)q * nP + tid;
+#pragma unroll
+        for (int s = 0; s < RPT; ++s)
+          if (tid + TPB * s < n) dot[s] = fma(row[TPB * s], lp, dot[s]);
+      }
     }
 #pragma unroll
     for (int s = 0; s < RPT; ++s) {
