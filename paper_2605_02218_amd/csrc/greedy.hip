@@ -108,6 +108,17 @@ __global__ __launch_bounds__(GT) void greedy_kernel(const double* __restrict__ G
     {
       const double* col = Ltb + i;
       int q = w;
+      // eight loads in flight per wave: the step lives on their latency
+      for (; q + 28 < t; q += 32) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = col[(long)(q + 4 * u) * nP];
+#pragma unroll
+        for (int u = 0; u < 8; u += 2) {
+          d0 = fma(v[u], Lp[q + 4 * u], d0);
+          d1 = fma(v[u + 1], Lp[q + 4 * u + 4], d1);
+        }
+      }
       for (; q + 4 < t; q += 8) {
         d0 = fma(col[(long)q * nP], Lp[q], d0);
         d1 = fma(col[(long)(q + 4) * nP], Lp[q + 4], d1);
