@@ -328,7 +328,11 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
   // entries themselves, so its Gram matrix is accumulated in fp64; the energy ranking is not a
   // cancellation and takes the bf16 MFMA with fp32 partial sums flushed into fp64.
   if (q.dtype == COVSPEC_FP32) HIPCHK(launch_gemm64_nt(g, false, false, st));
-  else if (q.lr == COVSPEC_LR_GREEDY_RESIDUAL) HIPCHK(launch_gemm64_bf16(g, st));
+  else if (q.lr == COVSPEC_LR_GREEDY_RESIDUAL) {
+    g.lower_only = true;      // Z Z^T is symmetric: the tiles above the diagonal are the transposes of those below
+    g.mirror = true;
+    HIPCHK(launch_gemm64_bf16(g, st));
+  }
   else HIPCHK(launch_gemm_nt(g, DT_BF16, st));
 
   bool probed = false;

@@ -159,6 +159,8 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
             double* out = (double*)g.C + coff + (long)r * g.ldc + c;
             if (EPI == EPI_SUB_F64) *out -= acc[i][j][v];
             else *out = acc[i][j][v];
+            // lanes of equal i16 hold four consecutive rows r: the transposed store goes out in 32-byte pieces
+            if (EPI == EPI_STORE_F64 && g.mirror && tn != tm) ((double*)g.C)[coff + (long)c * g.ldc + r] = acc[i][j][v];
           }
         }
   } else {  // EPI_ROWNORM2: per-row sum over this tile's columns of C^2 (fp64)

@@ -34,6 +34,8 @@ struct GemmArgs {
   int epilogue = EPI_STORE_F32;
   // fp64 kernel only:
   bool lower_only = false;                     // tiles entirely above the diagonal of C are not computed
+  bool mirror = false;                         // with lower_only, square tiles and a symmetric product (A = B): tiles below the
+                                               // diagonal are also stored transposed, so that C comes out full
   bool transB = false;                         // B is stored [K][N] (row pitch ldb), i.e. C = A * B
   const int* skip = nullptr;                   // per outer batch: the work is skipped while skip[b] > skip_if
   int skip_if = 1;
