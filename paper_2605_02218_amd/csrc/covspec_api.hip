@@ -333,7 +333,11 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
     g.mirror = true;
     HIPCHK(launch_gemm64_bf16(g, st));
   }
-  else HIPCHK(launch_gemm_nt(g, DT_BF16, st));
+  else {
+    g.lower_only = true;
+    g.mirror = true;
+    HIPCHK(launch_gemm_nt(g, DT_BF16, st));
+  }
 
   bool probed = false;
   if (q.lr == COVSPEC_LR_ENERGY_TOPK) {

@@ -73,6 +73,7 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_kernel(GemmArgs g, int tiles_
   const int wm = wave >> 1, wn = wave & 1;
   const TileMap tmap = map_block(blockIdx.x, gridDim.x, tiles_m, tiles_n);
   const int row0 = tmap.tm * BT, col0 = tmap.tn * BT;
+  if (g.lower_only && tmap.tn > tmap.tm) return;      // square tiles: entirely above the diagonal (uniform)
 
   const int bo = tmap.b / g.batch_inner, bi = tmap.b - bo * g.batch_inner;
   const In* __restrict__ A = (const In*)g.A + (long)bo * g.strideA + (long)bi * g.strideA2;
@@ -229,7 +230,12 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_kernel(GemmArgs g, int tiles_
           if (r < g.M && c < g.N) {
             long o = coff + (long)r * g.ldc + c;
             if (EPI == EPI_STORE_F32) ((float*)g.C)[o] = acc[i][j][v];
-            else ((double*)g.C)[o] = acc64[(i * TW + j) * 16 + v];
+            else {
+              ((double*)g.C)[o] = acc64[(i * TW + j) * 16 + v];
+              // symmetric product: the tile below the diagonal is also stored transposed (v & 3 walks four
+              // consecutive rows r, so each thread writes 32 contiguous bytes of row c)
+              if (g.mirror && tmap.tn != tmap.tm) ((double*)g.C)[coff + (long)c * g.ldc + r] = acc64[(i * TW + j) * 16 + v];
+            }
           }
         }
   } else if (EPI == EPI_ROWNORM2) {

@@ -460,6 +460,8 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
       g.A = cur; g.B = oth; g.C = H; g.M = P; g.N = P; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = P;
       g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)P * nP; g.strideC = (long)P * P;
       g.epilogue = EPI_STORE_F64;
+      g.lower_only = true;      // H is symmetric: the tiles below the diagonal are mirrored
+      g.mirror = true;
       mask(g);
       if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
     }
