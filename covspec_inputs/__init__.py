@@ -202,6 +202,17 @@ def small_workload(cid: int = 0, **kw) -> Workload:
     return replace(WORKLOADS[1], cid=cid, name=kw.pop("name", "custom"), **kw)
 
 
+def make_spectrum_tokens(n: int, d: int, sigma: np.ndarray, seed: int, dtype: int = FP32) -> np.ndarray:
+    """n tokens of width d >= n whose singular values are exactly ``sigma`` (before the one rounding to the
+    storage dtype): X = U diag(sigma) W^T with U (n x n) and W (d x n) the orthonormal factors of Gaussian
+    matrices.  For tests that need a prescribed decay of the Gram matrix's eigenvalues sigma^2."""
+    rng = np.random.default_rng(BASE_SEED + 700000 + seed)
+    U, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    W, _ = np.linalg.qr(rng.standard_normal((d, n)))
+    X = (U * np.asarray(sigma, dtype=np.float64)[None, :]) @ W.T
+    return store(X.astype(np.float32), dtype)
+
+
 # --------------------------------------------------------------------------
 # logits for the speculative verification step (paper Sec. II-A)
 # --------------------------------------------------------------------------

@@ -201,6 +201,18 @@ int covspec_reduce_ragged(const covspec_params* p, const covspec_ragged* r, cons
                           const covspec_stream_t* streams, int32_t n_streams);
 
 /*
+ * Which way each image's eigen-solve went in the LAST covspec_select / covspec_reduce call with these
+ * parameters on this workspace (COVSPEC_LR_ENERGY_TOPK only; diagnostics for tests and tuning: the
+ * paper's Sec. III-A.3 asks for a rank-r SVD and says nothing of how).  path_out: DEVICE int32 [B]:
+ *   1  block subspace iteration, converged at the first residual check
+ *   2  converged after the additional steps of the second pass
+ *   0  full Jacobi solve of the Gram matrix (fallback, or the block would be most of the matrix)
+ * Enqueued on `stream` after the call in question; reads the workspace, writes nothing else.
+ */
+int covspec_lowrank_path(const covspec_params* p, const void* workspace, int32_t* path_out,
+                         covspec_stream_t stream);
+
+/*
  * Description of the probed launch for these parameters: number of equal launches per call (0 when
  * nothing is probed) and, if non-NULL, its dimensions: the product is [rows x inner] * [inner x cols]
  * per image in fp64 (2*rows*cols*inner flops per image).

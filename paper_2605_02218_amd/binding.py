@@ -24,7 +24,7 @@ EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspe
            "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string",
            "covspec_verify_workspace_size", "covspec_verify", "covspec_draft_fanout", "covspec_draft_workspace_size",
            "covspec_draft_gate", "covspec_last_error", "covspec_ragged_resolve", "covspec_ragged_workspace_size",
-           "covspec_reduce_ragged")
+           "covspec_reduce_ragged", "covspec_lowrank_path")
 
 
 class CovspecParams(ctypes.Structure):
@@ -108,6 +108,8 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_ragged_workspace_size.argtypes = [pp, rp, ctypes.c_int32]
     lib.covspec_reduce_ragged.restype = ctypes.c_int
     lib.covspec_reduce_ragged.argtypes = [pp, rp] + [vp] * 7 + [vp, ctypes.c_size_t, ctypes.POINTER(vp), ctypes.c_int32]
+    lib.covspec_lowrank_path.restype = ctypes.c_int
+    lib.covspec_lowrank_path.argtypes = [pp, vp, vp, vp]
     lib.covspec_last_error.restype = ctypes.c_char_p
     lib.covspec_last_error.argtypes = []
     _lib = lib
@@ -430,3 +432,15 @@ def reduce_ragged(p: Params, n_tokens, n_query, X, hidden, Q, Wq, Wk, streams=No
         for s in streams:
             s.synchronize()
     return idx, tok, ks
+
+
+def lowrank_path(p: Params, workspace):
+    """covspec_lowrank_path: int32 [B] tensor, the eigen-solve path of each image in the last call on `workspace`."""
+    import torch
+    out = torch.empty(p.batch, dtype=torch.int32, device=workspace.device)
+    wp, _ = _ws_args(workspace)
+    cs = p.c_struct()
+    st = load_library().covspec_lowrank_path(ctypes.byref(cs), wp, _ptr(out), _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_lowrank_path")
+    return out

@@ -541,6 +541,22 @@ int covspec_reduce_ragged(const covspec_params* p, const covspec_ragged* r, cons
   });
 }
 
+int covspec_lowrank_path(const covspec_params* p, const void* workspace, int32_t* path_out, covspec_stream_t stream) {
+  Plan pl;
+  const int st = make_plan(p, &pl);
+  if (st != COVSPEC_OK) return st;
+  if (!workspace || !path_out || ((uintptr_t)workspace & 255u)) return COVSPEC_INVALID_ARG;
+  if (pl.lr != COVSPEC_LR_ENERGY_TOPK) return COVSPEC_INVALID_ARG;
+  discard_pending_error();
+  if (pl.P > 0) {
+    HIPCHK(hipMemcpyAsync(path_out, (const char*)workspace + pl.ok, (size_t)pl.B * sizeof(int32_t), hipMemcpyDeviceToDevice,
+                          (hipStream_t)stream));
+  } else {
+    HIPCHK(launch_fill_int(path_out, pl.B, 0, (hipStream_t)stream));
+  }
+  return COVSPEC_OK;
+}
+
 int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols, int32_t* inner) {
   Plan pl;
   if (make_plan(p, &pl) != COVSPEC_OK) return 0;

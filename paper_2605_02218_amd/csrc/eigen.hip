@@ -396,14 +396,14 @@ __global__ __launch_bounds__(256) void row_length_kernel(const double* __restric
 }
 
 // c[b,i] = sum over the r longest rows k of A[b] (rows x pitch) of A[k][i]^2 / |row k|, rows added in
-// ascending k; i < n.  Images with flag[b] != run_if are skipped (flag == nullptr: none).
+// ascending k; i < n.  Images with (flag[b] != 0) != (run_if != 0) are skipped (flag == nullptr: none).
 __global__ __launch_bounds__(256) void energy_kernel(const double* __restrict__ A, int rows, int n, int pitch, long img_stride,
                                                       int r, const double* __restrict__ lam, float* __restrict__ c,
                                                       const int* __restrict__ flag, int run_if) {
   __shared__ double slam[4096];
   __shared__ unsigned char sel[4096];
   const int b = blockIdx.y;
-  if (flag && flag[b] != run_if) return;
+  if (flag && (flag[b] != 0) != (run_if != 0)) return;     // flag: 0 = not converged, any other value = converged
   const double* lb = lam + (long)b * rows;
   for (int k = threadIdx.x; k < rows; k += 256) slam[k] = lb[k];
   __syncthreads();

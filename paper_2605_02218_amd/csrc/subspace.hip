@@ -324,7 +324,7 @@ __global__ void mask_passed_kernel(const int* __restrict__ ok, int* __restrict__
   last_orth[b] = -1;
 }
 
-// Residual check of the r dominant Ritz pairs.  Ut rows are theta_k u_k^T, Rt = Ut G.  ok[b] = 1 when
+// Residual check of the r dominant Ritz pairs.  Ut rows are theta_k u_k^T, Rt = Ut G.  ok[b] = 1 (2 in the second pass) when
 // |Rt_k - theta_k Ut_k| <= tol * theta_k^2 for each of them (theta_k = |Ut_k|, so this is the relative
 // residual |G u - theta u| / theta).
 __global__ __launch_bounds__(256) void ritz_check_kernel(const double* __restrict__ Ut, const double* __restrict__ Rt,
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256) void ritz_check_kernel(const double* __restric
     if (lane == 0 && !(sqrt(s) <= tol * th * th)) bad = 1;   // also catches NaN
   }
   __syncthreads();
-  if (threadIdx.x == 0) ok[b] = bad ? 0 : 1;
+  if (threadIdx.x == 0) ok[b] = bad ? 0 : (only_failed ? 2 : 1);    // 1: first pass, 2: second pass
 }
 
 }  // namespace

@@ -242,11 +242,39 @@ def test_flat_spectrum_takes_the_full_eigen_solve(C):
     op = U.oracle_params(w)
     refs = [U.oracle_image(w, batch, b, op) for b in range(w.batch)]
     sf32 = np.stack([O.decision_values(r["s_fused"]) for r in refs])
-    out = C.select(U.lib_params(C, w, w.batch), dev["X"], torch.from_numpy(sf32).cuda())
+    p = U.lib_params(C, w, w.batch)
+    ws = C.alloc_workspace(p)
+    out = C.select(p, dev["X"], torch.from_numpy(sf32).cuda(), workspace=ws)
+    assert list(_cpu(C.lowrank_path(p, ws))) == [0] * w.batch          # neither pass of the block iteration converged
     for b, ref in enumerate(refs):
         assert ref["sigma_gap"] > 1e-3, "workload has no usable gap at r: %r" % ref["sigma_gap"]
         U.assert_scores_close(_cpu(out["c"])[b], ref["c"], w.dtype, "flat c[%d]" % b, tol=1e-4)
         np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"], err_msg="margin_topk=%r" % ref["margin_topk"])
+
+
+@pytest.mark.parametrize("decay,path", [(0.03, 1), (0.00775, 2), (0.001, 0)])
+def test_eigen_solve_ladder_by_spectral_decay(C, decay, path):
+    """Tokens with singular values exp(-decay i): the block iteration (r = 32, block of 128 of 256) contracts the
+    error of the 32nd Ritz pair by lambda_129 / lambda_32 = exp(-194 decay) per step.  Fast decay passes the first
+    residual check (12 steps); exp(-1.5) per step needs the 4 further steps of the second pass (the residual is
+    about 0.2 contraction^steps against a tolerance of 1e-9); slow decay ends in the full solve.  Whatever the
+    path, energies and kept indices match the oracle."""
+    import torch
+    n, d, k, r = 256, 384, 64, 32
+    sigma = np.exp(-decay * np.arange(n))
+    B = 2
+    X = np.stack([I.make_spectrum_tokens(n, d, sigma, seed=b, dtype=I.FP32) for b in range(B)])
+    sf = np.stack([np.random.default_rng(b).random(n).astype(np.float32) for b in range(B)])
+    p = C.Params(batch=B, n_tokens=n, d_model=d, n_query=1, dtype=C.FP32, keep_k=k, preselect_m=n, rank_r=r)
+    ws = C.alloc_workspace(p)
+    out = C.select(p, torch.from_numpy(X).cuda(), torch.from_numpy(sf).cuda(), workspace=ws)
+    paths = _cpu(C.lowrank_path(p, ws))
+    assert list(paths) == [path] * B, paths
+    op = O.Params(preselect_m=n, rank_r=r, keep_k=k)
+    for b in range(B):
+        ref = O.select(X[b].astype(np.float64), sf[b], op)
+        U.assert_scores_close(_cpu(out["c"])[b], ref["c"], I.FP32, "c[%d] decay %g" % (b, decay), tol=1e-4)
+        np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"], err_msg="margin_topk=%r" % ref.get("margin_topk"))
 
 
 def test_select_ties_and_exact_duplicates(C):
