@@ -29,7 +29,7 @@ TRAFFIC = {
     (5, "gemm_nt_dma_kernel<rownorm2>"): 4424852 * 1024 * 2.0 + 23040 * 1024 * 1.0,
     (5, "activity_kernel"): 3686457 * 1024 * 2.0 + 1994 * 1024 * 1.0,
     # whole calls of the vocabulary passes at 64 x 8 x 151,936 bf16 (profiles/verify_draft_s64_l8_v151936_hbm_counters.txt)
-    ("verify", "whole call"): 180664 * 1024 * 2.0 + 150 * 1024 * 1.0,
+    ("verify", "whole call"): 166599 * 1024 * 2.0 + 86 * 1024 * 1.0,
     ("draft", "whole call"): 77174 * 1024 * 2.0 + 1264 * 1024 * 1.0,
 }
 

@@ -2,13 +2,13 @@
 // acceptance probability of each drafted token, residual distribution after the first rejection).
 //
 // Per sequence s and drafted position tau the two logit rows z_t, z_d [V] are read ONCE by the statistics
-// pass (row maximum and sum of exponentials of both, fp32 exponentials, partial results per chunk so that a
+// pass (reference and sum of exponentials of both, fp32 exponentials, partial results per chunk so that a
 // few rows still fill the device); the acceptance pass combines them in fp64, evaluates
 // alpha = min(1, p_t(y)/p_d(y)) at the drafted token, finds the first rejection and notes that row's
-// statistics; only that one row per sequence is read again, twice, in fp64: chunk sums of
-// max(p_t - p_d, 0), then the inverse-CDF search of the correction inside the chunk that holds
-// u_res * (total residual mass).  Everything is HBM-bound streaming except the fp64 exponentials of the
-// residual passes (2 per word, one row per sequence).
+// statistics; only that one row per sequence is read again, in fp64: once for the exact sums and the chunk
+// masses of max(p_t - p_d, 0), then, inside the one chunk that holds u_res * (total residual mass), for the
+// inverse-CDF search of the correction.  Everything is HBM-bound streaming except the fp64 exponentials of the
+// residual pass (2 per word, one row per sequence).
 #include "common.h"
 #include "kernels.h"
 #include "vocab.h"
@@ -47,9 +47,10 @@ __global__ __launch_bounds__(VT) void verify_stats_kernel(const void* __restrict
 }
 
 // One wave per sequence, one lane per drafted position: row statistics from the chunk partials, alpha at the
-// drafted token, first rejection.  rowmax[s * 2 + {0,1}] = the rejected row's references brought back to the
+// drafted token, first rejection.  rowmax[s * 4 + {0,1}] = the rejected row's references brought back to the
 // natural domain, i.e. its maximum logits to within rounding: the shift the fp64 passes below use (any value
-// near the maximum serves, as long as every pass uses the same); untouched when nothing is rejected.
+// near the maximum serves, as long as every pass uses the same), [2] = the ratio of the two streaming sums;
+// untouched when nothing is rejected.
 template <int DT>
 __global__ __launch_bounds__(64) void verify_accept_kernel(const void* __restrict__ zt, const void* __restrict__ zd,
                                                            const int32_t* __restrict__ tok, const float* __restrict__ u_acc, int L,
@@ -85,55 +86,81 @@ __global__ __launch_bounds__(64) void verify_accept_kernel(const void* __restric
     if (mask != 0ull) {
       const int fl = __ffsll((long long)mask) - 1;
       first = t0 + fl;
-      if (lane == fl) { rowmax[s * 2] = m[0] / (double)kLog2e; rowmax[s * 2 + 1] = m[1] / (double)kLog2e; }
+      if (lane == fl) {
+        rowmax[s * 4] = m[0] / (double)kLog2e;
+        rowmax[s * 4 + 1] = m[1] / (double)kLog2e;
+        // estimate of (sum_w exp(z_t - shift_t)) / (sum_w exp(z_d - shift_d)), good to the ~1e-6 of the streaming sums
+        rowmax[s * 4 + 2] = sum[0] / sum[1];
+      }
       break;      // uniform: the ballot is the same in every lane
     }
   }
   if (lane == 0) n_acc[s] = first;
 }
 
-// fp64 sums of exponentials of both logit rows at the rejected position, per chunk: the residual is a
-// difference of the two distributions, and the fp32 sums of the first pass (good to ~1e-7) would move its
-// cumulative sums by more than a flat residual's single words.  rowsum[(s * rchunks + c) * 2 + {0,1}].
+// The one fp64 pass over the rejected row of each sequence, per chunk: exact sums S_t, S_d of the exponentials
+// (the residual is a difference of the two distributions, and the fp32 sums of the first pass, good to ~1e-6,
+// would move its cumulative sums by more than a flat residual's single words) and, in the same pass, the
+// chunk's residual mass.  max(p_t - p_d, 0) = max(e_t - kappa e_d, 0) / S_t with kappa = S_t / S_d, which is not
+// known before the pass ends; but the mass is A - kappa B with A, B the sums of e_t, e_d over the words where
+// e_t > kappa e_d, and an error delta in the kappa that picks those words changes the mass only to second
+// order (a word that changes sides carries a residual below delta e_d).  So the words are picked with the
+// streaming estimate (delta ~ 1e-6, mass error ~ 1e-12 relative) and A, B are combined with the exact kappa
+// afterwards.  rowsum[(s * rchunks + c) * 4 + {0,1,2,3}] = S_t, S_d, A, B of the chunk.
 template <int DT>
-__global__ __launch_bounds__(VT) void verify_rowsum64_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
-                                                             int rlen, int rchunks, const int32_t* __restrict__ n_acc,
-                                                             const double* __restrict__ rowmax, double* __restrict__ rowsum) {
-  __shared__ double red[2][VT / 64];
+__global__ __launch_bounds__(VT) void verify_rowpass64_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
+                                                              int rlen, int rchunks, const int32_t* __restrict__ n_acc,
+                                                              const double* __restrict__ rowmax, double* __restrict__ rowsum) {
+  __shared__ double red[4][VT / 64];
   const int s = blockIdx.y, c = blockIdx.x;
   const int t = n_acc[s];
   if (t >= L) return;
   const long base = ((long)s * L + t) * V;
   const int w0 = c * rlen, w1 = min(V, w0 + rlen);
-  const double mt = rowmax[s * 2], md = rowmax[s * 2 + 1];
-  double sm[2] = {0.0, 0.0};
+  const double mt = rowmax[s * 4], md = rowmax[s * 4 + 1], kap = rowmax[s * 4 + 2];
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
   for (int w = w0 + threadIdx.x; w < w1; w += VT) {
-    sm[0] += exp(LogitVec<DT>::at(zt, base + w) - mt);
-    sm[1] += exp(LogitVec<DT>::at(zd, base + w) - md);
+    const double et = exp(LogitVec<DT>::at(zt, base + w) - mt);
+    const double ed = exp(LogitVec<DT>::at(zd, base + w) - md);
+    acc[0] += et;
+    acc[1] += ed;
+    if (et > kap * ed) { acc[2] += et; acc[3] += ed; }     // equal rows: kap == 1 and et == ed exactly, nothing is picked
   }
 #pragma unroll
-  for (int q = 0; q < 2; ++q) sm[q] = wave_sum(sm[q]);
+  for (int q = 0; q < 4; ++q) acc[q] = wave_sum(acc[q]);
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  if (lane == 0) { red[0][wv] = sm[0]; red[1][wv] = sm[1]; }
+  if (lane == 0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) red[q][wv] = acc[q];
+  }
   __syncthreads();
-  if (threadIdx.x < 2) {
+  if (threadIdx.x < 4) {
     const int q = threadIdx.x;
     double tot = 0.0;
     for (int k = 0; k < VT / 64; ++k) tot += red[q][k];
-    rowsum[((long)s * rchunks + c) * 2 + q] = tot;
+    rowsum[((long)s * rchunks + c) * 4 + q] = tot;
   }
 }
 
 // wave 0 of a workgroup (all 64 lanes): the row's (max_t, 1/sum_t, max_d, 1/sum_d) from the chunk sums, into
-// LDS.  rchunks <= 64: lane c holds chunk c, butterfly sums (the same order wherever this is called).
-__device__ __forceinline__ void combine_rowstat(const double* __restrict__ rowmax, const double* __restrict__ rowsum, int s, int rchunks,
-                                                double* sh4) {
+// LDS.  rchunks <= 64: lane c holds chunk c, butterfly sums (the same order wherever this is called).  Returns
+// the residual mass of chunk `lane`, A / S_t - B / S_d (0 for lanes beyond the chunks).
+__device__ __forceinline__ double combine_rowstat(const double* __restrict__ rowmax, const double* __restrict__ rowsum, int s, int rchunks,
+                                                  double* sh4) {
   const int lane = threadIdx.x & 63;
-  double st = lane < rchunks ? rowsum[((long)s * rchunks + lane) * 2] : 0.0;
-  double sd = lane < rchunks ? rowsum[((long)s * rchunks + lane) * 2 + 1] : 0.0;
-  st = wave_sum(st);
-  sd = wave_sum(sd);
-  if (lane == 0) { sh4[0] = rowmax[s * 2]; sh4[1] = 1.0 / st; sh4[2] = rowmax[s * 2 + 1]; sh4[3] = 1.0 / sd; }
+  const double* rs = rowsum + ((long)s * rchunks + lane) * 4;
+  const double st_c = lane < rchunks ? rs[0] : 0.0, sd_c = lane < rchunks ? rs[1] : 0.0;
+  const double a_c = lane < rchunks ? rs[2] : 0.0, b_c = lane < rchunks ? rs[3] : 0.0;
+  const double st = wave_sum(st_c), sd = wave_sum(sd_c);
+  const double ist = 1.0 / st, isd = 1.0 / sd;
+  if (lane == 0) { sh4[0] = rowmax[s * 4]; sh4[1] = ist; sh4[2] = rowmax[s * 4 + 1]; sh4[3] = isd; }
+  double mass;
+  {
+#pragma clang fp contract(off)
+    const double x = a_c * ist, y = b_c * isd;
+    mass = x - y;
+  }
+  return mass > 0.0 ? mass : 0.0;
 }
 
 template <int DT>
@@ -147,40 +174,11 @@ __device__ __forceinline__ double residual_at(const void* zt, const void* zd, lo
   return d > 0.0 ? d : 0.0;
 }
 
-// part[s * chunks + c] = sum over the chunk of max(p_t - p_d, 0) at the rejected row (0 when nothing was rejected)
-template <int DT>
-__global__ __launch_bounds__(VT) void verify_residual_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
-                                                             int clen, int chunks, const int32_t* __restrict__ n_acc,
-                                                             const double* __restrict__ rowmax, const double* __restrict__ rowsum,
-                                                             double* __restrict__ part) {
-  __shared__ double red[VT / 64];
-  __shared__ double sh4[4];
-  const int s = blockIdx.y, c = blockIdx.x;
-  const int t = n_acc[s];
-  if (t >= L) { if (threadIdx.x == 0) part[(long)s * chunks + c] = 0.0; return; }
-  const long base = ((long)s * L + t) * V;
-  if (threadIdx.x < 64) combine_rowstat(rowmax, rowsum, s, chunks, sh4);
-  __syncthreads();
-  const double mt = sh4[0], ist = sh4[1], md = sh4[2], isd = sh4[3];
-  const int w0 = c * clen, w1 = min(V, w0 + clen);
-  double acc = 0.0;
-  for (int w = w0 + threadIdx.x; w < w1; w += VT) acc += residual_at<DT>(zt, zd, base + w, mt, ist, md, isd);
-  acc = wave_sum(acc);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double tot = 0.0;
-    for (int k = 0; k < VT / 64; ++k) tot += red[k];
-    part[(long)s * chunks + c] = tot;
-  }
-}
-
 // One 1024-thread workgroup per sequence: inverse CDF of the residual in vocabulary order.
 template <int DT>
 __global__ __launch_bounds__(1024) void verify_sample_kernel(const void* __restrict__ zt, const void* __restrict__ zd, int L, int V,
                                                              int clen, int chunks, const int32_t* __restrict__ n_acc,
                                                              const double* __restrict__ rowmax, const double* __restrict__ rowsum,
-                                                             const double* __restrict__ part,
                                                              const float* __restrict__ u_res, int32_t* __restrict__ corr) {
   __shared__ double wsum[16];
   __shared__ double sh_prefix, sh_target;
@@ -191,12 +189,12 @@ __global__ __launch_bounds__(1024) void verify_sample_kernel(const void* __restr
   if (t >= L) { if (tid == 0) corr[s] = -1; return; }
   const long base = ((long)s * L + t) * V;
   __shared__ double sh4[4];
-  if (tid < 64) combine_rowstat(rowmax, rowsum, s, chunks, sh4);
+  double pc = 0.0;
+  if (tid < 64) pc = combine_rowstat(rowmax, rowsum, s, chunks, sh4);     // this lane's chunk mass (wave 0)
   __syncthreads();
   const double mt = sh4[0], ist = sh4[1], md = sh4[2], isd = sh4[3];
   if (tid < 64) {
     // lane c holds chunk c's residual mass; inclusive scan in lane order, total in lane 63
-    const double pc = lane < chunks ? part[(long)s * chunks + lane] : 0.0;
     double inc = pc;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -299,7 +297,7 @@ size_t verify_workspace_bytes(int S, int L, int V, int dtype) {
   int clen, chunks, rlen, rchunks;
   verify_plan(S, L, V, dtype, &clen, &chunks);
   residual_plan(S, V, &rlen, &rchunks);
-  return ((size_t)S * L * chunks * 4 + (size_t)S * 2 + (size_t)S * rchunks * 3) * sizeof(double) + 512;
+  return ((size_t)S * L * chunks * 4 + (size_t)S * 4 + (size_t)S * rchunks * 4) * sizeof(double) + 512;
 }
 
 template <int DT>
@@ -309,18 +307,15 @@ static hipError_t launch_verify_t(const void* zt, const void* zd, const int32_t*
   verify_plan(S, L, V, DT, &clen, &chunks);
   residual_plan(S, V, &rlen, &rchunks);
   double* stats = (double*)ws;                               // [S*L][chunks][4]
-  double* rowmax = stats + (size_t)S * L * chunks * 4;       // [S][2]
-  double* rowsum = rowmax + (size_t)S * 2;                   // [S][rchunks][2]
-  double* part = rowsum + (size_t)S * rchunks * 2;           // [S][rchunks]
+  double* rowmax = stats + (size_t)S * L * chunks * 4;       // [S][4]
+  double* rowsum = rowmax + (size_t)S * 4;                   // [S][rchunks][4]
   hipLaunchKernelGGL((verify_stats_kernel<DT>), dim3(chunks, S * L), dim3(VT), 0, st, zt, zd, V, clen, chunks, stats);
   hipLaunchKernelGGL((verify_accept_kernel<DT>), dim3(S), dim3(64), 0, st, zt, zd, tok, u_acc, L, V, chunks, (const double*)stats, n_acc,
                      alpha, rowmax);
-  hipLaunchKernelGGL((verify_rowsum64_kernel<DT>), dim3(rchunks, S), dim3(VT), 0, st, zt, zd, L, V, rlen, rchunks, (const int32_t*)n_acc,
+  hipLaunchKernelGGL((verify_rowpass64_kernel<DT>), dim3(rchunks, S), dim3(VT), 0, st, zt, zd, L, V, rlen, rchunks, (const int32_t*)n_acc,
                      (const double*)rowmax, rowsum);
-  hipLaunchKernelGGL((verify_residual_kernel<DT>), dim3(rchunks, S), dim3(VT), 0, st, zt, zd, L, V, rlen, rchunks, (const int32_t*)n_acc,
-                     (const double*)rowmax, (const double*)rowsum, part);
   hipLaunchKernelGGL((verify_sample_kernel<DT>), dim3(S), dim3(1024), 0, st, zt, zd, L, V, rlen, rchunks, (const int32_t*)n_acc,
-                     (const double*)rowmax, (const double*)rowsum, (const double*)part, u_res, corr);
+                     (const double*)rowmax, (const double*)rowsum, u_res, corr);
   return hipGetLastError();
 }
 
