@@ -33,6 +33,7 @@ BASE_SEED = 260502218
 
 FP32 = 0
 BF16 = 1
+FP16 = 2      # logits of the vocabulary passes only; stored as uint16 bit patterns like bf16
 
 
 @dataclass(frozen=True)
@@ -90,6 +91,8 @@ def store(x: np.ndarray, dtype: int) -> np.ndarray:
     """Round a float32 array once to the storage dtype."""
     if dtype == FP32:
         return np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == FP16:
+        return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
     return f32_to_bf16_bits(x)
 
 
@@ -97,6 +100,8 @@ def as_f32(a: np.ndarray, dtype: int) -> np.ndarray:
     """Stored array -> float32 with exactly the stored values."""
     if dtype == FP32:
         return np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == FP16:
+        return np.ascontiguousarray(a, dtype=np.uint16).view(np.float16).astype(np.float32)
     return bf16_bits_to_f32(a)
 
 

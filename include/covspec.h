@@ -45,7 +45,8 @@ enum {
   COVSPEC_HIP_ERROR = 4            /* a launch failed; hipGetLastError() still holds the cause    */
 };
 
-enum { COVSPEC_FP32 = 0, COVSPEC_BF16 = 1 };
+enum { COVSPEC_FP32 = 0, COVSPEC_BF16 = 1,
+       COVSPEC_FP16 = 2 /* logits of covspec_verify and covspec_draft_gate only */ };
 
 /* Query-relevance definition.
  *   COSINE_MAX   : S^query_i = max_j cos(e(v_i), e(q_j))  (paper Sec. III-A.1, query-aware score).
@@ -235,12 +236,12 @@ int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols
  * The random numbers are inputs: uniforms in [0, 1) drawn by the caller.
  *
  * All pointers are DEVICE pointers, dense row-major, 16-byte aligned:
- *   z_target, z_draft [n_seq, n_draft, vocab]  dtype (fp32 or bf16 bit patterns)
+ *   z_target, z_draft [n_seq, n_draft, vocab]  dtype (fp32, or bf16 / fp16 bit patterns)
  *   tokens            [n_seq, n_draft] int32 in [0, vocab); a value outside is clamped into the range
  *   u_accept          [n_seq, n_draft] fp32;  u_resample [n_seq] fp32
  *   n_accept_out      [n_seq] int32 (required);  correction_out [n_seq] int32 (required)
  *   alpha_out         [n_seq, n_draft] fp32 (or NULL)
- * Limits: vocab a multiple of 8 (bf16) or 4 (fp32), 2 <= vocab, n_seq * n_draft <= 65535, else
+ * Limits: vocab a multiple of 8 (bf16, fp16) or 4 (fp32), 2 <= vocab, n_seq * n_draft <= 65535, else
  * COVSPEC_UNSUPPORTED.  The workspace (covspec_verify_workspace_size bytes, 256-byte aligned, owned
  * by the caller, contents undefined between calls) holds per-chunk partial sums.  Work is enqueued on
  * `stream`; the call does not synchronise and allocates nothing.  Returns a covspec_status.
@@ -277,7 +278,7 @@ int covspec_verify(const covspec_verify_params* p, const void* z_target, const v
  *   excludes nothing);  margin_out [n_seq, n_draft] fp32 (required);  gate_out [n_seq, n_draft] int32
  *   (required);  cand_out [n_seq, n_draft, fanout0] int32 (required unless fanout0 == 0).
  * Limits: 0 <= fanout0 <= 32, 0 < rho <= 1, n_draft <= 64, n_seq * n_draft <= 65535, vocab a multiple of
- * 8 (bf16) or 4 (fp32) and at most 524288, else COVSPEC_INVALID_ARG / COVSPEC_UNSUPPORTED.  Workspace as
+ * 8 (bf16, fp16) or 4 (fp32) and at most 524288, else COVSPEC_INVALID_ARG / COVSPEC_UNSUPPORTED.  Workspace as
  * for covspec_verify (covspec_draft_workspace_size bytes, 256-byte aligned).  Enqueues on `stream`,
  * does not synchronise, allocates nothing.  Returns a covspec_status.
  */

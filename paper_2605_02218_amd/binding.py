@@ -16,6 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcovspec.so")
 
 FP32, BF16 = 0, 1
+FP16 = 2          # logits of verify / draft_gate only
 REL_COSINE_MAX, REL_ATTN_SOFTMAX = 0, 1
 LR_ENERGY_TOPK, LR_GREEDY_RESIDUAL, LR_SCORE_TOPK, LR_RANDOM = 0, 1, 2, 3
 OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4

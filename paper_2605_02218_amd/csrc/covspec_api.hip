@@ -570,9 +570,9 @@ int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols
 static int verify_check(const covspec_verify_params* p) {
   if (!p) return COVSPEC_INVALID_ARG;
   if (p->n_seq < 1 || p->n_draft < 1 || p->vocab < 2) return COVSPEC_INVALID_ARG;
-  if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16) return COVSPEC_INVALID_ARG;
+  if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16 && p->dtype != COVSPEC_FP16) return COVSPEC_INVALID_ARG;
   if ((long)p->n_seq * p->n_draft > 65535) return COVSPEC_UNSUPPORTED;
-  if (p->vocab % (p->dtype == COVSPEC_BF16 ? 8 : 4) != 0) return COVSPEC_UNSUPPORTED;
+  if (p->vocab % (p->dtype == COVSPEC_FP32 ? 4 : 8) != 0) return COVSPEC_UNSUPPORTED;
   return COVSPEC_OK;
 }
 
@@ -601,10 +601,10 @@ int covspec_verify(const covspec_verify_params* p, const void* z_target, const v
 static int draft_check(const covspec_draft_params* p) {
   if (!p) return COVSPEC_INVALID_ARG;
   if (p->n_seq < 1 || p->n_draft < 1 || p->vocab < 2 || p->fanout0 < 0) return COVSPEC_INVALID_ARG;
-  if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16) return COVSPEC_INVALID_ARG;
+  if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16 && p->dtype != COVSPEC_FP16) return COVSPEC_INVALID_ARG;
   if (!(p->rho > 0.f && p->rho <= 1.f) || !(p->gamma == p->gamma)) return COVSPEC_INVALID_ARG;
   if (p->fanout0 > 32 || p->n_draft > 64 || (long)p->n_seq * p->n_draft > 65535) return COVSPEC_UNSUPPORTED;
-  if (p->vocab % (p->dtype == COVSPEC_BF16 ? 8 : 4) != 0 || p->vocab > draft_max_vocab()) return COVSPEC_UNSUPPORTED;
+  if (p->vocab % (p->dtype == COVSPEC_FP32 ? 4 : 8) != 0 || p->vocab > draft_max_vocab()) return COVSPEC_UNSUPPORTED;
   return COVSPEC_OK;
 }
 

@@ -233,6 +233,8 @@ hipError_t launch_draft(const void* zd, const int32_t* tok, int S, int L, int V,
   u64* top = (u64*)(stats + (size_t)rows * chunks * 2);
   if (dtype == DT_BF16)
     hipLaunchKernelGGL((draft_scan_kernel<DT_BF16>), dim3(chunks, (unsigned)rows), dim3(DTH), 0, st, zd, V, chunks, K, stats, top);
+  else if (dtype == DT_F16)
+    hipLaunchKernelGGL((draft_scan_kernel<DT_F16>), dim3(chunks, (unsigned)rows), dim3(DTH), 0, st, zd, V, chunks, K, stats, top);
   else
     hipLaunchKernelGGL((draft_scan_kernel<DT_F32>), dim3(chunks, (unsigned)rows), dim3(DTH), 0, st, zd, V, chunks, K, stats, top);
   hipLaunchKernelGGL(draft_merge_kernel, dim3((unsigned)rows), dim3(64), (size_t)chunks * K * sizeof(u64), st, (const double*)stats,

@@ -7,7 +7,7 @@
 
 namespace covspec {
 
-enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 /* logits of the vocabulary passes only */ };
 
 // ---------------------------------------------------------------- gemm.hip
 // C[M,N] = A[M,K] * B[N,K]^T  (both operands K-contiguous), fp32 accumulation on MFMA.

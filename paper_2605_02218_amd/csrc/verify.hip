@@ -270,7 +270,7 @@ __global__ __launch_bounds__(1024) void verify_sample_kernel(const void* __restr
 void verify_plan(int S, int L, int V, int dtype, int* clen, int* chunks) {
   // chunks per row so that even a few rows give the streaming kernel ~1024 workgroups; chunk length a
   // multiple of what one pass of the workgroup covers
-  const int vec = dtype == DT_BF16 ? 8 : 4;
+  const int vec = dtype == DT_F32 ? 4 : 8;
   const int step = VT * vec;
   long rows = (long)S * L;
   int want = (int)((1024 + rows - 1) / rows);
@@ -322,8 +322,9 @@ static hipError_t launch_verify_t(const void* zt, const void* zd, const int32_t*
 hipError_t launch_verify(const void* zt, const void* zd, const int32_t* tok, const float* u_acc, const float* u_res, int S, int L,
                          int V, int dtype, int32_t* n_acc, int32_t* corr, float* alpha, void* ws, hipStream_t st) {
   if (S < 1 || L < 1 || V < 2 || (long)S * L > 65535) return hipErrorInvalidValue;
-  return dtype == DT_BF16 ? launch_verify_t<DT_BF16>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st)
-                          : launch_verify_t<DT_F32>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st);
+  if (dtype == DT_BF16) return launch_verify_t<DT_BF16>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st);
+  if (dtype == DT_F16) return launch_verify_t<DT_F16>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st);
+  return launch_verify_t<DT_F32>(zt, zd, tok, u_acc, u_res, S, L, V, n_acc, corr, alpha, ws, st);
 }
 
 }  // namespace covspec

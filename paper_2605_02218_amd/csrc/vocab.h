@@ -18,6 +18,18 @@ template <> struct LogitVec<DT_BF16> {
   static __device__ __forceinline__ void load(const void* p, long i, float (&v)[8]) { unpack(load_raw(p, i), v); }
   static __device__ __forceinline__ double at(const void* p, long i) { return (double)bf16_to_f32(((const bf16_t*)p)[i]); }
 };
+template <> struct LogitVec<DT_F16> {
+  static constexpr int N = 8;
+  typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+  static __device__ __forceinline__ u32x4_t load_raw(const void* p, long i) { return *(const u32x4_t*)((const _Float16*)p + i); }
+  static __device__ __forceinline__ void unpack(const u32x4_t& w, float (&v)[8]) {
+    const half8_t h = __builtin_bit_cast(half8_t, w);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)h[e];
+  }
+  static __device__ __forceinline__ void load(const void* p, long i, float (&v)[8]) { unpack(load_raw(p, i), v); }
+  static __device__ __forceinline__ double at(const void* p, long i) { return (double)(float)((const _Float16*)p)[i]; }
+};
 template <> struct LogitVec<DT_F32> {
   static constexpr int N = 4;
   static __device__ __forceinline__ u32x4_t load_raw(const void* p, long i) { return *(const u32x4_t*)((const float*)p + i); }

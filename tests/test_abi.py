@@ -108,13 +108,14 @@ def test_verify_params_are_validated_on_the_host():
     assert C.verify_workspace_size(C.VerifyParams(1, 1, 8, C.BF16)) > 0
     fake = 4096
     for bad, status in [(C.VerifyParams(0, 8, 4096), Bd.INVALID_ARG), (C.VerifyParams(4, 0, 4096), Bd.INVALID_ARG),
-                        (C.VerifyParams(4, 8, 1), Bd.INVALID_ARG), (C.VerifyParams(4, 8, 4096, 2), Bd.INVALID_ARG),
+                        (C.VerifyParams(4, 8, 1), Bd.INVALID_ARG), (C.VerifyParams(4, 8, 4096, 3), Bd.INVALID_ARG),
                         (C.VerifyParams(4, 8, 4100, C.BF16), Bd.UNSUPPORTED), (C.VerifyParams(4, 8, 4098, C.FP32), Bd.UNSUPPORTED),
                         (C.VerifyParams(8192, 8, 4096), Bd.UNSUPPORTED)]:
         assert C.verify_workspace_size(bad) == 0
         cs = bad.c_struct()
         assert lib.covspec_verify(ctypes.byref(cs), fake, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == status
     assert C.verify_workspace_size(C.VerifyParams(4, 8, 4100, C.FP32)) > 0
+    assert C.verify_workspace_size(C.VerifyParams(4, 8, 4096, C.FP16)) > 0 and C.verify_workspace_size(C.VerifyParams(4, 8, 4100, C.FP16)) == 0
     cs = ok.c_struct()
     assert lib.covspec_verify(ctypes.byref(cs), None, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == Bd.INVALID_ARG
     assert lib.covspec_verify(ctypes.byref(cs), fake, fake, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == Bd.INVALID_ARG

@@ -19,6 +19,8 @@ def _dev(a, dtype=None):
     import torch
     if dtype == I.BF16:
         return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+    if dtype == I.FP16:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.float16)
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
@@ -47,7 +49,8 @@ def _check(zd, tok, dtype, f0, rho, gamma, margin, gate, cand, seqs=None):
             assert np.array_equal(cand[s, t], want), (s, t, cand[s, t], want)
 
 
-@pytest.mark.parametrize("dtype,V", [(I.BF16, 2 * 8192 + 520), (I.FP32, 8192 + 36), (I.BF16, 8192), (I.BF16, 8), (I.FP32, 4), (I.BF16, 264)])
+@pytest.mark.parametrize("dtype,V", [(I.BF16, 2 * 8192 + 520), (I.FP32, 8192 + 36), (I.BF16, 8192), (I.BF16, 8), (I.FP32, 4), (I.BF16, 264),
+                                     (I.FP16, 2 * 8192 + 520), (I.FP16, 16)])
 def test_draft_gate_matches_oracle_small(dtype, V):
     """Several chunks with a ragged last one, an exact chunk, and vocabularies smaller than the candidate count
     (fewer quads with data than K: the block-wide fallback)."""

@@ -22,6 +22,8 @@ def _dev(a, dtype=None):
     import torch
     if dtype == I.BF16:
         return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+    if dtype == I.FP16:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.float16)
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
@@ -57,7 +59,8 @@ def _check(d, dtype, n_acc, corr, alpha, seqs=None):
         assert corr[s] == o["corr"], (s, corr[s], o["corr"])
 
 
-@pytest.mark.parametrize("dtype,V", [(I.BF16, 4392), (I.FP32, 4100), (I.BF16, 8), (I.FP32, 4), (I.BF16, 2048 * 3)])
+@pytest.mark.parametrize("dtype,V", [(I.BF16, 4392), (I.FP32, 4100), (I.BF16, 8), (I.FP32, 4), (I.BF16, 2048 * 3), (I.FP16, 4392),
+                                     (I.FP16, 8)])
 def test_verify_matches_oracle_small(dtype, V):
     """Several chunks with a ragged last one (4392 = 2 * 2048 + 296), exact multiples, and the smallest widths."""
     d = I.make_verify_batch(6, 4, V, dtype, seed=V, copy_rows=1)
