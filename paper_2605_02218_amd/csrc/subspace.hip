@@ -157,7 +157,12 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
     double* inv = a;
     {
       double* Db = Dinv + ((long)b * nblk + J) * NB * NB;
-      for (int e = tid; e < NB * NB; e += 512) Db[e] = inv[(e >> 6) * NBP + (e & 63)];
+      // stored with the columns of every group of 16 permuted, 16x + 4v + q -> 16x + 4q + v: trsm_kernel's lane
+      // of quarter q contracts the columns 16x + 4v + q, v = 0..3, of a step group and reads them as one 32-byte piece
+      for (int e = tid; e < NB * NB; e += 512) {
+        const int c = e & 63;
+        Db[(e & ~63) | (c & 48) | ((c & 3) << 2) | ((c >> 2) & 3)] = inv[(e >> 6) * NBP + c];
+      }
     }
     // ---- panel: X = S[I,J] inv^T, 16-row tiles dealt to the waves
     const int below = P - j0 - NB;
@@ -300,13 +305,22 @@ __global__ __launch_bounds__(256) void trsm_kernel(double* Yt, const double* __r
     const double* Db = Dinv + ((long)b * nblk + bi) * NB * NB;
     f64x4_t out[4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      out[a] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+    for (int a = 0; a < 4; ++a) out[a] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+    // step (x, v) contracts k = 16x + 4v + kq, the row acc[x][v] holds in this lane; the inverse block is stored
+    // with its columns permuted so that the four v of a group are contiguous.  Two groups of loads in flight.
 #pragma unroll
-      for (int x = 0; x < 4; ++x)
+    for (int xh = 0; xh < 4; xh += 2) {
+      f64x4_t da[2][4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v)   // this step contracts k = 16x + 4v + kq, the row acc[x][v] holds in this lane
-          out[a] = __builtin_amdgcn_mfma_f64_16x16x4f64(Db[(16 * a + i16) * NB + 16 * x + 4 * v + kq], acc[x][v], out[a], 0, 0, 0);
+      for (int xx = 0; xx < 2; ++xx)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) da[xx][a] = *(const f64x4_t*)(Db + (16 * a + i16) * NB + 16 * (xh + xx) + 4 * kq);
+#pragma unroll
+      for (int xx = 0; xx < 2; ++xx)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+          for (int a = 0; a < 4; ++a) out[a] = __builtin_amdgcn_mfma_f64_16x16x4f64(da[xx][a][v], acc[xh + xx][v], out[a], 0, 0, 0);
     }
 #pragma unroll
     for (int a = 0; a < 4; ++a)
