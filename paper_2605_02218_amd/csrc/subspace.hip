@@ -141,6 +141,7 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
         const int m = e >> (2 * ls), i = (e >> ls) & (s_ - 1), j = e & (s_ - 1);
         const int base = 2 * s_ * m;
         double t1 = 0.0;   // (C inv(A))[i][j], inv(A) lower triangular
+#pragma unroll 8
         for (int t = j; t < s_; ++t) t1 = fma(fac[(base + s_ + i) * NBP + base + t], a[(base + t) * NBP + base + j], t1);
         fac[(base + j) * NBP + base + s_ + i] = t1;
       }
@@ -149,6 +150,7 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
         const int m = e >> (2 * ls), i = (e >> ls) & (s_ - 1), j = e & (s_ - 1);
         const int base = 2 * s_ * m;
         double x = 0.0;    // (inv(D) T1)[i][j], inv(D) lower triangular
+#pragma unroll 8
         for (int u = 0; u <= i; ++u) x = fma(a[(base + s_ + i) * NBP + base + s_ + u], fac[(base + j) * NBP + base + s_ + u], x);
         a[(base + s_ + i) * NBP + base + j] = -x;
       }
