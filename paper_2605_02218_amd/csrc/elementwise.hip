@@ -178,7 +178,8 @@ __global__ __launch_bounds__(256) void cosine_max_kernel(const F* __restrict__ l
 }
 
 // ---------------------------------------------------------------- softmax relevance (variant)
-// stats[row] = (max_i scale*S[row,i], sum_i exp(scale*S[row,i] - max)); one wave per row.
+// stats[row] = (max_i scale*S[row,i], 1 / sum_i exp(scale*S[row,i] - max)); one wave per row, one pass: every
+// lane keeps a running (maximum, sum) of its elements and rescales the sum when the maximum moves.
 template <typename F>
 __global__ __launch_bounds__(256) void softmax_stats_kernel(const F* __restrict__ S, double2* __restrict__ stats,
                                                              long rows, int N, double scale) {
@@ -187,15 +188,20 @@ __global__ __launch_bounds__(256) void softmax_stats_kernel(const F* __restrict_
   if (row >= rows) return;
   const F* p = S + row * (long)N;
   F m = -INFINITY;
-  for (int i = lane; i < N; i += 64) { const F v = p[i] * (F)scale; m = v > m ? v : m; }
-  m = wave_max(m);
   double z = 0.0;
-  for (int i = lane; i < N; i += 64) z += (double)exp(p[i] * (F)scale - m);
+  for (int i = lane; i < N; i += 64) {
+    const F v = p[i] * (F)scale;
+    if (v > m) { z *= (double)exp(m - v); m = v; }      // m = -inf at first: exp(-inf) = 0
+    z += (double)exp(v - m);
+  }
+  const F mw = wave_max(m);
+  z *= (m == -INFINITY) ? 0.0 : (double)exp(m - mw);
   z = wave_sum(z);
-  if (lane == 0) stats[row] = make_double2((double)m, z);
+  if (lane == 0) stats[row] = make_double2((double)mw, 1.0 / z);
 }
 
-// s_query[b,i] = (1/HT) sum_{row < HT} exp(scale*S[b,row,i] - max_row) / Z_row, rows added in order.
+// s_query[b,i] = (1/HT) sum_{row < HT} exp(scale*S[b,row,i] - max_row) / Z_row, rows added in order (four
+// interleaved partial sums, so that four loads are in flight).
 template <typename F>
 __global__ __launch_bounds__(256) void softmax_mean_kernel(const F* __restrict__ S, const double2* __restrict__ stats,
                                                             float* __restrict__ s_query, int HT, int N, double scale) {
@@ -204,12 +210,23 @@ __global__ __launch_bounds__(256) void softmax_mean_kernel(const F* __restrict__
   if (i >= N) return;
   const F* p = S + (long)b * HT * N + i;
   const double2* st = stats + (long)b * HT;
-  double acc = 0.0;
-  for (int r = 0; r < HT; ++r) {
-    const double2 mz = st[r];
-    acc += (double)exp(p[(long)r * N] * (F)scale - (F)mz.x) / mz.y;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  int r = 0;
+  for (; r + 4 <= HT; r += 4) {
+    F v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = p[(long)(r + u) * N];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const double2 mz = st[r + u];
+      acc[u] = fma((double)exp(v[u] * (F)scale - (F)mz.x), mz.y, acc[u]);
+    }
   }
-  s_query[(long)b * N + i] = (float)(acc / HT);
+  for (; r < HT; ++r) {
+    const double2 mz = st[r];
+    acc[0] = fma((double)exp(p[(long)r * N] * (F)scale - (F)mz.x), mz.y, acc[0]);
+  }
+  s_query[(long)b * N + i] = (float)(((acc[0] + acc[1]) + (acc[2] + acc[3])) / HT);
 }
 
 // ---------------------------------------------------------------- min-max + fuse (paper fusion equation)
