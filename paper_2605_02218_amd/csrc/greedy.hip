@@ -142,8 +142,9 @@ __global__ __launch_bounds__(GT) void greedy_kernel(const double* __restrict__ G
   }
 }
 
-// One 1024-thread workgroup per image (no barriers between workgroups): the better choice when the batch
-// alone fills the device.
+// One 1024-thread workgroup per image (no barriers between workgroups), left-looking: used when the batch alone
+// fills the device and the blocked kernel below does not apply (more than 1024 rows, or a block of columns that
+// does not fit LDS).
 constexpr int RPT = 4;  // rows per thread: n <= 4096
 
 __global__ __launch_bounds__(TPB) void greedy_single_kernel(const double* __restrict__ G, int n, int nP, int k,
@@ -240,6 +241,93 @@ __global__ __launch_bounds__(TPB) void greedy_single_kernel(const double* __rest
   }
 }
 
+// One 1024-thread workgroup per image, n <= 1024 (thread i owns row i), right-looking in blocks of 16 picks: the
+// residual matrix R = G - L L^T is kept in global memory IN PLACE of G and brought up to date once per block by
+// a rank-16 update on the MFMA; inside a block a new column is the pivot's row of R minus the product with the
+// block's at most 15 earlier columns, which live in LDS.  The left-looking kernel above re-reads every earlier
+// column at every step (k^2 n / 2 values from L2); this one reads one row of R per step and reads and writes R
+// once per block.  Dynamic LDS: 16 * nP doubles.
+constexpr int GBK = 16;
+
+__global__ __launch_bounds__(TPB) void greedy_blocked_kernel(double* __restrict__ G, int n, int nP, int k, int32_t* __restrict__ order,
+                                                              float* __restrict__ resid) {
+  extern __shared__ double Lblk[];        // [GBK][nP]: column jj of the current block, all rows
+  __shared__ unsigned long long red[16];
+  __shared__ double sh_piv;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i16 = lane & 15, kq = lane >> 4;
+  double* R = G + (long)b * nP * nP;
+  const bool mine = tid < n;
+  double rho = mine ? R[(long)tid * nP + tid] : 0.0;
+  bool picked = !mine;
+  for (int e = tid; e < GBK * nP; e += TPB) Lblk[e] = 0.0;
+  __syncthreads();
+
+  for (int t = 0; t < k; ++t) {
+    const int jj = t & (GBK - 1);
+    // ---- argmax over the unpicked rows of float(rho), lowest index on ties
+    unsigned long long best = 0ull;
+    if (!picked) best = ((unsigned long long)float_order_key((float)rho) << 32) | (0xFFFFFFFFu - (uint32_t)tid);
+    best = wave_max(best);
+    if (lane == 0) red[w] = best;
+    __syncthreads();
+    best = red[0];
+#pragma unroll
+    for (int q = 1; q < TPB / 64; ++q) best = red[q] > best ? red[q] : best;
+    const int p = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));     // < n: k <= n, so an unpicked row exists
+    if (tid == p) { sh_piv = rho; picked = true; }
+    // ---- the pivot's row of R (R is symmetric: its column), minus what this block has already taken out
+    double c = mine ? R[(long)p * nP + tid] : 0.0;
+    if (mine)
+      for (int q = 0; q < jj; ++q) c = fma(-Lblk[q * nP + tid], Lblk[q * nP + p], c);
+    __syncthreads();        // sh_piv written; red may be rewritten next step
+    const double rp = sh_piv;
+    const double piv = rp > 0.0 ? rp : 0.0;
+    const double col = (piv > 0.0 && mine) ? c / sqrt(piv) : 0.0;
+    if (tid < nP) Lblk[jj * nP + tid] = col;
+    rho -= col * col;
+    if (tid == 0) { order[(long)b * k + t] = p; resid[(long)b * k + t] = (float)rp; }
+    __syncthreads();        // the column is visible to the next step's products
+    // ---- end of a block: R -= Lblk^T Lblk on the MFMA (16 x 16 tiles, contraction over the 16 columns), then
+    //      the block's columns are cleared
+    if (jj == GBK - 1 && t + 1 < k) {
+      const int nt = (n + 15) >> 4, ntiles = nt * nt;
+      // four tiles per trip: their 16 values of R are requested before the first MFMA
+      for (int tile0 = w; tile0 < ntiles; tile0 += 4 * (TPB / 64)) {
+        double* out[4];
+        double r[4][4];
+        int ti[4], tj[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int tile = tile0 + u * (TPB / 64);
+          const int tc = tile < ntiles ? tile : tile0;          // a trailing slot repeats the first tile, result unused
+          ti[u] = tc / nt;
+          tj[u] = tc - ti[u] * nt;
+          // lane (i16, kq), register v: row 16 ti + 4v + kq, column 16 tj + i16 (inside the nP x nP buffer: nP % 64 == 0)
+          out[u] = R + (long)(16 * ti[u] + kq) * nP + 16 * tj[u] + i16;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) r[u][v] = out[u][(long)(4 * v) * nP];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          f64x4_t d = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+          for (int s4 = 0; s4 < GBK / 4; ++s4)
+            d = __builtin_amdgcn_mfma_f64_16x16x4f64(Lblk[(4 * s4 + kq) * nP + 16 * ti[u] + i16], Lblk[(4 * s4 + kq) * nP + 16 * tj[u] + i16], d,
+                                                     0, 0, 0);
+          if (tile0 + u * (TPB / 64) < ntiles) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) out[u][(long)(4 * v) * nP] = r[u][v] - d[v];
+          }
+        }
+      }
+      __syncthreads();
+      for (int e = tid; e < GBK * nP; e += TPB) Lblk[e] = 0.0;
+      __threadfence_block();
+      __syncthreads();
+    }
+  }
+}
+
 // idx_out[b,:] = ascending positions idx_m[b, picked]; pick_out[b,t] = idx_m[b, order[b,t]]
 __global__ __launch_bounds__(TPB) void greedy_finish_kernel(const int32_t* __restrict__ order, const int32_t* __restrict__ idx_m,
                                                              int M, int k, int32_t* __restrict__ idx_out,
@@ -272,13 +360,24 @@ size_t greedy_scratch_bytes(int B, int nP) {
   return (size_t)B * sizeof(GreedyCtl) + 256 + (size_t)B * 4 * (nP / GR) * 8;
 }
 
-hipError_t launch_greedy(const double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
+hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
                          hipStream_t st) {
   if (nP % GR != 0 || n > nP || n > 4096 || k > n || k > 4096) return hipErrorInvalidValue;
   const int W = nP / GR;
   // Spreading an image over W workgroups costs a device-scope barrier per step; it pays while the batch
   // leaves most of the device idle (measured: B = 4 and 8 gain 3-7x, B = 64 loses 2.5x).
   if ((long)B * W > 256) {
+    const size_t blk_lds = (size_t)GBK * nP * sizeof(double);
+    if (n <= TPB && blk_lds <= 128 * 1024) {
+      static bool raised = false;
+      if (!raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)greedy_blocked_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+      }
+      hipLaunchKernelGGL(greedy_blocked_kernel, dim3(B), dim3(TPB), blk_lds, st, G, n, nP, k, order, resid);
+      return hipGetLastError();
+    }
     hipLaunchKernelGGL(greedy_single_kernel, dim3(B), dim3(TPB), 0, st, G, n, nP, k, Lt, order, resid);
     return hipGetLastError();
   }

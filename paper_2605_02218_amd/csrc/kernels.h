@@ -139,11 +139,12 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
                                  hipStream_t stream);
 
 // ---------------------------------------------------------------- greedy.hip
-// Greedy residual picks (variant): pivoted Cholesky of G[b] (fp64, pitch nP).  Lt is scratch [B][k][nP] fp64.
+// Greedy residual picks (variant): pivoted Cholesky of G[b] (fp64, pitch nP; G may be overwritten with the residual
+// matrix).  Lt is scratch [B][k][nP] fp64.
 // order[b,t] = local position picked at step t, resid[b,t] = residual squared norm at that pick.
 // nP % 64 == 0; `scratch` holds greedy_scratch_bytes(B, nP) bytes (barrier counters and per-step posts).
 size_t greedy_scratch_bytes(int B, int nP);
-hipError_t launch_greedy(const double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
+hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
                          hipStream_t stream);
 // idx_out[b,:] = sort ascending of idx_m[b, order[b,:]];  pick_out[b,t] = idx_m[b, order[b,t]] (optional).
 hipError_t launch_greedy_finish(const int32_t* order, const int32_t* idx_m, int B, int M, int k, int32_t* idx_out,

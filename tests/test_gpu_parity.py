@@ -277,6 +277,27 @@ def test_eigen_solve_ladder_by_spectral_decay(C, decay, path):
         np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"], err_msg="margin_topk=%r" % ref.get("margin_topk"))
 
 
+@pytest.mark.parametrize("k", [37, 100])
+def test_greedy_blocked_kernel_on_a_large_batch_of_small_images(C, k):
+    """Many images (batch x row blocks > 256 workgroups) take the one-workgroup-per-image kernel that works in
+    blocks of 16 picks; 100 tokens and k = 37 leave ragged 16-tiles and a partial last block, k = 100 picks
+    every token.  Pick order, residuals and kept set against the oracle."""
+    import torch
+    w = I.small_workload(cid=16, name="manysmall", batch=130, n_tokens=100, d_model=128, dtype=I.FP32, n_query=2, n_heads=1,
+                         keep_k=k, preselect_m=100, rank_r=8, factor_rank=120, n_act_layers=0)
+    batch = U.gen_batch(w)
+    X = torch.from_numpy(batch["X"]).cuda()
+    sf = torch.from_numpy(np.random.default_rng(1).random((w.batch, w.n_tokens)).astype(np.float32)).cuda()
+    p = U.lib_params(C, w, w.batch, lr_mode=C.LR_GREEDY_RESIDUAL)
+    out = C.select(p, X, sf)
+    op = U.oracle_params(w, lr_mode=1)
+    for b in (0, 1, 64, 129):
+        ref = O.select(batch["X"][b].astype(np.float64), _cpu(sf)[b], op)
+        np.testing.assert_array_equal(_cpu(out["pick_order"])[b], ref["pick_order"], err_msg="image %d" % b)
+        U.assert_scores_close(_cpu(out["resid"])[b], ref["resid"], I.FP32, "resid[%d]" % b, tol=1e-5)
+        np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"])
+
+
 def test_select_ties_and_exact_duplicates(C):
     import torch
     # constant fused scores: every cut is a tie -> the first M positions; duplicates tie in the energy ranking
