@@ -143,8 +143,7 @@ __global__ __launch_bounds__(GT) void greedy_kernel(const double* __restrict__ G
 }
 
 // One 1024-thread workgroup per image (no barriers between workgroups), left-looking: used when the batch alone
-// fills the device and the blocked kernel below does not apply (more than 1024 rows, or a block of columns that
-// does not fit LDS).
+// fills the device and the picks are a small part of the rows (see the right-looking kernel below).
 constexpr int RPT = 4;  // rows per thread: n <= 4096
 
 __global__ __launch_bounds__(TPB) void greedy_single_kernel(const double* __restrict__ G, int n, int nP, int k,
@@ -241,32 +240,59 @@ __global__ __launch_bounds__(TPB) void greedy_single_kernel(const double* __rest
   }
 }
 
-// One 1024-thread workgroup per image, n <= 1024 (thread i owns row i), right-looking in blocks of 16 picks: the
-// residual matrix R = G - L L^T is kept in global memory IN PLACE of G and brought up to date once per block by
-// a rank-16 update on the MFMA; inside a block a new column is the pivot's row of R minus the product with the
-// block's at most 15 earlier columns, which live in LDS.  The left-looking kernel above re-reads every earlier
-// column at every step (k^2 n / 2 values from L2); this one reads one row of R per step and reads and writes R
-// once per block.  Dynamic LDS: 16 * nP doubles.
-constexpr int GBK = 16;
-
-__global__ __launch_bounds__(TPB) void greedy_blocked_kernel(double* __restrict__ G, int n, int nP, int k, int32_t* __restrict__ order,
-                                                              float* __restrict__ resid) {
-  extern __shared__ double Lblk[];        // [GBK][nP]: column jj of the current block, all rows
+// Right-looking in blocks of BK picks, an image of up to 4096 rows spread over W workgroups of 1024 threads (thread
+// tid owns the NR rows tid, tid + 1024, ...).  The residual matrix R = G - L L^T is kept in global memory IN PLACE of G and
+// brought up to date once per block by a rank-BK update on the MFMA; inside a block a new column is the pivot's
+// row of R minus the product with the block's earlier columns, which live in LDS.  The left-looking kernels above
+// re-read every earlier column at every step (k^2 n / 2 values); this one reads one row of R per step and reads
+// and writes R once per block (2 n^2 k / BK values), which is less unless k is a small part of n.
+// Every workgroup of the image runs the BK picks of a block redundantly (same loads, same arithmetic, hence the
+// same decisions: nothing is exchanged), then the workgroups meet at the image's barrier, each brings its own
+// 16-row bands of R up to date, and they meet again before the next block reads rows of R: two barriers per
+// block instead of one per pick, and the device's bandwidth on the update instead of one workgroup's.
+// Dynamic LDS: BK * nP doubles; workgroups take (image, slot) from the ticket counter.
+template <int BK, int NR>
+__global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int nP, int k, int W, int32_t* __restrict__ order,
+                                                            float* __restrict__ resid, GreedyCtl* ctl) {
+  extern __shared__ double Lblk[];        // [BK][nP]
   __shared__ unsigned long long red[16];
   __shared__ double sh_piv;
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i16 = lane & 15, kq = lane >> 4;
+  __shared__ int s_flag;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i16 = lane & 15, kq = lane >> 4;
+  if (tid == 0) s_flag = (int)atomicAdd(&ctl[0].ticket, 1u);
+  __syncthreads();
+  const int ticket = s_flag;
+  __syncthreads();
+  const int b = ticket / W, slot = ticket - b * W;
+  GreedyCtl* cb = ctl + b;
   double* R = G + (long)b * nP * nP;
-  const bool mine = tid < n;
-  double rho = mine ? R[(long)tid * nP + tid] : 0.0;
-  bool picked = !mine;
-  for (int e = tid; e < GBK * nP; e += TPB) Lblk[e] = 0.0;
+
+  double rho[NR];
+  bool picked[NR];
+#pragma unroll
+  for (int s = 0; s < NR; ++s) {
+    const int i = tid + TPB * s;
+    rho[s] = (i < n) ? R[(long)i * nP + i] : 0.0;
+    picked[s] = !(i < n);
+  }
+  for (int e = tid; e < BK * nP; e += TPB) Lblk[e] = 0.0;
+  unsigned int target = 0;
+  bool alive = true;
+  // the diagonal is read above and R is first written at the end of block 0, behind a barrier
   __syncthreads();
 
   for (int t = 0; t < k; ++t) {
-    const int jj = t & (GBK - 1);
+    const int jj = t & (BK - 1);
     // ---- argmax over the unpicked rows of float(rho), lowest index on ties
     unsigned long long best = 0ull;
-    if (!picked) best = ((unsigned long long)float_order_key((float)rho) << 32) | (0xFFFFFFFFu - (uint32_t)tid);
+#pragma unroll
+    for (int s = 0; s < NR; ++s) {
+      if (!picked[s]) {
+        const unsigned long long key =
+            ((unsigned long long)float_order_key((float)rho[s]) << 32) | (0xFFFFFFFFu - (uint32_t)(tid + TPB * s));
+        best = key > best ? key : best;
+      }
+    }
     best = wave_max(best);
     if (lane == 0) red[w] = best;
     __syncthreads();
@@ -274,34 +300,73 @@ __global__ __launch_bounds__(TPB) void greedy_blocked_kernel(double* __restrict_
 #pragma unroll
     for (int q = 1; q < TPB / 64; ++q) best = red[q] > best ? red[q] : best;
     const int p = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));     // < n: k <= n, so an unpicked row exists
-    if (tid == p) { sh_piv = rho; picked = true; }
-    // ---- the pivot's row of R (R is symmetric: its column), minus what this block has already taken out
-    double c = mine ? R[(long)p * nP + tid] : 0.0;
-    if (mine)
-      for (int q = 0; q < jj; ++q) c = fma(-Lblk[q * nP + tid], Lblk[q * nP + p], c);
+    if ((unsigned)p >= (unsigned)n) {   // never index with anything else
+      if (tid == 0) __hip_atomic_store(&cb->bar.failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      alive = false;
+      break;
+    }
+    if ((p & (TPB - 1)) == tid) {
+#pragma unroll
+      for (int s = 0; s < NR; ++s)
+        if (s == (p >> 10)) { sh_piv = rho[s]; picked[s] = true; }
+    }
+    // ---- the pivot's row of R, minus what this block has already taken out (summed apart, so that the sum
+    //      does not wait for the row)
+    double c[NR];
+#pragma unroll
+    for (int s = 0; s < NR; ++s) {
+      const int i = tid + TPB * s;
+      c[s] = (i < n) ? R[(long)p * nP + i] : 0.0;
+    }
+    {
+      double taken[NR];
+#pragma unroll
+      for (int s = 0; s < NR; ++s) taken[s] = 0.0;
+      for (int q = 0; q < jj; ++q) {
+        const double lp = Lblk[q * nP + p];
+#pragma unroll
+        for (int s = 0; s < NR; ++s) {
+          const int i = tid + TPB * s;
+          if (i < n) taken[s] = fma(Lblk[q * nP + i], lp, taken[s]);
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < NR; ++s) c[s] -= taken[s];
+    }
     __syncthreads();        // sh_piv written; red may be rewritten next step
     const double rp = sh_piv;
     const double piv = rp > 0.0 ? rp : 0.0;
-    const double col = (piv > 0.0 && mine) ? c / sqrt(piv) : 0.0;
-    if (tid < nP) Lblk[jj * nP + tid] = col;
-    rho -= col * col;
-    if (tid == 0) { order[(long)b * k + t] = p; resid[(long)b * k + t] = (float)rp; }
+    const double root = sqrt(piv);
+#pragma unroll
+    for (int s = 0; s < NR; ++s) {
+      const int i = tid + TPB * s;
+      const double col = (piv > 0.0 && i < n) ? c[s] / root : 0.0;
+      if (i < nP) Lblk[jj * nP + i] = col;
+      rho[s] -= col * col;
+    }
+    if (slot == 0 && tid == 0) { order[(long)b * k + t] = p; resid[(long)b * k + t] = (float)rp; }
     __syncthreads();        // the column is visible to the next step's products
-    // ---- end of a block: R -= Lblk^T Lblk on the MFMA (16 x 16 tiles, contraction over the 16 columns), then
-    //      the block's columns are cleared
-    if (jj == GBK - 1 && t + 1 < k) {
-      const int nt = (n + 15) >> 4, ntiles = nt * nt;
-      // four tiles per trip: their 16 values of R are requested before the first MFMA
-      for (int tile0 = w; tile0 < ntiles; tile0 += 4 * (TPB / 64)) {
+    if (jj == BK - 1 && t + 1 < k) {
+      // every workgroup of the image has read its last row of the old R
+      target += (unsigned int)W;
+      alive = image_barrier_wait(&cb->bar, target, &s_flag);
+      if (!alive) break;
+      // ---- R -= Lblk^T Lblk on this workgroup's bands (band ti belongs to slot ti % W); a wave takes four
+      //      neighbouring 16 x 16 tiles per trip and requests their 16 values of R before the first MFMA
+      const int nt = (n + 15) >> 4;
+      const int bands = (nt - slot + W - 1) / W;
+      const int ntiles = bands * nt;
+      for (int tile0 = 4 * w; tile0 < ntiles; tile0 += 4 * (TPB / 64)) {
         double* out[4];
         double r[4][4];
         int ti[4], tj[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int tile = tile0 + u * (TPB / 64);
+          const int tile = tile0 + u;
           const int tc = tile < ntiles ? tile : tile0;          // a trailing slot repeats the first tile, result unused
-          ti[u] = tc / nt;
-          tj[u] = tc - ti[u] * nt;
+          const int band = tc / nt;
+          ti[u] = slot + band * W;
+          tj[u] = tc - band * nt;
           // lane (i16, kq), register v: row 16 ti + 4v + kq, column 16 tj + i16 (inside the nP x nP buffer: nP % 64 == 0)
           out[u] = R + (long)(16 * ti[u] + kq) * nP + 16 * tj[u] + i16;
 #pragma unroll
@@ -311,20 +376,27 @@ __global__ __launch_bounds__(TPB) void greedy_blocked_kernel(double* __restrict_
         for (int u = 0; u < 4; ++u) {
           f64x4_t d = (f64x4_t){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-          for (int s4 = 0; s4 < GBK / 4; ++s4)
+          for (int s4 = 0; s4 < BK / 4; ++s4)
             d = __builtin_amdgcn_mfma_f64_16x16x4f64(Lblk[(4 * s4 + kq) * nP + 16 * ti[u] + i16], Lblk[(4 * s4 + kq) * nP + 16 * tj[u] + i16], d,
                                                      0, 0, 0);
-          if (tile0 + u * (TPB / 64) < ntiles) {
+          if (tile0 + u < ntiles) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) out[u][(long)(4 * v) * nP] = r[u][v] - d[v];
           }
         }
       }
-      __syncthreads();
-      for (int e = tid; e < GBK * nP; e += TPB) Lblk[e] = 0.0;
-      __threadfence_block();
+      // every band is up to date before any workgroup reads a row of R again
+      target += (unsigned int)W;
+      alive = image_barrier_wait(&cb->bar, target, &s_flag);
+      if (!alive) break;
+      for (int e = tid; e < BK * nP; e += TPB) Lblk[e] = 0.0;
       __syncthreads();
     }
+  }
+  if (!alive && slot == 0) {
+    // a wait ran out: leave valid (distinct) positions and poisoned residuals behind
+    const float qnan = __uint_as_float(0x7fc00000u);
+    for (int t = tid; t < k; t += TPB) { order[(long)b * k + t] = t; resid[(long)b * k + t] = qnan; }
   }
 }
 
@@ -360,24 +432,56 @@ size_t greedy_scratch_bytes(int B, int nP) {
   return (size_t)B * sizeof(GreedyCtl) + 256 + (size_t)B * 4 * (nP / GR) * 8;
 }
 
+template <int BK, int NR>
+static hipError_t launch_panel(double* G, int B, int n, int nP, int k, int W, int32_t* order, float* resid, GreedyCtl* ctl,
+                               hipStream_t st) {
+  const size_t lds = (size_t)BK * nP * sizeof(double);
+  static size_t raised = 0;
+  if (lds > raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)greedy_panel_kernel<BK, NR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    raised = lds;
+  }
+  // the workgroups of one image wait for one another, so one image has to fit the device
+  int dev = 0, per_cu = 0, cus = 0;
+  hipError_t e;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+  if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (greedy_panel_kernel<BK, NR>), TPB, lds)) != hipSuccess) return e;
+  if (per_cu < 1 || cus < 1 || W > per_cu * cus) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(greedy_init_kernel, dim3((B + 255) / 256), dim3(256), 0, st, ctl, B);
+  hipLaunchKernelGGL((greedy_panel_kernel<BK, NR>), dim3((unsigned)(B * W)), dim3(TPB), lds, st, G, n, nP, k, W, order, resid, ctl);
+  return hipGetLastError();
+}
+
 hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
                          hipStream_t st) {
   if (nP % GR != 0 || n > nP || n > 4096 || k > n || k > 4096) return hipErrorInvalidValue;
+  GreedyCtl* ctl = (GreedyCtl*)scratch;
+  // the largest block of picks whose columns fit LDS
+  const size_t lds_cap = 150 * 1024;
+  const int BK = (size_t)16 * nP * 8 <= lds_cap ? 16 : (size_t)8 * nP * 8 <= lds_cap ? 8 : 4;
+  // values moved: the right-looking kernel reads and writes R once per block that is followed by another, the
+  // left-looking ones read every earlier column at every step; the former also has far fewer barriers
+  const double right = (double)((k - 1) / BK) * 2.0 * n * n, left = 0.5 * k * k * n;
+  if (right <= 2.0 * left) {
+    // workgroups per image: measured best with about 128 on the device, at most 32 and (while they fit) at least 4 per image
+    const int nt = (n + 15) / 16;
+    int Wp = 128 / B;
+    if (Wp < 4) Wp = 256 / B < 4 ? 256 / B : 4;
+    Wp = Wp < 1 ? 1 : Wp > 32 ? 32 : Wp;
+    Wp = Wp > nt ? nt : Wp;
+    // rows per thread: nP <= 1200 with blocks of 16, <= 2400 with blocks of 8
+    if (BK == 16) return n <= TPB ? launch_panel<16, 1>(G, B, n, nP, k, Wp, order, resid, ctl, st)
+                                  : launch_panel<16, 2>(G, B, n, nP, k, Wp, order, resid, ctl, st);
+    if (BK == 8) return n <= 2 * TPB ? launch_panel<8, 2>(G, B, n, nP, k, Wp, order, resid, ctl, st)
+                                     : launch_panel<8, 4>(G, B, n, nP, k, Wp, order, resid, ctl, st);
+    return launch_panel<4, 4>(G, B, n, nP, k, Wp, order, resid, ctl, st);
+  }
   const int W = nP / GR;
-  // Spreading an image over W workgroups costs a device-scope barrier per step; it pays while the batch
-  // leaves most of the device idle (measured: B = 4 and 8 gain 3-7x, B = 64 loses 2.5x).
+  // Left-looking: spreading an image over W workgroups costs a device-scope barrier per step; it pays while the
+  // batch leaves most of the device idle.
   if ((long)B * W > 256) {
-    const size_t blk_lds = (size_t)GBK * nP * sizeof(double);
-    if (n <= TPB && blk_lds <= 128 * 1024) {
-      static bool raised = false;
-      if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)greedy_blocked_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-      }
-      hipLaunchKernelGGL(greedy_blocked_kernel, dim3(B), dim3(TPB), blk_lds, st, G, n, nP, k, order, resid);
-      return hipGetLastError();
-    }
     hipLaunchKernelGGL(greedy_single_kernel, dim3(B), dim3(TPB), 0, st, G, n, nP, k, Lt, order, resid);
     return hipGetLastError();
   }
@@ -393,7 +497,6 @@ hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int
     capacity = per_cu * cus;
   }
   if (W > capacity) return hipErrorInvalidValue;
-  GreedyCtl* ctl = (GreedyCtl*)scratch;
   unsigned long long* posts = (unsigned long long*)((char*)scratch + (((size_t)B * sizeof(GreedyCtl) + 255) / 256) * 256);
   hipLaunchKernelGGL(greedy_init_kernel, dim3((B + 255) / 256), dim3(256), 0, st, ctl, B);
   hipLaunchKernelGGL(greedy_kernel, dim3((unsigned)(B * W)), dim3(GT), 0, st, G, n, nP, k, Lt, order, resid, ctl, posts);

@@ -278,10 +278,10 @@ def test_eigen_solve_ladder_by_spectral_decay(C, decay, path):
 
 
 @pytest.mark.parametrize("k", [37, 100])
-def test_greedy_blocked_kernel_on_a_large_batch_of_small_images(C, k):
-    """Many images (batch x row blocks > 256 workgroups) take the one-workgroup-per-image kernel that works in
-    blocks of 16 picks; 100 tokens and k = 37 leave ragged 16-tiles and a partial last block, k = 100 picks
-    every token.  Pick order, residuals and kept set against the oracle."""
+def test_greedy_picks_on_a_large_batch_of_small_images(C, k):
+    """With more images than workgroups that the greedy kernel wants on the device, every image gets a single
+    workgroup (no waiting between workgroups); 100 tokens and k = 37 leave ragged 16-tiles and a partial last block
+    of 16 picks, k = 100 picks every token.  Pick order, residuals and kept set against the oracle."""
     import torch
     w = I.small_workload(cid=16, name="manysmall", batch=130, n_tokens=100, d_model=128, dtype=I.FP32, n_query=2, n_heads=1,
                          keep_k=k, preselect_m=100, rank_r=8, factor_rank=120, n_act_layers=0)
@@ -294,6 +294,32 @@ def test_greedy_blocked_kernel_on_a_large_batch_of_small_images(C, k):
     for b in (0, 1, 64, 129):
         ref = O.select(batch["X"][b].astype(np.float64), _cpu(sf)[b], op)
         np.testing.assert_array_equal(_cpu(out["pick_order"])[b], ref["pick_order"], err_msg="image %d" % b)
+        U.assert_scores_close(_cpu(out["resid"])[b], ref["resid"], I.FP32, "resid[%d]" % b, tol=1e-5)
+        np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"])
+
+
+@pytest.mark.parametrize("B,n,d,k,why", [
+    (3, 1100, 320, 150, "two rows per thread, blocks of 16 picks, 32 workgroups per image"),
+    (2, 1300, 704, 330, "blocks of 8 picks (16 columns of 1344 rows do not fit LDS)"),
+    (1, 2500, 2560, 1260, "four rows per thread, blocks of 4 picks"),
+    (2, 1500, 256, 40, "few picks out of many rows: the left-looking kernel on several workgroups"),
+], ids=["rows2-block16", "rows2-block8", "rows4-block4", "left-looking"])
+def test_greedy_picks_on_large_images(C, B, n, d, k, why):
+    """Images above 1024 rows: the greedy kernel keeps several rows per thread, shrinks its block of picks to what
+    LDS holds, and falls back to the left-looking scheme when the picks are a small part of the rows.  Pick order,
+    residuals and kept set against the oracle for every image."""
+    import torch
+    w = I.small_workload(cid=17, name="greedy-large", batch=B, n_tokens=n, d_model=d, dtype=I.FP32, n_query=2, n_heads=1,
+                         keep_k=k, preselect_m=n, rank_r=8, factor_rank=min(d, n) - 8, n_act_layers=0)
+    batch = U.gen_batch(w)
+    X = torch.from_numpy(batch["X"]).cuda()
+    sf = torch.from_numpy(np.random.default_rng(2).random((B, n)).astype(np.float32)).cuda()
+    p = U.lib_params(C, w, B, lr_mode=C.LR_GREEDY_RESIDUAL)
+    out = C.select(p, X, sf)
+    op = U.oracle_params(w, lr_mode=1)
+    for b in range(B):
+        ref = O.select(batch["X"][b].astype(np.float64), _cpu(sf)[b], op)
+        np.testing.assert_array_equal(_cpu(out["pick_order"])[b], ref["pick_order"], err_msg="image %d (%s)" % (b, why))
         U.assert_scores_close(_cpu(out["resid"])[b], ref["resid"], I.FP32, "resid[%d]" % b, tol=1e-5)
         np.testing.assert_array_equal(_cpu(out["idx"])[b], ref["idx"])
 
