@@ -245,7 +245,7 @@ __global__ __launch_bounds__(TPB) void greedy_single_kernel(const double* __rest
 // brought up to date once per block by a rank-BK update on the MFMA; inside a block a new column is the pivot's
 // row of R minus the product with the block's earlier columns, which live in LDS.  The left-looking kernels above
 // re-read every earlier column at every step (k^2 n / 2 values); this one reads one row of R per step and reads
-// and writes R once per block (2 n^2 k / BK values), which is less unless k is a small part of n.
+// and writes R once per block (up to 2 n^2 k / BK values), which is less unless k is a small part of n.
 // Every workgroup of the image runs the BK picks of a block redundantly (same loads, same arithmetic, hence the
 // same decisions: nothing is exchanged), then the workgroups meet at the image's barrier, each brings its own
 // 16-row bands of R up to date, and they meet again before the next block reads rows of R: two barriers per
@@ -282,7 +282,7 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
   __syncthreads();
 
   for (int t = 0; t < k; ++t) {
-    const int jj = t & (BK - 1);
+    const int jj = t % BK;
     // ---- argmax over the unpicked rows of float(rho), lowest index on ties
     unsigned long long best = 0ull;
 #pragma unroll
@@ -458,9 +458,10 @@ hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int
                          hipStream_t st) {
   if (nP % GR != 0 || n > nP || n > 4096 || k > n || k > 4096) return hipErrorInvalidValue;
   GreedyCtl* ctl = (GreedyCtl*)scratch;
-  // the largest block of picks whose columns fit LDS
-  const size_t lds_cap = 150 * 1024;
-  const int BK = (size_t)16 * nP * 8 <= lds_cap ? 16 : (size_t)8 * nP * 8 <= lds_cap ? 8 : 4;
+  // the largest block of picks (a multiple of the MFMA's depth of 4) whose columns fit LDS beside the kernel's few
+  // static words
+  const size_t lds_cap = 159 * 1024;
+  const int BK = (size_t)16 * nP * 8 <= lds_cap ? 16 : (size_t)12 * nP * 8 <= lds_cap ? 12 : (size_t)8 * nP * 8 <= lds_cap ? 8 : 4;
   // values moved: the right-looking kernel reads and writes R once per block that is followed by another, the
   // left-looking ones read every earlier column at every step; the former also has far fewer barriers
   const double right = (double)((k - 1) / BK) * 2.0 * n * n, left = 0.5 * k * k * n;
@@ -471,9 +472,10 @@ hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int
     if (Wp < 4) Wp = 256 / B < 4 ? 256 / B : 4;
     Wp = Wp < 1 ? 1 : Wp > 32 ? 32 : Wp;
     Wp = Wp > nt ? nt : Wp;
-    // rows per thread: nP <= 1200 with blocks of 16, <= 2400 with blocks of 8
+    // rows per thread: at most 1216 rows with blocks of 16, 1664 with 12, 2496 with 8
     if (BK == 16) return n <= TPB ? launch_panel<16, 1>(G, B, n, nP, k, Wp, order, resid, ctl, st)
                                   : launch_panel<16, 2>(G, B, n, nP, k, Wp, order, resid, ctl, st);
+    if (BK == 12) return launch_panel<12, 2>(G, B, n, nP, k, Wp, order, resid, ctl, st);
     if (BK == 8) return n <= 2 * TPB ? launch_panel<8, 2>(G, B, n, nP, k, Wp, order, resid, ctl, st)
                                      : launch_panel<8, 4>(G, B, n, nP, k, Wp, order, resid, ctl, st);
     return launch_panel<4, 4>(G, B, n, nP, k, Wp, order, resid, ctl, st);

@@ -300,10 +300,11 @@ def test_greedy_picks_on_a_large_batch_of_small_images(C, k):
 
 @pytest.mark.parametrize("B,n,d,k,why", [
     (3, 1100, 320, 150, "two rows per thread, blocks of 16 picks, 32 workgroups per image"),
-    (2, 1300, 704, 330, "blocks of 8 picks (16 columns of 1344 rows do not fit LDS)"),
+    (2, 1300, 704, 330, "blocks of 12 picks (16 columns of 1344 rows do not fit LDS)"),
+    (1, 1700, 896, 430, "blocks of 8 picks"),
     (1, 2500, 2560, 1260, "four rows per thread, blocks of 4 picks"),
     (2, 1500, 256, 40, "few picks out of many rows: the left-looking kernel on several workgroups"),
-], ids=["rows2-block16", "rows2-block8", "rows4-block4", "left-looking"])
+], ids=["rows2-block16", "rows2-block12", "rows2-block8", "rows4-block4", "left-looking"])
 def test_greedy_picks_on_large_images(C, B, n, d, k, why):
     """Images above 1024 rows: the greedy kernel keeps several rows per thread, shrinks its block of picks to what
     LDS holds, and falls back to the left-looking scheme when the picks are a small part of the rows.  Pick order,
