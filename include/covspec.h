@@ -21,6 +21,13 @@
  *    value: COVSPEC_OK or one of the codes below; no exception crosses the ABI.
  *  - The library keeps no global state; concurrent calls are safe when they use
  *    distinct workspaces.
+ *  - The eigen-solve and the greedy picks of covspec_select / covspec_reduce spread an image over
+ *    several workgroups (at most 64) that wait for one another inside one launch, so such a launch
+ *    needs that many workgroup slots of the device at the same time.  Alone on the device it always
+ *    has them.  Every such wait is bounded (2 s of wall clock): if other work holds the device for
+ *    longer, the call still ends, COVSPEC_OK has long been returned, and the image concerned comes back
+ *    with NaN energies (or NaN residuals) and valid but meaningless kept indices.  Keep concurrent
+ *    calls of these two entry points to COVSPEC_MAX_CONCURRENT_CALLS per device.
  *  - Ties in every ranking go to the lower index.  Ranking decisions are taken
  *    on the fp32 score values that the library returns.
  */
@@ -36,6 +43,10 @@ extern "C" {
 
 /* Opaque stream handle: pass a hipStream_t (NULL = the default stream). */
 typedef void* covspec_stream_t;
+
+/* Calls of covspec_select / covspec_reduce that may run on one device at the same time without their
+ * multi-workgroup kernels starving one another; also the most streams covspec_reduce_ragged takes. */
+#define COVSPEC_MAX_CONCURRENT_CALLS 8
 
 enum {
   COVSPEC_OK = 0,
@@ -183,7 +194,8 @@ int covspec_reduce_staged(const covspec_params* p, const void* X, const void* hi
  * (covspec_ragged_workspace_size bytes for that n_streams, 256-byte aligned).  The caller makes the
  * inputs visible to every stream before the call and synchronises all of them before reading the
  * outputs; with n_streams == 1 the call behaves like the other entry points.  Streams are the
- * caller's (default priority); nothing is created, allocated or synchronised inside.  Errors: as
+ * caller's (default priority); nothing is created, allocated or synchronised inside.  1 <= n_streams <=
+ * COVSPEC_MAX_CONCURRENT_CALLS, else COVSPEC_INVALID_ARG (and a workspace size of 0).  Errors: as
  * covspec_reduce for the first run whose parameters are invalid or unsupported; runs enqueued before
  * a failing one stay enqueued.
  */

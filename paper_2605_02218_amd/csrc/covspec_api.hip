@@ -506,7 +506,7 @@ int covspec_ragged_resolve(const covspec_params* p, const covspec_ragged* r, int
 }
 
 size_t covspec_ragged_workspace_size(const covspec_params* p, const covspec_ragged* r, int32_t n_streams) {
-  if (n_streams < 1) return 0;
+  if (n_streams < 1 || n_streams > COVSPEC_MAX_CONCURRENT_CALLS) return 0;
   size_t most = 0;
   const int st = ragged_walk(p, r, nullptr, [&](const RaggedRun&, const covspec_params&, const Plan& pl) {
     if (pl.total > most) most = pl.total;
@@ -518,7 +518,7 @@ size_t covspec_ragged_workspace_size(const covspec_params* p, const covspec_ragg
 int covspec_reduce_ragged(const covspec_params* p, const covspec_ragged* r, const void* X, const void* hidden, const void* Q,
                           const void* Wq, const void* Wk, int32_t* idx_out, void* tokens_out, void* workspace,
                           size_t workspace_bytes, const covspec_stream_t* streams, int32_t n_streams) {
-  if (n_streams < 1 || !streams) return COVSPEC_INVALID_ARG;
+  if (n_streams < 1 || n_streams > COVSPEC_MAX_CONCURRENT_CALLS || !streams) return COVSPEC_INVALID_ARG;
   if (!X || !Q || !idx_out || !tokens_out || !workspace || ((uintptr_t)workspace & 255u)) return COVSPEC_INVALID_ARG;
   const size_t need = covspec_ragged_workspace_size(p, r, n_streams);
   if (need == 0) {   // report why

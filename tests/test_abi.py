@@ -179,3 +179,5 @@ def test_ragged_resolution_runs_and_validation():
     assert call(None, None, fake, None, None, fake, fake, fake, 1 << 40, streams, 1) == Bd.INVALID_ARG
     assert call(fake, None, fake, None, None, fake, fake, fake, 1 << 40, None, 1) == Bd.INVALID_ARG
     assert call(fake, None, fake, None, None, fake, fake, fake, 1 << 40, streams, 0) == Bd.INVALID_ARG
+    many = (ctypes.c_void_p * 9)(*([None] * 9))
+    assert call(fake, None, fake, None, None, fake, fake, fake, 1 << 40, many, 9) == Bd.INVALID_ARG     # more than 8 streams
