@@ -218,6 +218,25 @@ def make_spectrum_tokens(n: int, d: int, sigma: np.ndarray, seed: int, dtype: in
     return store(X.astype(np.float32), dtype)
 
 
+def make_video_stream(n_frames: int, n_frame: int, d: int, dtype: int = BF16, seed: int = 0, factor_rank: int = 64,
+                      noise_std: float = 0.05, drift: float = 0.25, cut_every: int = 0):
+    """One video as frames that arrive one by one: X [n_frames, n_frame, d] in the storage dtype and fused
+    scores s [n_frames, n_frame] (float32, uniform in [0, 1): what a score pass over the frame would hand on).
+    Frame 0 is the low-rank-plus-noise token model of the image workloads; frame f is frame f-1 with every token
+    moved by `drift` times a fresh draw of the same model (slowly changing content, as in workload 4), and, when
+    cut_every > 0, a fresh scene every cut_every frames."""
+    rng = np.random.default_rng(BASE_SEED + 800000 + seed)
+    R = min(factor_rank, d, n_frame)
+    X = np.empty((n_frames, n_frame, d), dtype=np.float32)
+    def fresh():
+        return _factor(rng, n_frame, d, R) + np.float32(noise_std) * _randn(rng, n_frame, d)
+    X[0] = fresh()
+    for f in range(1, n_frames):
+        X[f] = fresh() if (cut_every and f % cut_every == 0) else X[f - 1] + np.float32(drift) * fresh()
+    s = rng.random((n_frames, n_frame), dtype=np.float32)
+    return store(X, dtype), s
+
+
 # --------------------------------------------------------------------------
 # logits for the speculative verification step (paper Sec. II-A)
 # --------------------------------------------------------------------------

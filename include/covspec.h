@@ -214,6 +214,49 @@ int covspec_reduce_ragged(const covspec_params* p, const covspec_ragged* r, cons
                           const covspec_stream_t* streams, int32_t n_streams);
 
 /*
+ * covspec_stream_step: the frame-by-frame form of the low-rank selection for video whose frames arrive one by
+ * one.  NOT in the paper, which selects the tokens of one image at once (Sec. III-A.3); defined so that every
+ * frame is exactly one application of that section (stack the candidates, rank-r SVD, energy, keep the
+ * largest) to the candidate set "tokens kept so far, then the frame's pre-selected tokens":
+ *   1. the frame_m tokens of the frame with the largest s_fused are pre-selected (ascending position);
+ *   2. candidates = the n_keep kept tokens in their order, then the pre-selected ones: n_C = n_keep + frame_m;
+ *   3. n_C <= keep_k: every candidate is kept.  Otherwise c_i = energy of candidate i in the top-r singular
+ *      subspace of the n_C candidate rows, and the keep_k candidates with the largest c (fp32 values, ties to
+ *      the earlier candidate) are kept, in candidate order.
+ * The kept tokens' Gram matrix travels with the state, so only the frame_m rows of the arriving tokens are
+ * computed (frame_m * n_C * d products instead of n_C^2 * d); the kept block is copied and, after the
+ * decision, gathered.  `batch` independent videos advance together, one frame each, all with the same n_keep.
+ * State, owned by the caller, device memory, one set read and another written (they must not overlap; swap
+ * them between frames; before the first frame n_keep = 0 and the input set is not read):
+ *   Z  [batch, keep_k, d] feature rows in the storage dtype;  G [batch, keep_k, keep_k] fp64, G_ij = z_i . z_j;
+ *   id [batch, keep_k] int32 caller-side token ids (an arriving token gets id_base + its position in the
+ *   frame).  Rows and entries at or beyond the kept count are unspecified.
+ * X_frame [batch, n_frame, d], s_fused [batch, n_frame] fp32 (covspec_score of the frame, or any score).
+ * c_out (optional) [batch, n_keep + frame_m] fp32 energies, written only when n_C > keep_k.
+ * *n_keep_out (HOST, optional) = min(keep_k, n_keep + frame_m), the count to pass with the next frame.
+ * Precision as covspec_select: bf16 storage takes the Gram rows on the bf16 MFMA with fp32 partial sums flushed
+ * into fp64, fp32 storage on the fp64 MFMA; the eigen-solve is fp64.
+ * Errors: COVSPEC_INVALID_ARG (NULL pointer, n_keep outside 0..keep_k, frame_m outside 1..n_frame, rank_r
+ * outside 1..min(keep_k, d_model)-1, misaligned workspace), COVSPEC_UNSUPPORTED (keep_k + frame_m > 4096,
+ * n_frame > 16384, d_model not a multiple of 8 (bf16) / 4 (fp32)), COVSPEC_WORKSPACE_TOO_SMALL, COVSPEC_HIP_ERROR.
+ */
+typedef struct covspec_stream_params {
+  int32_t batch;     /* videos advancing together                     */
+  int32_t n_frame;   /* N_f: tokens per arriving frame                 */
+  int32_t d_model;
+  int32_t dtype;     /* COVSPEC_FP32 / COVSPEC_BF16: X_frame and Z     */
+  int32_t frame_m;   /* M_f: pre-selected per frame                    */
+  int32_t keep_k;    /* k: tokens kept across frames                   */
+  int32_t rank_r;    /* r                                              */
+} covspec_stream_params;
+
+size_t covspec_stream_workspace_size(const covspec_stream_params* p);
+int covspec_stream_step(const covspec_stream_params* p, int32_t n_keep, int32_t id_base, const void* X_frame,
+                        const float* s_fused, const void* Z_in, const double* G_in, const int32_t* id_in,
+                        void* Z_out, double* G_out, int32_t* id_out, float* c_out, int32_t* n_keep_out,
+                        void* workspace, size_t workspace_bytes, covspec_stream_t stream);
+
+/*
  * Which way each image's eigen-solve went in the LAST covspec_select / covspec_reduce call with these
  * parameters on this workspace (COVSPEC_LR_ENERGY_TOPK only; diagnostics for tests and tuning: the
  * paper's Sec. III-A.3 asks for a rank-r SVD and says nothing of how).  path_out: DEVICE int32 [B]:

@@ -25,7 +25,7 @@ EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspe
            "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string",
            "covspec_verify_workspace_size", "covspec_verify", "covspec_draft_fanout", "covspec_draft_workspace_size",
            "covspec_draft_gate", "covspec_last_error", "covspec_ragged_resolve", "covspec_ragged_workspace_size",
-           "covspec_reduce_ragged", "covspec_lowrank_path")
+           "covspec_reduce_ragged", "covspec_lowrank_path", "covspec_stream_workspace_size", "covspec_stream_step")
 
 
 class CovspecParams(ctypes.Structure):
@@ -47,6 +47,10 @@ class CovspecDraftParams(ctypes.Structure):
 class CovspecRagged(ctypes.Structure):
     _fields_ = [("n_images", ctypes.c_int32), ("n_tokens", ctypes.POINTER(ctypes.c_int32)),
                 ("n_query", ctypes.POINTER(ctypes.c_int32))]
+
+
+class CovspecStreamParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("batch", "n_frame", "d_model", "dtype", "frame_m", "keep_k", "rank_r")]
 
 
 class CovspecError(RuntimeError):
@@ -111,6 +115,11 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_reduce_ragged.argtypes = [pp, rp] + [vp] * 7 + [vp, ctypes.c_size_t, ctypes.POINTER(vp), ctypes.c_int32]
     lib.covspec_lowrank_path.restype = ctypes.c_int
     lib.covspec_lowrank_path.argtypes = [pp, vp, vp, vp]
+    spp = ctypes.POINTER(CovspecStreamParams)
+    lib.covspec_stream_workspace_size.restype = ctypes.c_size_t
+    lib.covspec_stream_workspace_size.argtypes = [spp]
+    lib.covspec_stream_step.restype = ctypes.c_int
+    lib.covspec_stream_step.argtypes = [spp, ctypes.c_int32, ctypes.c_int32] + [vp] * 9 + [ctypes.POINTER(ctypes.c_int32), vp, ctypes.c_size_t, vp]
     lib.covspec_last_error.restype = ctypes.c_char_p
     lib.covspec_last_error.argtypes = []
     _lib = lib
@@ -445,3 +454,52 @@ def lowrank_path(p: Params, workspace):
     if st != OK:
         raise CovspecError(st, "covspec_lowrank_path")
     return out
+
+
+@dataclass
+class StreamParams:
+    batch: int
+    n_frame: int
+    d_model: int
+    frame_m: int
+    keep_k: int
+    rank_r: int
+    dtype: int = BF16
+
+    def c_struct(self) -> CovspecStreamParams:
+        return CovspecStreamParams(self.batch, self.n_frame, self.d_model, self.dtype, self.frame_m, self.keep_k, self.rank_r)
+
+
+def stream_workspace_size(p: StreamParams) -> int:
+    cs = p.c_struct()
+    return int(load_library().covspec_stream_workspace_size(ctypes.byref(cs)))
+
+
+def stream_alloc_state(p: StreamParams, device="cuda"):
+    """One set of state buffers (Z [B,k,d], G [B,k,k] fp64, ids [B,k] int32); a caller keeps two and swaps them."""
+    import torch
+    return (torch.empty(p.batch, p.keep_k, p.d_model, dtype=_torch_dtype(p.dtype), device=device),
+            torch.empty(p.batch, p.keep_k, p.keep_k, dtype=torch.float64, device=device),
+            torch.empty(p.batch, p.keep_k, dtype=torch.int32, device=device))
+
+
+def stream_step(p: StreamParams, n_keep: int, id_base: int, X_frame, s_fused, state_in, state_out, workspace=None, want_c=False):
+    """covspec_stream_step: advances every video by one frame.  state_in / state_out are (Z, G, ids) tuples that
+    must not share memory (state_in may be None while n_keep == 0).  Returns (n_keep_next, c or None)."""
+    import torch
+    if workspace is None:
+        n = stream_workspace_size(p)
+        if n == 0:
+            raise CovspecError(INVALID_ARG, "covspec_stream_workspace_size")
+        workspace = torch.empty(n + 256, dtype=torch.uint8, device=X_frame.device)
+    wp, wb = _ws_args(workspace)
+    zi, gi, ii = state_in if state_in is not None else (None, None, None)
+    zo, go, io = state_out
+    c = torch.empty(p.batch, n_keep + p.frame_m, dtype=torch.float32, device=X_frame.device) if want_c else None
+    nxt = ctypes.c_int32(-1)
+    cs = p.c_struct()
+    st = load_library().covspec_stream_step(ctypes.byref(cs), n_keep, id_base, _ptr(X_frame), _ptr(s_fused), _ptr(zi), _ptr(gi),
+                                            _ptr(ii), _ptr(zo), _ptr(go), _ptr(io), _ptr(c), ctypes.byref(nxt), wp, wb, _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_stream_step")
+    return nxt.value, (c if (want_c and n_keep + p.frame_m > p.keep_k) else None)

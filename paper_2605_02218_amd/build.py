@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcovspec.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["covspec_api.hip", "gemm.hip", "gemm64.hip", "elementwise.hip", "select.hip", "eigen.hip", "subspace.hip", "greedy.hip", "verify.hip", "draft.hip"]
+SOURCES = ["covspec_api.hip", "gemm.hip", "gemm64.hip", "elementwise.hip", "select.hip", "eigen.hip", "subspace.hip", "greedy.hip", "verify.hip", "draft.hip", "stream.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

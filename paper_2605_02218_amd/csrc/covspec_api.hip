@@ -377,6 +377,45 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
   return COVSPEC_OK;
 }
 
+// ---- streaming selection (frame by frame; each frame is one low-rank step of Sec. III-A.3 on the candidates)
+struct StreamPlan {
+  int B, N, d, dtype, M, k, r, cap, nP, esz, P;
+  size_t idxf, idc, sel, Gc, A, ctl, lam, c, sub, ok, total;
+};
+
+int make_stream_plan(const covspec_stream_params* p, StreamPlan* pl) {
+  if (!p) return COVSPEC_INVALID_ARG;
+  if (p->batch < 1 || p->n_frame < 1 || p->d_model < 1 || p->keep_k < 1) return COVSPEC_INVALID_ARG;
+  if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16) return COVSPEC_INVALID_ARG;
+  if (p->frame_m < 1 || p->frame_m > p->n_frame) return COVSPEC_INVALID_ARG;
+  const int mind = p->keep_k < p->d_model ? p->keep_k : p->d_model;
+  if (p->rank_r < 1 || p->rank_r >= mind) return COVSPEC_INVALID_ARG;
+  if ((long)p->keep_k + p->frame_m > kMaxPreselect || p->n_frame > kMaxTokens) return COVSPEC_UNSUPPORTED;
+  if (p->d_model % (p->dtype == COVSPEC_BF16 ? 8 : 4) != 0) return COVSPEC_UNSUPPORTED;
+  if ((long)p->batch * p->n_frame > 0x3fffffffL) return COVSPEC_UNSUPPORTED;
+  StreamPlan& q = *pl;
+  q.B = p->batch; q.N = p->n_frame; q.d = p->d_model; q.dtype = p->dtype; q.M = p->frame_m; q.k = p->keep_k; q.r = p->rank_r;
+  q.cap = q.k + q.M;
+  q.nP = jacobi_pitch(q.cap);
+  q.esz = q.dtype == COVSPEC_BF16 ? 2 : 4;
+  q.P = subspace_block(q.cap, q.r);      // the largest candidate count decides: a smaller one never needs more
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  const size_t B = q.B;
+  q.idxf = take(B * q.M * 4);
+  q.idc = take(B * q.cap * 4);
+  q.sel = take(B * q.k * 4);
+  q.Gc = take(B * (size_t)q.nP * q.nP * 8);
+  q.A = take(B * (size_t)q.nP * q.nP * 8);
+  q.ctl = take(jacobi_ctl_bytes(q.B));
+  q.lam = take(B * q.nP * 8);
+  q.c = take(B * q.cap * 4);
+  q.sub = take(subspace_workspace_bytes(q.B, q.cap, q.nP, q.P));
+  q.ok = take(B * 4);
+  q.total = off;
+  return COVSPEC_OK;
+}
+
 }  // namespace
 
 // A ragged batch is worked off as runs of consecutive images of equal shape, each run one dense call.
@@ -648,6 +687,91 @@ const char* covspec_status_string(int status) {
     case COVSPEC_HIP_ERROR: return "HIP launch error";
     default: return "unknown status";
   }
+}
+
+size_t covspec_stream_workspace_size(const covspec_stream_params* p) {
+  StreamPlan pl;
+  if (make_stream_plan(p, &pl) != COVSPEC_OK) return 0;
+  return pl.total;
+}
+
+int covspec_stream_step(const covspec_stream_params* p, int32_t n_keep, int32_t id_base, const void* X_frame,
+                        const float* s_fused, const void* Z_in, const double* G_in, const int32_t* id_in, void* Z_out,
+                        double* G_out, int32_t* id_out, float* c_out, int32_t* n_keep_out, void* workspace,
+                        size_t workspace_bytes, covspec_stream_t stream) {
+  StreamPlan q;
+  int rc = make_stream_plan(p, &q);
+  if (rc != COVSPEC_OK) return rc;
+  if (n_keep < 0 || n_keep > q.k || !X_frame || !s_fused || !Z_out || !G_out || !id_out) return COVSPEC_INVALID_ARG;
+  if (n_keep > 0 && (!Z_in || !G_in || !id_in)) return COVSPEC_INVALID_ARG;
+  if (!workspace || ((uintptr_t)workspace & 255u)) return COVSPEC_INVALID_ARG;
+  if (workspace_bytes < q.total) return COVSPEC_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  void* ws = workspace;
+  discard_pending_error();
+  const int nC = n_keep + q.M;
+  const long d = q.d, gstride = (long)q.nP * q.nP;
+  int32_t* idxf = at<int32_t>(ws, q.idxf);
+  int32_t* idc = at<int32_t>(ws, q.idc);
+  double* Gc = at<double>(ws, q.Gc);
+
+  // 1. the frame's pre-selected tokens and the candidates' ids
+  HIPCHK(launch_select_top(s_fused, q.B, q.N, q.M, nullptr, idxf, st));
+  HIPCHK(launch_stream_ids(id_in, idxf, idc, q.B, n_keep, q.M, q.k, id_base, st));
+
+  // 2. Gram matrix of the candidates: the kept block is carried, the rows of the arriving tokens are computed
+  HIPCHK(launch_fill_zero(Gc, (size_t)q.B * gstride * 8, st));
+  HIPCHK(launch_copy_block(Gc, q.nP, gstride, G_in, q.k, (long)q.k * q.k, n_keep, q.B, st));
+  GemmArgs g;
+  g.A = X_frame; g.lda = d; g.strideA = (long)q.N * d; g.gatherA = idxf; g.gstrideA = q.M;
+  g.M = q.M; g.K = q.d; g.ldc = q.nP; g.batch = q.B; g.strideC = gstride;
+  g.epilogue = EPI_STORE_F64;
+  auto gram = [&](const GemmArgs& a) { return q.dtype == COVSPEC_FP32 ? launch_gemm64_nt(a, false, false, st) : launch_gemm_nt(a, DT_BF16, st); };
+  if (n_keep > 0) {
+    GemmArgs a = g;            // arriving x kept
+    a.B = Z_in; a.ldb = d; a.strideB = (long)q.k * d; a.N = n_keep;
+    a.C = Gc + (long)n_keep * q.nP;
+    HIPCHK(gram(a));
+    HIPCHK(launch_mirror_block(Gc, q.nP, gstride, n_keep, nC, q.B, st));
+  }
+  {
+    GemmArgs a = g;            // arriving x arriving
+    a.B = X_frame; a.ldb = d; a.strideB = (long)q.N * d; a.gatherB = idxf; a.gstrideB = q.M; a.N = q.M;
+    a.C = Gc + (long)n_keep * q.nP + n_keep;
+    HIPCHK(gram(a));
+  }
+
+  // 3. keep everything, or the keep_k candidates with the largest energy in the top-r subspace
+  const int32_t* sel = nullptr;
+  int n_out = nC;
+  if (nC > q.k) {
+    double* A = at<double>(ws, q.A);
+    float* c = c_out ? c_out : at<float>(ws, q.c);
+    HIPCHK(hipMemcpyAsync(A, Gc, (size_t)q.B * gstride * 8, hipMemcpyDeviceToDevice, st));   // the solve may overwrite its input
+    const int P = subspace_block(nC, q.r);
+    if (P > 0) {
+      int* ok = at<int>(ws, q.ok);
+      const double* Ut = nullptr;
+      HIPCHK(launch_subspace_eigen(A, q.B, nC, q.nP, q.r, P, kSubspaceIters, kSubspaceMoreIters, at<void>(ws, q.sub), at<void>(ws, q.ctl),
+                                   at<double>(ws, q.lam), ok, &Ut, nullptr, nullptr, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, st));
+      HIPCHK(launch_subspace_energy(Ut, q.B, P, nC, q.nP, (long)P * q.nP, q.r, at<double>(ws, q.lam), c, ok, 1, st));
+      HIPCHK(launch_subspace_energy(A, q.B, nC, nC, q.nP, gstride, q.r, at<double>(ws, q.lam), c, ok, 0, st));
+    } else {
+      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, st));
+      HIPCHK(launch_subspace_energy(A, q.B, nC, nC, q.nP, gstride, q.r, at<double>(ws, q.lam), c, nullptr, 0, st));
+    }
+    int32_t* selw = at<int32_t>(ws, q.sel);
+    HIPCHK(launch_select_top(c, q.B, nC, q.k, nullptr, selw, st));
+    sel = selw;
+    n_out = q.k;
+  }
+
+  // 4. the next state
+  HIPCHK(launch_stream_compact(Z_in, X_frame, idxf, sel, idc, Gc, q.nP, gstride, Z_out, id_out, G_out, q.B, n_keep, q.M, q.k, q.N, n_out,
+                               (long)q.d * q.esz, st));
+  if (n_keep_out) *n_keep_out = n_out;
+  return COVSPEC_OK;
 }
 
 }  // extern "C"

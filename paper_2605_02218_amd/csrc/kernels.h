@@ -150,6 +150,23 @@ hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int
 hipError_t launch_greedy_finish(const int32_t* order, const int32_t* idx_m, int B, int M, int k, int32_t* idx_out,
                                 int32_t* pick_out, hipStream_t stream);
 
+// ---------------------------------------------------------------- stream.hip
+// Streaming selection (frame by frame; not in the paper): candidates of a frame = the n_keep kept tokens, then
+// the frame's m pre-selected tokens.  State pitch kcap: Z [B, kcap, row], id [B, kcap], G [B, kcap, kcap].
+// idc[b, i] = id of candidate i.
+hipError_t launch_stream_ids(const int32_t* id_in, const int32_t* idx_f, int32_t* idc, int B, int n_keep, int m, int kcap,
+                             int id_base, hipStream_t stream);
+// dst[b][i][j] = src[b][i][j], i, j < n.
+hipError_t launch_copy_block(double* dst, long dpitch, long dstride, const double* src, long spitch, long sstride, int n, int B,
+                             hipStream_t stream);
+// G[b][j][i] = G[b][i][j] for n0 <= i < n1, j < n0.
+hipError_t launch_mirror_block(double* G, long pitch, long stride, int n0, int n1, int B, hipStream_t stream);
+// Next state: row j = candidate sel[b, j] (sel == nullptr: candidate j), with its id and the Gram block of the
+// survivors gathered from Gc (pitch, image stride).  row_bytes % 16 == 0; in and out state must not overlap.
+hipError_t launch_stream_compact(const void* Z_in, const void* X, const int32_t* idx_f, const int32_t* sel, const int32_t* idc,
+                                 const double* Gc, long pitch, long stride, void* Z_out, int32_t* id_out, double* G_out, int B,
+                                 int n_keep, int m, int kcap, int N, int n_out, long row_bytes, hipStream_t stream);
+
 // ---------------------------------------------------------------- verify.hip
 // Speculative verification over the vocabulary (paper Sec. II-A): zt, zd [S, L, V] target / draft logits,
 // tok [S, L] drafted tokens, u_acc [S, L], u_res [S] uniforms.  n_acc[s] = accepted positions before the first

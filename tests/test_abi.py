@@ -181,3 +181,24 @@ def test_ragged_resolution_runs_and_validation():
     assert call(fake, None, fake, None, None, fake, fake, fake, 1 << 40, streams, 0) == Bd.INVALID_ARG
     many = (ctypes.c_void_p * 9)(*([None] * 9))
     assert call(fake, None, fake, None, None, fake, fake, fake, 1 << 40, many, 9) == Bd.INVALID_ARG     # more than 8 streams
+
+
+def test_stream_params_are_validated_on_the_host():
+    assert ctypes.sizeof(Bd.CovspecStreamParams) == 7 * 4
+    ok = dict(batch=2, n_frame=256, d_model=128, frame_m=64, keep_k=192, rank_r=16, dtype=C.BF16)
+    assert C.stream_workspace_size(C.StreamParams(**ok)) > 0
+    for bad in (dict(frame_m=0), dict(frame_m=257), dict(rank_r=0), dict(rank_r=128), dict(rank_r=192), dict(keep_k=0),
+                dict(dtype=C.FP16), dict(batch=0), dict(d_model=100), dict(keep_k=4090), dict(n_frame=20000, frame_m=64)):
+        assert C.stream_workspace_size(C.StreamParams(**{**ok, **bad})) == 0, bad
+    lib = C.load_library()
+    cs = C.StreamParams(**ok).c_struct()
+    fake, big = 4096, 1 << 40
+    call = lambda n_keep, *a: lib.covspec_stream_step(ctypes.byref(cs), n_keep, 0, *a)
+    nxt = ctypes.c_int32(0)
+    # n_keep outside 0..k; a missing required pointer; a missing input state with tokens kept; workspace too small / misaligned
+    assert call(-1, fake, fake, fake, fake, fake, fake, fake, fake, None, ctypes.byref(nxt), fake, big, None) == Bd.INVALID_ARG
+    assert call(193, fake, fake, fake, fake, fake, fake, fake, fake, None, ctypes.byref(nxt), fake, big, None) == Bd.INVALID_ARG
+    assert call(0, None, fake, None, None, None, fake, fake, fake, None, ctypes.byref(nxt), fake, big, None) == Bd.INVALID_ARG
+    assert call(5, fake, fake, None, fake, fake, fake, fake, fake, None, ctypes.byref(nxt), fake, big, None) == Bd.INVALID_ARG
+    assert call(0, fake, fake, None, None, None, fake, fake, fake, None, ctypes.byref(nxt), fake, 16, None) == Bd.WORKSPACE_TOO_SMALL
+    assert call(0, fake, fake, None, None, None, fake, fake, fake, None, ctypes.byref(nxt), fake + 8, big, None) == Bd.INVALID_ARG
