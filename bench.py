@@ -347,6 +347,89 @@ def ragged_bench(a):
     print(json.dumps(line), flush=True)
 
 
+def stream_bench(a):
+    """--stream: covspec_stream_step in its steady state, own JSON line.
+
+    Four videos of workload 4's kind (frames of 1024 tokens, d = 1536, bf16, slowly drifting content) advance one
+    frame per step: 256 tokens pre-selected per frame, 1024 kept across frames, r = 128, so every step decides
+    among 1280 candidates.  Scores are inputs (a score pass over the frame precedes the step in a pipeline).
+    Beside it: the same decision without the carried Gram matrix (covspec_select over the 1280 stacked candidate
+    rows, which recomputes all of it), and the oracle on the host.
+    """
+    import numpy as np
+    import torch
+    import covspec_inputs as I
+    import paper_2605_02218_amd as C
+    C.load_library()
+    torch.cuda.set_device(0)
+    B, n_frame, d, m, k, r = 4, 1024, 1536, 256, 1024, 128
+    n_frames = 6
+    vids = [I.make_video_stream(n_frames, n_frame, d, dtype=I.BF16, seed=b) for b in range(B)]
+
+    def up(x):
+        return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).cuda().view(torch.bfloat16)
+
+    Xf = [up(np.stack([v[0][f] for v in vids])) for f in range(n_frames)]
+    sf = [torch.from_numpy(np.stack([v[1][f] for v in vids])).cuda() for f in range(n_frames)]
+    p = C.StreamParams(batch=B, n_frame=n_frame, d_model=d, frame_m=m, keep_k=k, rank_r=r, dtype=C.BF16)
+    ws = torch.empty(C.stream_workspace_size(p) + 256, dtype=torch.uint8, device="cuda")
+    states = [C.stream_alloc_state(p), C.stream_alloc_state(p)]
+    n_keep, f = 0, 0
+    while n_keep < k:                                    # fill the memory
+        n_keep, _ = C.stream_step(p, n_keep, f * n_frame, Xf[f % n_frames], sf[f % n_frames], states[f & 1] if n_keep else None,
+                                  states[(f + 1) & 1], workspace=ws)
+        f += 1
+
+    def step():
+        nonlocal f
+        C.stream_step(p, k, f * n_frame, Xf[f % n_frames], sf[f % n_frames], states[f & 1], states[(f + 1) & 1], workspace=ws)
+        f += 1
+
+    def timed(fn):
+        for _ in range(a.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / a.steps
+
+    ms = timed(step)
+    # the same decision from scratch: stack the candidates and let covspec_select recompute their Gram matrix
+    ps = C.Params(batch=B, n_tokens=k + m, d_model=d, n_query=1, dtype=C.BF16, keep_k=k, preselect_m=k + m, rank_r=r)
+    wss = C.alloc_workspace(ps)
+    Zc = torch.cat([states[f & 1][0], Xf[0][:, :m]], dim=1).contiguous()
+    flat = torch.zeros(B, k + m, dtype=torch.float32, device="cuda")
+    ms_scratch = None if a.no_comparison else timed(lambda: C.select(ps, Zc, flat, wss))
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        from oracle import stream_oracle as S
+        st = S.empty_state(d)
+        X0 = [I.as_f64(vids[0][0][g], I.BF16) for g in range(n_frames)]
+        g, n0 = 0, 0
+        while st.rows.shape[0] < k:
+            S.stream_step(st, X0[g % n_frames], vids[0][1][g % n_frames], g * n_frame, m, k, r)
+            g += 1
+        t0 = time.perf_counter()
+        done = 0
+        while done < 2 or time.perf_counter() - t0 < 10.0:
+            S.stream_step(st, X0[g % n_frames], vids[0][1][g % n_frames], g * n_frame, m, k, r)
+            g += 1
+            done += 1
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(done / dt, 3), "unit": "frames/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+               "kind": "oracle", "sample": "%d steady-state frames of one video (%.1f s)" % (done, dt)}
+    line = {"metric": "frames/sec for the streaming low-rank selection (steady state)", "value": round(B / ms * 1e3, 2), "unit": "frames/s",
+            "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "stream: %d videos, frames of %d tokens x %d, %d pre-selected per frame, %d kept, r=%d (%d candidates per step)"
+                       % (B, n_frame, d, m, k, r, k + m), "entry_point": "covspec_stream_step"},
+            "from_scratch_ms_per_step": None if ms_scratch is None else round(ms_scratch, 4), "tokens_per_s": round(B * n_frame / ms * 1e3, 1), "cpu_baseline": cpu}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -359,6 +442,8 @@ def main():
     ap.add_argument("--verify", action="store_true", help="time the speculative verification step instead (own JSON line)")
     ap.add_argument("--draft", action="store_true", help="time the draft-side margin gate / candidate pass instead (own JSON line)")
     ap.add_argument("--ragged", action="store_true", help="time covspec_reduce_ragged on a dynamic-resolution batch (own JSON line)")
+    ap.add_argument("--stream", action="store_true", help="time covspec_stream_step in its steady state (own JSON line)")
+    ap.add_argument("--no-comparison", action="store_true", help="with --stream: leave out the from-scratch comparison (clean kernel profiles)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 1 GiB device copies and exit (reference reading for the HBM byte counters)")
     a = ap.parse_args()
@@ -385,6 +470,9 @@ def main():
         return
     if a.ragged:
         ragged_bench(a)
+        return
+    if a.stream:
+        stream_bench(a)
         return
     import covspec_inputs as I
     import paper_2605_02218_amd as C
