@@ -343,33 +343,46 @@ __global__ void mask_passed_kernel(const int* __restrict__ ok, int* __restrict__
 // Residual check of the r dominant Ritz pairs.  Ut rows are theta_k u_k^T, Rt = Ut G.  ok[b] = 1 (2 in the second pass) when
 // |Rt_k - theta_k Ut_k| <= tol * theta_k^2 for each of them (theta_k = |Ut_k|, so this is the relative
 // residual |G u - theta u| / theta).
-__global__ __launch_bounds__(256) void ritz_check_kernel(const double* __restrict__ Ut, const double* __restrict__ Rt,
-                                                          const double* __restrict__ lam, int P, int n, int nP, int r,
-                                                          double tol, int* ok, int only_failed) {
+__global__ __launch_bounds__(1024) void ritz_check_kernel(const double* __restrict__ Ut, const double* __restrict__ Rt,
+                                                           const double* __restrict__ lam, int P, int n, int nP, int r,
+                                                           double tol, int* ok, int only_failed) {
   __shared__ double slam[4096];
   __shared__ unsigned char sel[4096];
   __shared__ int bad;
   const int b = blockIdx.x, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   if (only_failed && ok[b]) return;      // passed an earlier check; its rows were not touched since (uniform)
   const double* lb = lam + (long)b * P;
-  for (int k = threadIdx.x; k < P; k += 256) slam[k] = lb[k];
+  for (int k = threadIdx.x; k < P; k += 1024) slam[k] = lb[k];
   if (threadIdx.x == 0) bad = 0;
   __syncthreads();
-  for (int k = threadIdx.x; k < P; k += 256) {
+  for (int k = threadIdx.x; k < P; k += 1024) {
     const double v = slam[k];
     int rank = 0;
     for (int j = 0; j < P; ++j) { const double u = slam[j]; rank += (u > v || (u == v && j < k)) ? 1 : 0; }
     sel[k] = rank < r;
   }
   __syncthreads();
-  for (int k = w; k < P; k += 4) {
+  // one wave per row, four pairs of loads in flight per lane
+  for (int k = w; k < P; k += 16) {
     if (!sel[k]) continue;
     const double th = slam[k];
     const double* u = Ut + ((long)b * P + k) * nP;
     const double* rr = Rt + ((long)b * P + k) * nP;
-    double s = 0.0;
-    for (int j = lane; j < n; j += 64) { const double d = rr[j] - th * u[j]; s = fma(d, d, s); }
-    s = wave_sum(s);
+    double s0 = 0.0, s1 = 0.0;
+    int j = lane;
+    for (; j + 192 < n; j += 256) {
+      double a[4], c[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { a[q] = rr[j + 64 * q]; c[q] = u[j + 64 * q]; }
+#pragma unroll
+      for (int q = 0; q < 4; q += 2) {
+        const double d0 = a[q] - th * c[q], d1 = a[q + 1] - th * c[q + 1];
+        s0 = fma(d0, d0, s0);
+        s1 = fma(d1, d1, s1);
+      }
+    }
+    for (; j < n; j += 64) { const double d = rr[j] - th * u[j]; s0 = fma(d, d, s0); }
+    const double s = wave_sum(s0 + s1);
     if (lane == 0 && !(sqrt(s) <= tol * th * th)) bad = 1;   // also catches NaN
   }
   __syncthreads();
@@ -494,7 +507,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     // residuals: Rt = Ut G
     if ((e = gemm_yt_g(cur, oth)) != hipSuccess) return e;
     if ((e = launch_row_lengths(cur, B, P, nP, (long)P * nP, lam, st)) != hipSuccess) return e;
-    hipLaunchKernelGGL(ritz_check_kernel, dim3(B), dim3(256), 0, st, cur, oth, lam, P, n, nP, r, kRitzTol, ok, masked ? 1 : 0);
+    hipLaunchKernelGGL(ritz_check_kernel, dim3(B), dim3(1024), 0, st, cur, oth, lam, P, n, nP, r, kRitzTol, ok, masked ? 1 : 0);
     return hipGetLastError();
   };
 
