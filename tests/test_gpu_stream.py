@@ -25,10 +25,11 @@ def _dev(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-def _run(C, B, n_frames, n_frame, d, m, k, r, dtype, cut_every=0, factor_rank=64):
+def _run(C, B, n_frames, n_frame, d, m, k, r, dtype, cut_every=0, factor_rank=64, seed0=None):
     """Drives B videos through n_frames frames on the GPU and in the oracle; checks every frame."""
     import torch
-    vids = [I.make_video_stream(n_frames, n_frame, d, dtype=dtype, seed=10 * B + b, cut_every=cut_every,
+    seed0 = 10 * B if seed0 is None else seed0
+    vids = [I.make_video_stream(n_frames, n_frame, d, dtype=dtype, seed=seed0 + b, cut_every=cut_every,
                                 factor_rank=factor_rank) for b in range(B)]
     p = C.StreamParams(batch=B, n_frame=n_frame, d_model=d, frame_m=m, keep_k=k, rank_r=r, dtype=dtype)
     ws = torch.empty(C.stream_workspace_size(p) + 256, dtype=torch.uint8, device="cuda")
@@ -89,3 +90,10 @@ def test_stream_keeps_everything_while_the_memory_is_not_full(C):
 def test_stream_frame_m_equals_n_frame_and_single_video(C):
     # no pre-selection inside the frame (M_f = N_f), one video
     assert _run(C, B=1, n_frames=4, n_frame=72, d=128, m=72, k=100, r=10, dtype=I.FP32) == 3
+
+
+def test_stream_at_the_benchmark_shape(C):
+    # the shape bench.py --stream times: 4 videos, frames of 1024 x 1536 bf16, 256 pre-selected, 1024 kept, r = 128;
+    # four frames fill the memory, two decide among 1280 candidates (block iteration with a block of 192)
+    # (the videos of the benchmark: seeds 0..3)
+    assert _run(C, B=4, n_frames=6, n_frame=1024, d=1536, m=256, k=1024, r=128, dtype=I.BF16, seed0=0) == 8
