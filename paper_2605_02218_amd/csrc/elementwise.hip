@@ -161,8 +161,10 @@ __global__ __launch_bounds__(256) void cosine_max_kernel(const F* __restrict__ l
   const long token = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (token >= tokens) return;
   const long b = token / N;
+  // the partial sums of |e(v)|^2: one load per lane and a wave sum instead of nparts loads that every lane repeats
   double n2 = 0.0;
-  for (int t = 0; t < nparts; ++t) n2 += (double)vnorm2[token * nparts + t];
+  for (int t = lane; t < nparts; t += 64) n2 += (double)vnorm2[token * nparts + t];
+  n2 = wave_sum(n2);
   const double nv = sqrt(n2);
   const F* L = logits + token * (long)planes * T;
   double best = -INFINITY;
