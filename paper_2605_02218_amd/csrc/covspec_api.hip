@@ -30,7 +30,7 @@ struct Plan {
   int nparts;     // per-token partial sums of |e(v)|^2 written by the projection GEMM
   int nP;         // Gram pitch (padded order of the eigen-solve)
   // workspace offsets (bytes)
-  size_t wqT, wkT, Eq, qn2, Eq3, G3raw, G3, vn2p, logits, Ev, S, stats, sq, sa, sf;
+  size_t wqT, wkT, Eq, qn2, Eq3, G3raw, G3, vn2p, logits, Ev, S, stats, smean, sq, sa, sf;
   size_t idxm, Awork, ctl, lam, c, Lt, order, resid, gscr, sub, ok;
   int P;          // block size of the subspace iteration (0: full Jacobi solve)
   size_t total;
@@ -89,7 +89,7 @@ int make_plan(const covspec_params* p, Plan* pl) {
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t B = q.B, N = q.N, d = q.d, T = q.T, BT = B * T, BN = B * N;
   q.wqT = q.wkT = q.Eq = q.qn2 = 0;
-  q.Eq3 = q.G3raw = q.G3 = q.vn2p = q.logits = q.Ev = q.S = q.stats = 0;
+  q.Eq3 = q.G3raw = q.G3 = q.vn2p = q.logits = q.Ev = q.S = q.stats = q.smean = 0;
   // the random-selection ablation uses no scores; covspec_score with that mode still works on its own
   // workspace request, so the score buffers are always part of the plan
   q.wqT = take(d * d * q.esz);
@@ -106,6 +106,7 @@ int make_plan(const covspec_params* p, Plan* pl) {
     q.Ev = take(BN * d * fsz);
     q.S = take(B * q.H * T * N * fsz);
     q.stats = take(B * q.H * T * 16);
+    if (softmax_base2(q.dtype == COVSPEC_FP32, q.N)) q.smean = take(softmax_scratch_bytes(q.B, q.N));
   }
   q.sq = take(BN * 4);
   q.sa = take(BN * 4);
@@ -278,8 +279,9 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
     HIPCHK(f64 ? launch_gemm64_nt(g, true, true, st) : launch_gemm_nt(g, DT_F32, st));
     const double scale = 1.0 / sqrt((double)dh);
     void* stats = at<void>(ws, q.stats);
-    HIPCHK(launch_softmax_stats(S, f64, stats, B * q.H * T, q.N, scale, st));
-    HIPCHK(launch_softmax_mean(S, f64, stats, sq, q.B, q.H * q.T, q.N, scale, st));
+    const bool base2 = softmax_base2(f64, q.N);
+    HIPCHK(launch_softmax_stats(S, f64, stats, B * q.H * T, q.N, scale, base2, st));
+    HIPCHK(launch_softmax_mean(S, f64, stats, sq, q.B, q.H * q.T, q.N, scale, base2 ? at<void>(ws, q.smean) : nullptr, st));
   }
 
   marks.mark(COVSPEC_STAGE_ACTIVITY);

@@ -231,6 +231,80 @@ __global__ __launch_bounds__(256) void softmax_mean_kernel(const F* __restrict__
   s_query[(long)b * N + i] = (float)(((acc[0] + acc[1]) + (acc[2] + acc[3])) / HT);
 }
 
+// fp32 logits with N a multiple of 4 (the bf16 workloads): the same two passes with 16-byte loads, base-2
+// exponentials (one v_exp_f32 each) and fp32 partial sums; fp64 only where partial results are combined.
+// stats[row] = (max_i log2(e)*scale*S[row,i], 1 / sum_i 2^(log2(e)*scale*S[row,i] - max)).
+constexpr float kLog2eF = 1.44269504f;
+
+__global__ __launch_bounds__(256) void softmax_stats4_kernel(const float4* __restrict__ S, double2* __restrict__ stats, long rows,
+                                                              int N4, float sl2) {
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float4* p = S + row * (long)N4;
+  float m = -INFINITY, z = 0.f;
+  for (int c = lane; c < N4; c += 64) {
+    const float4 x = p[c];
+    const float a = x.x * sl2, b = x.y * sl2, cc = x.z * sl2, d = x.w * sl2;
+    const float mx = fmaxf(fmaxf(a, b), fmaxf(cc, d));
+    if (mx > m) { z *= __builtin_amdgcn_exp2f(m - mx); m = mx; }     // m = -inf at first: 2^-inf = 0
+    z += (__builtin_amdgcn_exp2f(a - m) + __builtin_amdgcn_exp2f(b - m)) + (__builtin_amdgcn_exp2f(cc - m) + __builtin_amdgcn_exp2f(d - m));
+  }
+  const float mw = wave_max(m);
+  double zd = (m == -INFINITY) ? 0.0 : (double)z * (double)__builtin_amdgcn_exp2f(m - mw);
+  zd = wave_sum(zd);
+  if (lane == 0) stats[row] = make_double2((double)mw, 1.0 / zd);
+}
+
+// part[seg][b][i] = sum over the rows of segment seg of 2^(sl2*S[b,row,i] - max_row) / Z_row; a thread owns four
+// neighbouring tokens and keeps four rows (64 bytes) in flight.
+__global__ __launch_bounds__(256) void softmax_mean4_part_kernel(const float4* __restrict__ S, const double2* __restrict__ stats,
+                                                                  double* __restrict__ part, int HT, int N4, int seg_rows, float sl2) {
+  const int i4 = blockIdx.x * blockDim.x + threadIdx.x;
+  const int b = blockIdx.y, seg = blockIdx.z, B = gridDim.y;
+  if (i4 >= N4) return;
+  const int r0 = seg * seg_rows, r1 = min(HT, r0 + seg_rows);
+  const float4* p = S + (long)b * HT * N4 + i4;
+  const double2* st = stats + (long)b * HT;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int r = r0;
+  for (; r + 4 <= r1; r += 4) {
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = p[(long)(r + u) * N4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const double2 mz = st[r + u];
+      const float mref = (float)mz.x, rz = (float)mz.y;
+      a0 = fmaf(__builtin_amdgcn_exp2f(fmaf(v[u].x, sl2, -mref)), rz, a0);
+      a1 = fmaf(__builtin_amdgcn_exp2f(fmaf(v[u].y, sl2, -mref)), rz, a1);
+      a2 = fmaf(__builtin_amdgcn_exp2f(fmaf(v[u].z, sl2, -mref)), rz, a2);
+      a3 = fmaf(__builtin_amdgcn_exp2f(fmaf(v[u].w, sl2, -mref)), rz, a3);
+    }
+  }
+  for (; r < r1; ++r) {
+    const float4 v = p[(long)r * N4];
+    const double2 mz = st[r];
+    const float mref = (float)mz.x, rz = (float)mz.y;
+    a0 = fmaf(__builtin_amdgcn_exp2f(fmaf(v.x, sl2, -mref)), rz, a0);
+    a1 = fmaf(__builtin_amdgcn_exp2f(fmaf(v.y, sl2, -mref)), rz, a1);
+    a2 = fmaf(__builtin_amdgcn_exp2f(fmaf(v.z, sl2, -mref)), rz, a2);
+    a3 = fmaf(__builtin_amdgcn_exp2f(fmaf(v.w, sl2, -mref)), rz, a3);
+  }
+  double* out = part + (((long)seg * B + b) * N4 + i4) * 4;
+  out[0] = a0; out[1] = a1; out[2] = a2; out[3] = a3;
+}
+
+// s_query[b,i] = (sum over the segments, in order, of part[seg][b][i]) / HT
+__global__ __launch_bounds__(256) void softmax_mean_finish_kernel(const double* __restrict__ part, float* __restrict__ s_query, long BN,
+                                                                   int segs, int HT) {
+  const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= BN) return;
+  double s = 0.0;
+  for (int g = 0; g < segs; ++g) s += part[(long)g * BN + e];
+  s_query[e] = (float)(s / HT);
+}
+
 // ---------------------------------------------------------------- min-max + fuse (paper fusion equation)
 __device__ __forceinline__ void block_minmax(float& lo, float& hi, float* red) {
   lo = wave_min(lo);
@@ -352,15 +426,36 @@ hipError_t launch_cosine_max(const void* logits, int planes, const void* vnorm2,
   return hipGetLastError();
 }
 
-hipError_t launch_softmax_stats(const void* S, bool f64, void* stats, long rows, int N, double scale, hipStream_t st) {
+// The fast path needs fp32 logits, N % 4 == 0 and `part` scratch of softmax_scratch_bytes(B, N) bytes.
+size_t softmax_scratch_bytes(int B, int N) { return (size_t)32 * B * N * sizeof(double); }
+
+hipError_t launch_softmax_stats(const void* S, bool f64, void* stats, long rows, int N, double scale, bool base2, hipStream_t st) {
   dim3 grid(blocks_for(rows, 4)), block(256);
   if (f64) hipLaunchKernelGGL((softmax_stats_kernel<double>), grid, block, 0, st, (const double*)S, (double2*)stats, rows, N, scale);
+  else if (base2) hipLaunchKernelGGL(softmax_stats4_kernel, grid, block, 0, st, (const float4*)S, (double2*)stats, rows, N / 4, (float)scale * kLog2eF);
   else hipLaunchKernelGGL((softmax_stats_kernel<float>), grid, block, 0, st, (const float*)S, (double2*)stats, rows, N, scale);
   return hipGetLastError();
 }
 
+bool softmax_base2(bool f64, int N) { return !f64 && N % 4 == 0; }
+
 hipError_t launch_softmax_mean(const void* S, bool f64, const void* stats, float* s_query, int B, int HT, int N, double scale,
-                               hipStream_t st) {
+                               void* part, hipStream_t st) {
+  if (softmax_base2(f64, N) && part) {
+    const int N4 = N / 4, gx = (N4 + 255) / 256;
+    // row segments: enough workgroups for eight waves per SIMD, at most 32 segments of at least 32 rows
+    int segs = (2048 + gx * B - 1) / (gx * B);
+    const int most = HT / 32 > 0 ? HT / 32 : 1;
+    segs = segs > 32 ? 32 : segs;
+    segs = segs > most ? most : segs;
+    const int seg_rows = (HT + segs - 1) / segs;
+    segs = (HT + seg_rows - 1) / seg_rows;
+    hipLaunchKernelGGL(softmax_mean4_part_kernel, dim3(gx, B, segs), dim3(256), 0, st, (const float4*)S, (const double2*)stats,
+                       (double*)part, HT, N4, seg_rows, (float)scale * kLog2eF);
+    const long BN = (long)B * N;
+    hipLaunchKernelGGL(softmax_mean_finish_kernel, dim3(blocks_for(BN, 256)), dim3(256), 0, st, (const double*)part, s_query, BN, segs, HT);
+    return hipGetLastError();
+  }
   dim3 grid((N + 255) / 256, B), block(256);
   if (f64) hipLaunchKernelGGL((softmax_mean_kernel<double>), grid, block, 0, st, (const double*)S, (const double2*)stats, s_query, HT, N, scale);
   else hipLaunchKernelGGL((softmax_mean_kernel<float>), grid, block, 0, st, (const float*)S, (const double2*)stats, s_query, HT, N, scale);

@@ -82,9 +82,14 @@ hipError_t launch_cosine_max(const void* logits, int planes, const void* vnorm2,
 // Attention-softmax relevance (variant): S is [B,H,T,N] logits (unscaled; fp32, or fp64 when f64 is set).
 // Pass 1 writes per (b,h,j) the row maximum and the sum of exponentials of scale*S as a double2; pass 2
 // averages the probabilities over (h,j).
-hipError_t launch_softmax_stats(const void* S, bool f64, void* stats, long rows, int N, double scale, hipStream_t stream);
+// softmax_base2(f64, N): fp32 logits with N % 4 == 0 take 16-byte loads and base-2 exponentials; then both calls
+// must be made with base2 = true / a `part` scratch of softmax_scratch_bytes(B, N) bytes (the statistics are kept
+// in base-2 units).
+bool softmax_base2(bool f64, int N);
+size_t softmax_scratch_bytes(int B, int N);
+hipError_t launch_softmax_stats(const void* S, bool f64, void* stats, long rows, int N, double scale, bool base2, hipStream_t stream);
 hipError_t launch_softmax_mean(const void* S, bool f64, const void* stats, float* s_query, int B, int HT, int N,
-                               double scale, hipStream_t stream);
+                               double scale, void* part, hipStream_t stream);
 
 // Per-image min-max normalisation and fusion (paper fusion equation):
 // s_fused = lambda*minmax(s_query) + (1-lambda)*minmax(s_act);  s_act == nullptr => s_fused = minmax(s_query).
