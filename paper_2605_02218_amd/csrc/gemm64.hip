@@ -14,6 +14,7 @@
 // parked in registers, LDS is double buffered, one barrier per k-tile.
 // MFMA layouts: operand lane l holds (row|col = l%16, k = l/16); result lane l, register v
 // holds (row 4v + l/16, col l%16).
+#include <type_traits>
 #include "common.h"
 #include "kernels.h"
 
@@ -85,8 +86,33 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
     }
   }
 
+  // bf16 x bf16, both K-contiguous, 64 x 64 tiles: a k-tile of an operand is 64 rows x 32 bytes, so the
+  // element-wise staging above would issue eight 2-byte loads per thread.  When rows and K allow 16-byte
+  // pieces, thread t instead loads ONE piece (operand t / 128, row (t % 128) / 2, half t % 2) and converts its
+  // eight values on the way into LDS.
+  constexpr bool WIDE_T = std::is_same<TA, bf16_t>::value && std::is_same<TB, bf16_t>::value && !TRANSB && MI == 2 && NJ == 2;
+  const bool wide = WIDE_T && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.K % 8 == 0 && (((uintptr_t)A | (uintptr_t)B) & 15) == 0;
+  const int wop = tid >> 7, wrow = (tid & 127) >> 1, whalf = tid & 1;
+  long woff = 0;
+  bool wok = false;
+  if (WIDE_T && wide) {
+    const int rr = (wop ? col0 : row0) + wrow;
+    wok = rr < (wop ? g.N : g.M);
+    long ir = rr;
+    const int32_t* gl = wop ? g.gatherB : g.gatherA;
+    if (GATHER && gl && wok) ir = gl[(long)bo * (wop ? g.gstrideB : g.gstrideA) + rr];
+    woff = ir * (wop ? g.ldb : g.lda) + 8 * whalf;
+  }
+  u32x4_t rw = {0u, 0u, 0u, 0u};
+
   double ra_[SA], rb_[SBn];
   auto fetch = [&](int k0) {
+    if (WIDE_T && wide) {
+      const u32x4_t z = {0u, 0u, 0u, 0u};
+      const bf16_t* P = wop ? (const bf16_t*)B : (const bf16_t*)A;
+      rw = (wok && k0 + 8 * whalf < g.K) ? *(const u32x4_t*)(P + woff + k0) : z;
+      return;
+    }
 #pragma unroll
     for (int s = 0; s < SA; ++s) ra_[s] = (aok[s] && k0 + lk < g.K) ? as_f64(A[aoff[s] + k0]) : 0.0;
 #pragma unroll
@@ -100,6 +126,15 @@ __global__ __launch_bounds__(256) void gemm64_kernel(GemmArgs g, int tiles_m, in
     }
   };
   auto park = [&](int buf) {
+    if (WIDE_T && wide) {
+      double* dst = (wop ? sB + buf * TN * PITCH : sA + buf * TM * PITCH) + wrow * PITCH + 8 * whalf;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        dst[2 * e] = (double)__uint_as_float(rw[e] << 16);
+        dst[2 * e + 1] = (double)__uint_as_float(rw[e] & 0xFFFF0000u);
+      }
+      return;
+    }
     double* a = sA + buf * TM * PITCH;
     double* b = sB + buf * TN * PITCH;
 #pragma unroll
