@@ -1,0 +1,21 @@
+"""bench.py's command line, host side only (nothing touches a GPU)."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    # this build runs on one GPU; the refusal comes before torch or the library is loaded
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and "--gpus 1" in r.stderr
+    assert r.stdout.strip() == ""            # no JSON line that could be taken for a measurement
+
+
+def test_help_lists_every_mode():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--help"], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0
+    for flag in ("--gpus", "--steps", "--warmup", "--workload", "--pipeline", "--all", "--verify", "--draft", "--ragged", "--stream"):
+        assert flag in r.stdout
