@@ -255,8 +255,8 @@ template <int BK, int NR>
 __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int nP, int k, int W, int32_t* __restrict__ order,
                                                             float* __restrict__ resid, GreedyCtl* ctl) {
   extern __shared__ double Lblk[];        // [BK][nP]
-  __shared__ unsigned long long red[16];
-  __shared__ double sh_piv;
+  __shared__ unsigned long long red[2][16];   // per wave: its best key and that row's residual, double-buffered by
+  __shared__ double red_rho[2][16];           // step parity so that a step needs one barrier only
   __shared__ int s_flag;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i16 = lane & 15, kq = lane >> 4;
   if (tid == 0) s_flag = (int)atomicAdd(&ctl[0].ticket, 1u);
@@ -282,25 +282,34 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
   __syncthreads();
 
   for (int t = 0; t < k; ++t) {
-    const int jj = t % BK;
-    // ---- argmax over the unpicked rows of float(rho), lowest index on ties
+    const int jj = t % BK, par = t & 1;
+    // ---- argmax over the unpicked rows of float(rho), lowest index on ties.  Keys are distinct, so exactly one
+    //      lane of a wave holds the wave's best and posts it with its residual.  One barrier per step: what a
+    //      step writes besides is read only behind the next step's barrier, and the posts alternate buffers.
     unsigned long long best = 0ull;
+    double brho = 0.0;
 #pragma unroll
     for (int s = 0; s < NR; ++s) {
       if (!picked[s]) {
         const unsigned long long key =
             ((unsigned long long)float_order_key((float)rho[s]) << 32) | (0xFFFFFFFFu - (uint32_t)(tid + TPB * s));
-        best = key > best ? key : best;
+        if (key > best) { best = key; brho = rho[s]; }
       }
     }
-    best = wave_max(best);
-    if (lane == 0) red[w] = best;
+    {
+      const unsigned long long wbest = wave_max(best);
+      if (wbest == 0ull) { if (lane == 0) red[par][w] = 0ull; }
+      else if (best == wbest) { red[par][w] = wbest; red_rho[par][w] = brho; }
+    }
     __syncthreads();
-    best = red[0];
+    best = red[par][0];
+    int wq = 0;
 #pragma unroll
-    for (int q = 1; q < TPB / 64; ++q) best = red[q] > best ? red[q] : best;
+    for (int q = 1; q < TPB / 64; ++q)
+      if (red[par][q] > best) { best = red[par][q]; wq = q; }
+    const double rp = red_rho[par][wq];
     const int p = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));     // < n: k <= n, so an unpicked row exists
-    if ((unsigned)p >= (unsigned)n) {   // never index with anything else
+    if (best == 0ull || (unsigned)p >= (unsigned)n) {   // never index with anything else
       if (tid == 0) __hip_atomic_store(&cb->bar.failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       alive = false;
       break;
@@ -308,7 +317,7 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
     if ((p & (TPB - 1)) == tid) {
 #pragma unroll
       for (int s = 0; s < NR; ++s)
-        if (s == (p >> 10)) { sh_piv = rho[s]; picked[s] = true; }
+        if (s == (p >> 10)) picked[s] = true;
     }
     // ---- the pivot's row of R, minus what this block has already taken out (summed apart, so that the sum
     //      does not wait for the row)
@@ -333,8 +342,6 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
 #pragma unroll
       for (int s = 0; s < NR; ++s) c[s] -= taken[s];
     }
-    __syncthreads();        // sh_piv written; red may be rewritten next step
-    const double rp = sh_piv;
     const double piv = rp > 0.0 ? rp : 0.0;
     const double root = sqrt(piv);
 #pragma unroll
@@ -345,9 +352,9 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
       rho[s] -= col * col;
     }
     if (slot == 0 && tid == 0) { order[(long)b * k + t] = p; resid[(long)b * k + t] = (float)rp; }
-    __syncthreads();        // the column is visible to the next step's products
     if (jj == BK - 1 && t + 1 < k) {
-      // every workgroup of the image has read its last row of the old R
+      // every workgroup of the image has read its last row of the old R (the wait starts with a barrier of
+      // the workgroup, behind which the block's columns are complete in LDS)
       target += (unsigned int)W;
       alive = image_barrier_wait(&cb->bar, target, &s_flag);
       if (!alive) break;
