@@ -6,8 +6,12 @@
 // argmax rho (decided on the fp32-rounded value, ties -> lower index), forms the new
 // Cholesky column l = (G[:,p] - L L[p,:]^T) / sqrt(rho_p) and updates rho -= l^2.
 //
-// The k steps are dependent, but inside a step the rows are independent, so an image is
-// spread over nP/64 workgroups of 64 rows each: a workgroup keeps rho of its rows in
+// Three kernels, chosen by launch_greedy from the values each would move: the right-looking panel kernel
+// (greedy_panel_kernel, the usual choice), and two left-looking ones for the case that the picks are a small
+// part of the rows, on several workgroups per image (greedy_kernel) or one (greedy_single_kernel).
+//
+// Left-looking on several workgroups (greedy_kernel).  The k steps are dependent, but inside a step the rows are
+// independent, so an image is spread over nP/64 workgroups of 64 rows each: a workgroup keeps rho of its rows in
 // registers, posts its best (key, rho) per step, all workgroups of the image meet at a
 // barrier in global memory (one per step), read the posts, agree on the pivot p, fetch
 // the pivot's Cholesky row L[p, 0..t) and extend their own 64 rows of L.  L is stored
