@@ -255,6 +255,27 @@ __global__ __launch_bounds__(TPB) void greedy_single_kernel(const double* __rest
 // 16-row bands of R up to date, and they meet again before the next block reads rows of R: two barriers per
 // block instead of one per pick, and the device's bandwidth on the update instead of one workgroup's.
 // Dynamic LDS: BK * nP doubles; workgroups take (image, slot) from the ticket counter.
+// Maximum of one 64-bit key per lane over the wave with DPP moves (no LDS round trips): quads, then shifts by 4 and
+// 8 inside a row of 16 lanes, then the last lane of a row broadcast into the next row (rows 1 and 3) and lane 31
+// into rows 2 and 3, which leaves the maximum in lane 63.  Lanes without a source take 0, the identity for keys.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ unsigned long long dpp_key(unsigned long long v) {
+  const unsigned lo = __builtin_amdgcn_update_dpp(0u, (unsigned)v, CTRL, ROW_MASK, 0xf, false);
+  const unsigned hi = __builtin_amdgcn_update_dpp(0u, (unsigned)(v >> 32), CTRL, ROW_MASK, 0xf, false);
+  return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long wave_max_key(unsigned long long v) {
+  unsigned long long o;
+  o = dpp_key<0xb1, 0xf>(v); v = o > v ? o : v;      // quad_perm [1,0,3,2]
+  o = dpp_key<0x4e, 0xf>(v); v = o > v ? o : v;      // quad_perm [2,3,0,1]
+  o = dpp_key<0x114, 0xf>(v); v = o > v ? o : v;     // row_shr:4
+  o = dpp_key<0x118, 0xf>(v); v = o > v ? o : v;     // row_shr:8
+  o = dpp_key<0x142, 0xa>(v); v = o > v ? o : v;     // row_bcast:15 into rows 1 and 3
+  o = dpp_key<0x143, 0xc>(v); v = o > v ? o : v;     // row_bcast:31 into rows 2 and 3
+  const unsigned lo = __builtin_amdgcn_readlane((unsigned)v, 63), hi = __builtin_amdgcn_readlane((unsigned)(v >> 32), 63);
+  return ((unsigned long long)hi << 32) | lo;
+}
+
 template <int BK, int NR>
 __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int nP, int k, int W, int32_t* __restrict__ order,
                                                             float* __restrict__ resid, GreedyCtl* ctl) {
@@ -301,7 +322,7 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
       }
     }
     {
-      const unsigned long long wbest = wave_max(best);
+      const unsigned long long wbest = wave_max_key(best);
       if (wbest == 0ull) { if (lane == 0) red[par][w] = 0ull; }
       else if (best == wbest) { red[par][w] = wbest; red_rho[par][w] = brho; }
     }
