@@ -64,6 +64,11 @@ def _gen(w, workers=16):
     return out
 
 
+def _wname(w):
+    return "%d:%s B=%d N=%d d=%d T=%d H=%d K=%d k=%d M=%d r=%d" % (
+        w.cid, w.name, w.batch, w.n_tokens, w.d_model, w.n_query, w.n_heads, w.n_act_layers, w.keep_k, w.preselect_m, w.rank_r)
+
+
 def time_reduce(C, p, dev, ws, steps, warmup):
     """Wall-clock ms per step of covspec_reduce, K steps bracketed by synchronisation."""
     import torch
@@ -347,6 +352,45 @@ def ragged_bench(a):
     print(json.dumps(line), flush=True)
 
 
+def ablation_bench(a):
+    """--ablations: what each term of the selector costs, own JSON line.
+
+    covspec_reduce on the chosen workload (default 5) with the selector variants of Table II and Sec. III-A.3:
+    the paper's selector; the M -> k cut on the fused score alone (no low-rank stage); random tokens (no scores at
+    all); full-token (k = M = N: scores are computed, everything is kept and gathered); query-only (lambda = 1) and
+    activity-only (lambda = 0) scores in front of the paper's low-rank stage.
+    """
+    from dataclasses import replace
+    import torch
+    import covspec_inputs as I
+    import paper_2605_02218_amd as C
+    C.load_library()
+    torch.cuda.set_device(0)
+    w = I.WORKLOADS[a.workload]
+    dev = _upload(_gen(w), w.dtype)
+    base = _params(C, w, 0, 0)
+    cases = {
+        "paper selector": base,
+        "fused-score top-k (no low-rank stage)": replace(base, lr_mode=C.LR_SCORE_TOPK),
+        "random tokens (no scores)": replace(base, lr_mode=C.LR_RANDOM, seed=1),
+        "full-token (k = M = N, score-only cut)": replace(base, lr_mode=C.LR_SCORE_TOPK, keep_k=w.n_tokens, preselect_m=w.n_tokens),
+        "query-only scores (lambda = 1)": replace(base, lam=1.0),
+        "activity-only scores (lambda = 0)": replace(base, lam=0.0),
+    }
+    res = {}
+    for name, p in cases.items():
+        ws = C.alloc_workspace(p)
+        res[name] = round(time_reduce(C, p, dev, ws, a.steps, a.warmup), 4)
+        del ws
+    ms = res["paper selector"]
+    line = {"metric": "images/sec for visual-token reduction (score+select+gather)", "value": round(w.batch / ms * 1e3, 3), "unit": "images/s",
+            "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16" if w.dtype == I.BF16 else "f64", "data": "synthetic",
+            "config": {"workload": _wname(w), "entry_point": "covspec_reduce", "pipeline": "selector ablations"},
+            "ms_per_step_by_selector": res}
+    print(json.dumps(line), flush=True)
+
+
 def stream_bench(a):
     """--stream: covspec_stream_step in its steady state, own JSON line.
 
@@ -442,6 +486,7 @@ def main():
     ap.add_argument("--verify", action="store_true", help="time the speculative verification step instead (own JSON line)")
     ap.add_argument("--draft", action="store_true", help="time the draft-side margin gate / candidate pass instead (own JSON line)")
     ap.add_argument("--ragged", action="store_true", help="time covspec_reduce_ragged on a dynamic-resolution batch (own JSON line)")
+    ap.add_argument("--ablations", action="store_true", help="time the selector ablations on the chosen workload (own JSON line)")
     ap.add_argument("--stream", action="store_true", help="time covspec_stream_step in its steady state (own JSON line)")
     ap.add_argument("--no-comparison", action="store_true", help="with --stream: leave out the from-scratch comparison (clean kernel profiles)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -473,6 +518,9 @@ def main():
         return
     if a.stream:
         stream_bench(a)
+        return
+    if a.ablations:
+        ablation_bench(a)
         return
     import covspec_inputs as I
     import paper_2605_02218_amd as C

@@ -117,6 +117,9 @@ int covspec_resolve(const covspec_params* p, int32_t* keep_k, int32_t* preselect
  *   s_query, s_act, s_fused [B, N] fp32 outputs; each may be NULL (s_act is untouched when the
  *                         activity term is dropped)
  * Both scores are min-max normalised per image before fusion; a constant score normalises to 0.
+ * A score whose weight in the fusion is zero (lambda = 1: activity, lambda = 0: query relevance, with
+ * hidden states given) is computed only when its output pointer is not NULL: 0 * score is an exact
+ * zero for finite scores, so s_fused is the same; covspec_reduce passes no score outputs and skips it.
  */
 int covspec_score(const covspec_params* p, const void* X, const void* hidden, const void* Q,
                   const void* Wq, const void* Wk, float* s_query, float* s_act, float* s_fused,

@@ -197,7 +197,13 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
     return f64 ? launch_gemm64_nt(g, a_mid, b_mid, st) : launch_gemm_nt(g, DT_BF16, st);
   };
 
+  // A score whose weight in the fusion is zero is computed only if the caller asked for it (selector ablations,
+  // Table II: query-only is lambda = 1, activity-only lambda = 0); 0 * score adds an exact zero for finite scores.
+  const bool need_q = s_query != nullptr || q.lambda > 0.f || !has_act;
+  const bool need_a = has_act && (s_act != nullptr || q.lambda < 1.f);
+
   marks.mark(COVSPEC_STAGE_QUERY_SIDE);
+  auto query_scores = [&]() -> int {
   // e(q) = q Wq
   if (Wq) {
     HIPCHK(launch_transpose(Wq, at<void>(ws, q.wqT), q.d, q.d, q.dtype, st));
@@ -283,11 +289,22 @@ int run_score(const Plan& q, const void* X, const void* hidden, const void* Q, c
     HIPCHK(launch_softmax_stats(S, f64, stats, B * q.H * T, q.N, scale, base2, st));
     HIPCHK(launch_softmax_mean(S, f64, stats, sq, q.B, q.H * q.T, q.N, scale, base2 ? at<void>(ws, q.smean) : nullptr, st));
   }
+  return COVSPEC_OK;
+  };
+  if (need_q) {
+    const int rc = query_scores();
+    if (rc != COVSPEC_OK) return rc;
+  } else {
+    marks.mark(COVSPEC_STAGE_TOKEN_PROJECTION);
+    marks.mark(COVSPEC_STAGE_RELEVANCE);
+  }
 
   marks.mark(COVSPEC_STAGE_ACTIVITY);
-  if (has_act) HIPCHK(launch_activity(hidden, sa, q.B, q.N, q.d, q.K, q.dtype, st));
+  if (need_a) HIPCHK(launch_activity(hidden, sa, q.B, q.N, q.d, q.K, q.dtype, st));
   marks.mark(COVSPEC_STAGE_FUSE);
-  HIPCHK(launch_fuse(sq, sa, sf, q.B, q.N, q.lambda, st));
+  // with one score left the fused score is that score, min-max normalised
+  if (need_q) HIPCHK(launch_fuse(sq, need_a ? sa : nullptr, sf, q.B, q.N, q.lambda, st));
+  else HIPCHK(launch_fuse(sa, nullptr, sf, q.B, q.N, q.lambda, st));
   return COVSPEC_OK;
 }
 

@@ -17,5 +17,5 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_help_lists_every_mode():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--help"], capture_output=True, text=True, timeout=60)
     assert r.returncode == 0
-    for flag in ("--gpus", "--steps", "--warmup", "--workload", "--pipeline", "--all", "--verify", "--draft", "--ragged", "--stream"):
+    for flag in ("--gpus", "--steps", "--warmup", "--workload", "--pipeline", "--all", "--verify", "--draft", "--ragged", "--stream", "--ablations"):
         assert flag in r.stdout

@@ -173,16 +173,19 @@ def test_selector_ablations_match_oracle(C, name):
                 np.testing.assert_array_equal(_cpu(out["idx_m"])[b], O.top_indices(sf32[b], w.preselect_m))
 
 
+@pytest.mark.parametrize("rel_mode", [0, 1])
 @pytest.mark.parametrize("lam", [0.0, 1.0])
-def test_activity_only_and_query_only_fusion(C, lam):
+def test_activity_only_and_query_only_fusion(C, lam, rel_mode):
+    # covspec_score is asked for all three scores and computes both terms; covspec_reduce asks for none and
+    # skips the term whose weight is zero: the fused scores and the kept indices are the oracle's either way
     w = SMALL["bf16-ragged"]
     batch = U.gen_batch(w)
     dev = U.upload(batch, w.dtype)
-    p = U.lib_params(C, w, w.batch, lam=lam)
+    p = U.lib_params(C, w, w.batch, lam=lam, rel_mode=rel_mode)
     _, _, sf = C.score(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
     idx, _ = C.reduce(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
     for b in range(w.batch):
-        ref = U.oracle_image(w, batch, b, U.oracle_params(w, lam=lam))
+        ref = U.oracle_image(w, batch, b, U.oracle_params(w, lam=lam, rel_mode=rel_mode))
         U.assert_scores_close(_cpu(sf)[b], ref["s_fused"], w.dtype, "s_fused lambda %g" % lam)
         np.testing.assert_array_equal(_cpu(idx)[b], ref["idx"])
 
