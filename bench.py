@@ -546,6 +546,10 @@ def main():
             else "variant: attention-softmax relevance + greedy residual picks", "entry_point": "covspec_reduce"},
         "roofline": roofline_for(w, p, modes, stages, probe_ms, C),
         "stages_ms": {k: round(v, 4) for k, v in stages.items()},
+        # the stages grouped by the entry point that runs them on its own
+        "entry_points_ms": {"covspec_score": round(sum(stages[k] for k in ("query_side", "token_projection", "relevance", "activity", "fuse")), 4),
+                            "covspec_select": round(sum(stages[k] for k in ("preselect", "gram", "lowrank", "keep")), 4),
+                            "gather": round(stages["gather"], 4)},
     }
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, batch, *modes)
