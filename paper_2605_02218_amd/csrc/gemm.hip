@@ -31,7 +31,13 @@ template <typename In> struct Tr;
 template <> struct Tr<bf16_t> { static constexpr int BK = 64; static constexpr int ESZ = 2; };
 template <> struct Tr<float> { static constexpr int BK = 32; static constexpr int ESZ = 4; };
 
-__device__ __forceinline__ int swz(int row, int chunk) { return row * ROWB + ((chunk ^ (row & 7)) << 4); }
+// Two 128-byte rows fill the 64 banks once, so rows of equal parity share their banks: the 16-byte chunk index is
+// XORed with bits 1-3 of the row, which puts any 16 consecutive rows' chunk c on 16 distinct bank groups (one
+// ds_read_b128 of 16 lanes is then free of conflicts; with bits 0-2 as the key rows r and r + 8 collided, and the
+// bank-conflict counter read more conflict cycles than active ones).  8-byte reads of 32 consecutive rows (the
+// fp32 path) additionally swap the two halves of a chunk in rows with bit 4 set: swz_half.
+__device__ __forceinline__ int swz(int row, int chunk) { return row * ROWB + ((chunk ^ ((row >> 1) & 7)) << 4); }
+__device__ __forceinline__ int swz_half(int row) { return (row & 16) >> 1; }   // 0 or 8 bytes
 
 struct TileMap { int b, tm, tn; };
 
@@ -120,11 +126,13 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_kernel(GemmArgs g, int tiles_
   auto lstore = [&](int st, const u32x4_t (&ra_)[NS], const u32x4_t (&rb_)[NS]) {
     unsigned char* sa = smem + st * STAGE;
     unsigned char* sb = sa + BT * ROWB;
+    const bool flip = ESZ == 4 && (lrow & 16);     // fp32: rows with bit 4 set keep the halves of a chunk swapped
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       int r = lrow + 32 * s;
-      *(u32x4_t*)(sa + swz(r, lchunk)) = ra_[s];
-      *(u32x4_t*)(sb + swz(r, lchunk)) = rb_[s];
+      const u32x4_t va = ra_[s], vb = rb_[s];
+      *(u32x4_t*)(sa + swz(r, lchunk)) = flip ? (u32x4_t){va[2], va[3], va[0], va[1]} : va;
+      *(u32x4_t*)(sb + swz(r, lchunk)) = flip ? (u32x4_t){vb[2], vb[3], vb[0], vb[1]} : vb;
     }
   };
 
@@ -173,9 +181,9 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_kernel(GemmArgs g, int tiles_
 #pragma unroll
         for (int i = 0; i < TW; ++i) {
           int r = wm * WT + i * 32 + li;
-          af[i] = *(const float2*)(sa + swz(r, ch) + 8 * lh);
+          af[i] = *(const float2*)(sa + swz(r, ch) + ((8 * lh) ^ swz_half(r)));
           int c = wn * WT + i * 32 + li;
-          bfr[i] = *(const float2*)(sb + swz(c, ch) + 8 * lh);
+          bfr[i] = *(const float2*)(sb + swz(c, ch) + ((8 * lh) ^ swz_half(c)));
         }
 #pragma unroll
         for (int i = 0; i < TW; ++i)
