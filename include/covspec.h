@@ -320,6 +320,24 @@ int covspec_verify(const covspec_verify_params* p, const void* z_target, const v
                    void* workspace, size_t workspace_bytes, covspec_stream_t stream);
 
 /*
+ * covspec_verify for callers that cannot allocate device memory or have no workspace to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors
+ * as covspec_verify without the workspace: the per-chunk sums go to a device array that is part of the library
+ * (COVSPEC_VERIFY_STATIC_MAX_SCRATCH bytes on every device the library runs on, held until the process ends).
+ * The call allocates and frees nothing and synchronises nothing; the array's address is looked up on the first
+ * call on a device.  Shapes whose workspace (covspec_verify_workspace_size) exceeds the array are refused with
+ * COVSPEC_UNSUPPORTED before anything is launched (covspec_last_error() then names both sizes).  All calls on one
+ * device share the array: two calls that may overlap on a device (different streams, or threads) race on it and
+ * give undefined results; calls on one stream are ordered and safe.  Nothing in the array needs clearing between
+ * calls: every value a call reads it has written itself.
+ */
+#define COVSPEC_VERIFY_STATIC_MAX_SCRATCH (1u << 20)
+int covspec_verify_static(const covspec_verify_params* p, const void* z_target, const void* z_draft,
+                          const int32_t* tokens, const float* u_accept, const float* u_resample,
+                          int32_t* n_accept_out, int32_t* correction_out, float* alpha_out,
+                          covspec_stream_t stream);
+
+/*
  * Draft-side vocabulary pass: margin gate (paper Sec. III-B, the margin and gating equations) and
  * bonus-token candidates for parallel branching (Sec. III-C, the fan-out equation and the candidate
  * rule), from one read of the draft logits.  For each of n_seq sequences and each position

@@ -23,7 +23,7 @@ OK, INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP_ERROR = 0, 1, 2, 3, 4
 
 EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspec_select",
            "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string",
-           "covspec_verify_workspace_size", "covspec_verify", "covspec_draft_fanout", "covspec_draft_workspace_size",
+           "covspec_verify_workspace_size", "covspec_verify", "covspec_verify_static", "covspec_draft_fanout", "covspec_draft_workspace_size",
            "covspec_draft_gate", "covspec_last_error", "covspec_ragged_resolve", "covspec_ragged_workspace_size",
            "covspec_reduce_ragged", "covspec_lowrank_path", "covspec_stream_workspace_size", "covspec_stream_step")
 
@@ -97,6 +97,8 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_verify_workspace_size.argtypes = [vpp]
     lib.covspec_verify.restype = ctypes.c_int
     lib.covspec_verify.argtypes = [vpp] + [vp] * 8 + [vp, ctypes.c_size_t, vp]
+    lib.covspec_verify_static.restype = ctypes.c_int
+    lib.covspec_verify_static.argtypes = [vpp] + [vp] * 8 + [vp]
     dpp = ctypes.POINTER(CovspecDraftParams)
     lib.covspec_draft_fanout.restype = ctypes.c_int
     lib.covspec_draft_fanout.argtypes = [dpp, ctypes.POINTER(ctypes.c_int32)]
@@ -331,6 +333,22 @@ def verify(p: VerifyParams, z_target, z_draft, tokens, u_accept, u_resample, wor
     if st != OK:
         raise CovspecError(st, "covspec_verify")
     return n_acc, corr, alpha
+
+
+VERIFY_STATIC_MAX_SCRATCH = 1 << 20
+
+
+def verify_static(p: VerifyParams, z_target, z_draft, tokens, u_accept, u_resample, n_accept_out, correction_out,
+                  alpha_out=None):
+    """covspec_verify_static: as verify(), with the scratch in the library's own device array and every output
+    supplied by the caller, so that the call allocates nothing."""
+    cs = p.c_struct()
+    st = load_library().covspec_verify_static(ctypes.byref(cs), _ptr(z_target), _ptr(z_draft), _ptr(tokens),
+                                              _ptr(u_accept), _ptr(u_resample), _ptr(n_accept_out),
+                                              _ptr(correction_out), _ptr(alpha_out), _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_verify_static")
+    return n_accept_out, correction_out, alpha_out
 
 
 @dataclass

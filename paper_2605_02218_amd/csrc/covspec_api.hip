@@ -5,6 +5,8 @@
 #include <math.h>
 #include <stdio.h>
 
+#include <atomic>
+
 #include "../../include/covspec.h"
 #include "kernels.h"
 
@@ -652,6 +654,56 @@ int covspec_verify(const covspec_verify_params* p, const void* z_target, const v
   discard_pending_error();
   const hipError_t e = launch_verify(z_target, z_draft, tokens, u_accept, u_resample, p->n_seq, p->n_draft, p->vocab, p->dtype,
                                      n_accept_out, correction_out, alpha_out, workspace, (hipStream_t)stream);
+  if (e != hipSuccess) note_error("launch_verify", e);
+  return e == hipSuccess ? COVSPEC_OK : COVSPEC_HIP_ERROR;
+}
+
+// ---- covspec_verify for callers that cannot allocate: the per-chunk sums live in a device array of the library.
+//
+// `scratch` below is, in host code, only a stand-in for the symbol: it is never passed to a kernel or a runtime call.
+// Its address on a device comes from hipGetSymbolAddress, looked up once per device with that device current (every
+// device holds its own copy of the array at its own address) and kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = COVSPEC_VERIFY_STATIC_MAX_SCRATCH;
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::atomic<void*> g_scratch_ptr[kStaticMaxDevices];
+
+// Device address of `scratch` on the current device (nullptr and *err set on failure).
+static void* static_scratch_of_current_device(hipError_t* err) {
+  int dev = -1;
+  if ((*err = hipGetDevice(&dev)) != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kStaticMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr) return ptr;
+  if ((*err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) != hipSuccess) return nullptr;
+  if (!ptr) { *err = hipErrorInvalidSymbol; return nullptr; }
+  g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // two threads racing here store the same address
+  return ptr;
+}
+
+int covspec_verify_static(const covspec_verify_params* p, const void* z_target, const void* z_draft, const int32_t* tokens,
+                          const float* u_accept, const float* u_resample, int32_t* n_accept_out, int32_t* correction_out,
+                          float* alpha_out, covspec_stream_t stream) {
+  const int st = verify_check(p);
+  if (st != COVSPEC_OK) return st;
+  if (!z_target || !z_draft || !tokens || !u_accept || !u_resample || !n_accept_out || !correction_out) return COVSPEC_INVALID_ARG;
+  if (((uintptr_t)z_target | (uintptr_t)z_draft) & 15) return COVSPEC_INVALID_ARG;
+  const size_t need = verify_workspace_bytes(p->n_seq, p->n_draft, p->vocab, p->dtype);
+  if (need > kStaticScratchBytes) {
+    snprintf(g_last_error, sizeof(g_last_error), "covspec_verify_static: %zu bytes of scratch needed, the static array holds %zu",
+             need, kStaticScratchBytes);
+    return COVSPEC_UNSUPPORTED;
+  }
+  discard_pending_error();
+  hipError_t e = hipSuccess;
+  void* ws = static_scratch_of_current_device(&e);
+  if (!ws) {
+    note_error("hipGetSymbolAddress of the static scratch array", e);
+    return COVSPEC_HIP_ERROR;
+  }
+  // every partial sum the kernels read was written earlier in the same call, so nothing has to be cleared
+  e = launch_verify(z_target, z_draft, tokens, u_accept, u_resample, p->n_seq, p->n_draft, p->vocab, p->dtype, n_accept_out,
+                    correction_out, alpha_out, ws, (hipStream_t)stream);
   if (e != hipSuccess) note_error("launch_verify", e);
   return e == hipSuccess ? COVSPEC_OK : COVSPEC_HIP_ERROR;
 }

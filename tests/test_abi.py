@@ -124,6 +124,21 @@ def test_verify_params_are_validated_on_the_host():
     assert lib.covspec_verify(None, fake, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == Bd.INVALID_ARG
 
 
+def test_static_scratch_verify_validates_on_the_host():
+    """covspec_verify_static refuses bad arguments and shapes beyond its array before it touches a device."""
+    lib = C.load_library()
+    fake = 4096
+    big = C.VerifyParams(4096, 15, 151936, C.BF16)
+    assert C.verify_workspace_size(big) > C.VERIFY_STATIC_MAX_SCRATCH
+    cs = big.c_struct()
+    assert lib.covspec_verify_static(ctypes.byref(cs), fake, fake, fake, fake, fake, fake, fake, None, None) == Bd.UNSUPPORTED
+    assert b"static array" in lib.covspec_last_error()
+    cs = C.VerifyParams(4, 8, 4096, C.BF16).c_struct()
+    assert lib.covspec_verify_static(ctypes.byref(cs), None, fake, fake, fake, fake, fake, fake, None, None) == Bd.INVALID_ARG
+    assert lib.covspec_verify_static(ctypes.byref(cs), fake, fake + 8, fake, fake, fake, fake, fake, None, None) == Bd.INVALID_ARG
+    assert lib.covspec_verify_static(None, fake, fake, fake, fake, fake, fake, fake, None, None) == Bd.INVALID_ARG
+
+
 def test_draft_params_validation_and_fanout_match_the_oracle_formula():
     """covspec_draft_fanout is host arithmetic: F_j = ceil(F_0 rho^j) must agree with the oracle's evaluation for
     every (F_0, rho) on a grid, exact powers of two included (rho is a float32 in the parameter block)."""
