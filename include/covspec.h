@@ -19,8 +19,10 @@
  *    are valid once the caller has synchronised the stream.
  *  - Arguments are validated on the host before anything is launched.  Return
  *    value: COVSPEC_OK or one of the codes below; no exception crosses the ABI.
- *  - The library keeps no global state; concurrent calls are safe when they use
- *    distinct workspaces.
+ *  - The library keeps no state between calls apart from per-process caches of device properties
+ *    (kernel attributes, how many workgroups of a kernel a device holds at once), kept per device and
+ *    filled once, and the thread-local text of covspec_last_error(); concurrent calls are safe when
+ *    they use distinct workspaces.
  *  - The eigen-solve and the greedy picks of covspec_select / covspec_reduce spread an image over
  *    several workgroups (at most 64) that wait for one another inside one launch, so such a launch
  *    needs that many workgroup slots of the device at the same time.  Alone on the device it always
@@ -53,7 +55,7 @@ enum {
   COVSPEC_INVALID_ARG = 1,         /* NULL required pointer, bad size / mode / lambda ...        */
   COVSPEC_WORKSPACE_TOO_SMALL = 2, /* workspace_bytes < covspec_workspace_size(params)            */
   COVSPEC_UNSUPPORTED = 3,         /* valid request outside the kernels' limits (see below)       */
-  COVSPEC_HIP_ERROR = 4            /* a launch failed; hipGetLastError() still holds the cause    */
+  COVSPEC_HIP_ERROR = 4            /* a launch failed; covspec_last_error() names the cause       */
 };
 
 enum { COVSPEC_FP32 = 0, COVSPEC_BF16 = 1,
@@ -299,8 +301,8 @@ int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols
  *   u_accept          [n_seq, n_draft] fp32;  u_resample [n_seq] fp32
  *   n_accept_out      [n_seq] int32 (required);  correction_out [n_seq] int32 (required)
  *   alpha_out         [n_seq, n_draft] fp32 (or NULL)
- * Limits: vocab a multiple of 8 (bf16, fp16) or 4 (fp32), 2 <= vocab, n_seq * n_draft <= 65535, else
- * COVSPEC_UNSUPPORTED.  The workspace (covspec_verify_workspace_size bytes, 256-byte aligned, owned
+ * Limits: vocab a multiple of 8 (bf16, fp16) or 4 (fp32), 2 <= vocab, n_draft <= 64, n_seq * n_draft <= 65535,
+ * else COVSPEC_UNSUPPORTED.  The workspace (covspec_verify_workspace_size bytes, 256-byte aligned, owned
  * by the caller, contents undefined between calls) holds per-chunk partial sums.  Work is enqueued on
  * `stream`; the call does not synchronise and allocates nothing.  Returns a covspec_status.
  */
@@ -344,7 +346,9 @@ int covspec_verify_static(const covspec_verify_params* p, const void* z_target, 
  * j = 0..n_draft-1 of its drafted segment, with p_d = softmax(z_draft[s, j, :]):
  *   margin[s, j] = p_(1) - p_(2), the two largest probabilities;
  *   gate[s, j]   = 0 if margin >= gamma (commit locally), 1 otherwise (verify); compared in fp32;
- *   F_j          = ceil(fanout0 * rho^j), evaluated on the host in double precision with pow();
+ *   F_j          = ceil(fanout0 * rho^j), evaluated on the host in double precision (a product within 1e-12
+ *                  relative above an integer counts as that integer, so that a decimal rho gives the value of
+ *                  the decimal formula: fanout0 = 30, rho = 0.1 gives F_1 = 3);
  *   cand[s, j, 0..F_j-1] = the F_j words with the largest draft logits other than tokens[s, j], by
  *                  descending logit, the lower word first among equal logits; entries from F_j (or from
  *                  vocab - 1, if smaller) up to fanout0 are -1.
@@ -353,7 +357,7 @@ int covspec_verify_static(const covspec_verify_params* p, const void* z_target, 
  *   z_draft [n_seq, n_draft, vocab] dtype;  tokens [n_seq, n_draft] int32 (a value outside [0, vocab)
  *   excludes nothing);  margin_out [n_seq, n_draft] fp32 (required);  gate_out [n_seq, n_draft] int32
  *   (required);  cand_out [n_seq, n_draft, fanout0] int32 (required unless fanout0 == 0).
- * Limits: 0 <= fanout0 <= 32, 0 < rho <= 1, n_draft <= 64, n_seq * n_draft <= 65535, vocab a multiple of
+ * Limits: 0 <= fanout0 <= 32, 0 < rho < 1, n_draft <= 64, n_seq * n_draft <= 65535, vocab a multiple of
  * 8 (bf16, fp16) or 4 (fp32) and at most 524288, else COVSPEC_INVALID_ARG / COVSPEC_UNSUPPORTED.  Workspace as
  * for covspec_verify (covspec_draft_workspace_size bytes, 256-byte aligned).  Enqueues on `stream`,
  * does not synchronise, allocates nothing.  Returns a covspec_status.
@@ -364,7 +368,7 @@ typedef struct covspec_draft_params {
   int32_t vocab;    /* V                                                    */
   int32_t dtype;    /* covspec_dtype of the logits                          */
   int32_t fanout0;  /* F_0: candidates at the first position                */
-  float rho;        /* decay of the fan-out, 0 < rho <= 1                   */
+  double rho;       /* decay of the fan-out, 0 < rho < 1                    */
   float gamma;      /* margin threshold of the gate                         */
 } covspec_draft_params;
 

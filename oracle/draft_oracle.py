@@ -15,9 +15,8 @@ Per drafted position tau with draft logits z_d [V] and drafted token y:
 
 Readings where the paper is silent: the gate compares the margin rounded to float32 with gamma as float32
 (the precision the library returns the margin in); equal logits are ordered by the lower word index, in the
-top-2 and in the candidate list; candidates are listed by descending logit; F_j is evaluated in float64 with
-the C library's pow (Python's ** on floats) and a vocabulary with fewer than F_j other words yields fewer
-candidates.
+top-2 and in the candidate list; candidates are listed by descending logit; F_j is the exact ceiling of F_0 rho^j for the decimal
+rho (rational arithmetic) and a vocabulary with fewer than F_j other words yields fewer candidates.
 
 Parity status: pinned by tests/test_draft_oracle_pins.py (closed forms for two words and for one boosted
 word, the fan-out sequence for rho = 1/2, brute-force repeated argmax, invariants).
@@ -25,6 +24,7 @@ word, the fan-out sequence for rho = 1/2, brute-force repeated argmax, invariant
 from __future__ import annotations
 
 import math
+from fractions import Fraction
 from typing import Dict, List
 
 import numpy as np
@@ -48,8 +48,11 @@ def gate(m: float, gamma: float) -> int:
 
 
 def fanout(f0: int, rho: float, n: int) -> List[int]:
-    """F_j = ceil(F_0 rho^j), j = 0..n-1 (fan-out equation, Sec. III-C)."""
-    return [int(math.ceil(f0 * float(rho) ** j)) for j in range(n)]
+    """F_j = ceil(F_0 rho^j), j = 0..n-1 (fan-out equation, Sec. III-C), in exact rational arithmetic: rho is
+    taken as the decimal number its shortest representation spells (0.1 is one tenth), so an exact integer is never
+    tipped over by the binary rounding of rho or of the power."""
+    q = Fraction(repr(float(rho)))
+    return [int(math.ceil(f0 * q ** j)) for j in range(n)]
 
 
 def candidates(zd: np.ndarray, y: int, f: int) -> np.ndarray:

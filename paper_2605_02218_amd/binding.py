@@ -41,7 +41,7 @@ class CovspecVerifyParams(ctypes.Structure):
 
 class CovspecDraftParams(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("n_seq", "n_draft", "vocab", "dtype", "fanout0")] + [
-        ("rho", ctypes.c_float), ("gamma", ctypes.c_float)]
+        ("rho", ctypes.c_double), ("gamma", ctypes.c_float)]
 
 
 class CovspecRagged(ctypes.Structure):

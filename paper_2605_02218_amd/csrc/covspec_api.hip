@@ -631,7 +631,8 @@ static int verify_check(const covspec_verify_params* p) {
   if (!p) return COVSPEC_INVALID_ARG;
   if (p->n_seq < 1 || p->n_draft < 1 || p->vocab < 2) return COVSPEC_INVALID_ARG;
   if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16 && p->dtype != COVSPEC_FP16) return COVSPEC_INVALID_ARG;
-  if ((long)p->n_seq * p->n_draft > 65535) return COVSPEC_UNSUPPORTED;
+  // one lane per drafted position in the acceptance kernel (alpha of every position is written in one pass)
+  if (p->n_draft > 64 || (long)p->n_seq * p->n_draft > 65535) return COVSPEC_UNSUPPORTED;
   if (p->vocab % (p->dtype == COVSPEC_FP32 ? 4 : 8) != 0) return COVSPEC_UNSUPPORTED;
   return COVSPEC_OK;
 }
@@ -712,7 +713,7 @@ static int draft_check(const covspec_draft_params* p) {
   if (!p) return COVSPEC_INVALID_ARG;
   if (p->n_seq < 1 || p->n_draft < 1 || p->vocab < 2 || p->fanout0 < 0) return COVSPEC_INVALID_ARG;
   if (p->dtype != COVSPEC_FP32 && p->dtype != COVSPEC_BF16 && p->dtype != COVSPEC_FP16) return COVSPEC_INVALID_ARG;
-  if (!(p->rho > 0.f && p->rho <= 1.f) || !(p->gamma == p->gamma)) return COVSPEC_INVALID_ARG;
+  if (!(p->rho > 0.0 && p->rho < 1.0) || !(p->gamma == p->gamma)) return COVSPEC_INVALID_ARG;   // Sec. III-C: 0 < rho < 1
   if (p->fanout0 > 32 || p->n_draft > 64 || (long)p->n_seq * p->n_draft > 65535) return COVSPEC_UNSUPPORTED;
   if (p->vocab % (p->dtype == COVSPEC_FP32 ? 4 : 8) != 0 || p->vocab > draft_max_vocab()) return COVSPEC_UNSUPPORTED;
   return COVSPEC_OK;
@@ -722,7 +723,12 @@ int covspec_draft_fanout(const covspec_draft_params* p, int32_t* fanout_out) {
   const int st = draft_check(p);
   if (st != COVSPEC_OK) return st;
   if (!fanout_out) return COVSPEC_INVALID_ARG;
-  for (int j = 0; j < p->n_draft; ++j) fanout_out[j] = (int32_t)ceil((double)p->fanout0 * pow((double)p->rho, (double)j));
+  // F_j = ceil(F_0 rho^j).  rho is a double, so a decimal rho arrives as its nearest double; the product is then
+  // off the decimal formula's value by a few 1e-16 relative, which must not tip an exact integer over (F_0 = 30,
+  // rho = 0.1: 30 * 0.1 = 3.0000000000000004 in doubles): a product within 1e-12 relative above an integer
+  // counts as that integer.
+  for (int j = 0; j < p->n_draft; ++j)
+    fanout_out[j] = (int32_t)ceil((double)p->fanout0 * pow(p->rho, (double)j) * (1.0 - 1e-12));
   return COVSPEC_OK;
 }
 

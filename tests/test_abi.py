@@ -110,7 +110,7 @@ def test_verify_params_are_validated_on_the_host():
     for bad, status in [(C.VerifyParams(0, 8, 4096), Bd.INVALID_ARG), (C.VerifyParams(4, 0, 4096), Bd.INVALID_ARG),
                         (C.VerifyParams(4, 8, 1), Bd.INVALID_ARG), (C.VerifyParams(4, 8, 4096, 3), Bd.INVALID_ARG),
                         (C.VerifyParams(4, 8, 4100, C.BF16), Bd.UNSUPPORTED), (C.VerifyParams(4, 8, 4098, C.FP32), Bd.UNSUPPORTED),
-                        (C.VerifyParams(8192, 8, 4096), Bd.UNSUPPORTED)]:
+                        (C.VerifyParams(8192, 8, 4096), Bd.UNSUPPORTED), (C.VerifyParams(4, 65, 4096), Bd.UNSUPPORTED)]:
         assert C.verify_workspace_size(bad) == 0
         cs = bad.c_struct()
         assert lib.covspec_verify(ctypes.byref(cs), fake, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == status
@@ -136,26 +136,30 @@ def test_static_scratch_verify_validates_on_the_host():
     cs = C.VerifyParams(4, 8, 4096, C.BF16).c_struct()
     assert lib.covspec_verify_static(ctypes.byref(cs), None, fake, fake, fake, fake, fake, fake, None, None) == Bd.INVALID_ARG
     assert lib.covspec_verify_static(ctypes.byref(cs), fake, fake + 8, fake, fake, fake, fake, fake, None, None) == Bd.INVALID_ARG
+    cs = C.VerifyParams(4, 65, 4096, C.BF16).c_struct()
+    assert lib.covspec_verify_static(ctypes.byref(cs), fake, fake, fake, fake, fake, fake, fake, None, None) == Bd.UNSUPPORTED
     assert lib.covspec_verify_static(None, fake, fake, fake, fake, fake, fake, fake, None, None) == Bd.INVALID_ARG
 
 
 def test_draft_params_validation_and_fanout_match_the_oracle_formula():
-    """covspec_draft_fanout is host arithmetic: F_j = ceil(F_0 rho^j) must agree with the oracle's evaluation for
-    every (F_0, rho) on a grid, exact powers of two included (rho is a float32 in the parameter block)."""
-    import numpy as np
+    """covspec_draft_fanout is host arithmetic: F_j = ceil(F_0 rho^j) must agree with the oracle's exact rational
+    evaluation for every (F_0, rho) on a grid, exact powers of two and decimal rho whose products are exact
+    integers included (rho is a double in the parameter block)."""
     from oracle import draft_oracle as DO
-    assert ctypes.sizeof(Bd.CovspecDraftParams) == 7 * 4
-    for f0 in (0, 1, 2, 5, 8, 16, 32):
-        for rho in (0.5, 0.25, 0.6, 0.7, 0.9, 1.0, 1 / 3, 0.999):
+    assert ctypes.sizeof(Bd.CovspecDraftParams) == 40     # 5 int32, padding, double, float, padding
+    for f0 in (0, 1, 2, 5, 8, 10, 16, 20, 30, 32):
+        for rho in (0.5, 0.25, 0.6, 0.7, 0.9, 0.1, 0.2, 0.3, 0.05, 1 / 3, 0.999):
             p = C.DraftParams(n_seq=2, n_draft=12, vocab=4096, fanout0=f0, rho=rho)
-            assert C.draft_fanout(p) == DO.fanout(f0, float(np.float32(rho)), 12), (f0, rho)
+            assert C.draft_fanout(p) == DO.fanout(f0, rho, 12), (f0, rho)
+    assert C.draft_fanout(C.DraftParams(1, 3, 4096, fanout0=10, rho=0.1)) == [10, 1, 1]
+    assert C.draft_fanout(C.DraftParams(1, 3, 4096, fanout0=30, rho=0.1)) == [30, 3, 1]
     assert C.draft_fanout(C.DraftParams(1, 6, 4096, fanout0=8, rho=0.5)) == [8, 4, 2, 1, 1, 1]
     lib = C.load_library()
     ok = C.DraftParams(4, 8, 8192)
     assert C.draft_workspace_size(ok) > 0
     fake = 4096
     for bad, status in [(C.DraftParams(0, 8, 8192), Bd.INVALID_ARG), (C.DraftParams(4, 8, 8192, rho=0.0), Bd.INVALID_ARG),
-                        (C.DraftParams(4, 8, 8192, rho=1.5), Bd.INVALID_ARG), (C.DraftParams(4, 8, 8192, gamma=float("nan")), Bd.INVALID_ARG),
+                        (C.DraftParams(4, 8, 8192, rho=1.5), Bd.INVALID_ARG), (C.DraftParams(4, 8, 8192, rho=1.0), Bd.INVALID_ARG), (C.DraftParams(4, 8, 8192, gamma=float("nan")), Bd.INVALID_ARG),
                         (C.DraftParams(4, 8, 8192, fanout0=-1), Bd.INVALID_ARG), (C.DraftParams(4, 8, 8192, fanout0=33), Bd.UNSUPPORTED),
                         (C.DraftParams(4, 65, 8192), Bd.UNSUPPORTED), (C.DraftParams(4, 8, 8196, C.BF16), Bd.UNSUPPORTED),
                         (C.DraftParams(4, 8, 524288 + 8), Bd.UNSUPPORTED), (C.DraftParams(2000, 64, 8192), Bd.UNSUPPORTED)]:

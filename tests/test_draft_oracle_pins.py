@@ -42,6 +42,12 @@ def test_fanout_sequence():
     assert DO.fanout(8, 0.5, 6) == [8, 4, 2, 1, 1, 1]         # ceil(8 * 2^-j); never below one
     assert DO.fanout(5, 0.6, 4) == [5, 3, 2, 2]               # 5, 3.0, 1.8, 1.08
     assert DO.fanout(1, 0.9, 3) == [1, 1, 1]
+    # decimal rho whose products are exact integers in the fan-out equation: binary rounding of rho or of the power
+    # must not tip them over (10 * 0.1 = 1, 30 * 0.1 = 3, 20 * 0.3^2 = 1.8, 100 * 0.7^2 = 49)
+    assert DO.fanout(10, 0.1, 3) == [10, 1, 1]
+    assert DO.fanout(30, 0.1, 3) == [30, 3, 1]
+    assert DO.fanout(20, 0.3, 3) == [20, 6, 2]
+    assert DO.fanout(100, 0.7, 3) == [100, 70, 49]
     f = DO.fanout(16, 0.7, 12)
     assert f[0] == 16 and all(a >= b >= 1 for a, b in zip(f, f[1:]))
 
