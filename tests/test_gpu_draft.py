@@ -36,7 +36,7 @@ def _run(zd, tok, dtype, f0, rho, gamma):
 
 def _check(zd, tok, dtype, f0, rho, gamma, margin, gate, cand, seqs=None):
     S, L, V = zd.shape
-    rho32, gamma32 = float(np.float32(rho)), float(np.float32(gamma))
+    rho32, gamma32 = float(rho), float(np.float32(gamma))      # rho is a double in the parameter block
     for s in (range(S) if seqs is None else seqs):
         o = DO.draft_pass(I.as_f64(zd[s], dtype), tok[s], f0, rho32, gamma32)
         tol = 1e-5 * o["margin"] + 2e-6
@@ -59,7 +59,7 @@ def test_draft_gate_matches_oracle_small(dtype, V):
     _check(d["zd"], d["tok"], dtype, 6, 0.6, 0.3, m, g, c)
 
 
-@pytest.mark.parametrize("f0,rho", [(1, 0.5), (32, 0.9), (8, 1.0), (8, 0.5)])
+@pytest.mark.parametrize("f0,rho", [(1, 0.5), (32, 0.9), (8, 0.99), (10, 0.1), (8, 0.5)])
 def test_draft_gate_fanouts(f0, rho):
     d = I.make_verify_batch(2, 7, 3 * 8192, I.BF16, seed=f0)
     m, g, c = _run(d["zd"], d["tok"], I.BF16, f0, rho, 0.5)
