@@ -4,7 +4,8 @@
 A step is one covspec_reduce call over one batch of a synthetic workload whose inputs are
 already resident in HBM.  Prints ONE JSON line: images/sec, the roofline position of the
 dominant kernel (stage times measured live with HIP events recorded by the library on the
-work stream) and the CPU oracle timed on a bounded sample of the same workload.
+work stream), the CPU oracle timed on a bounded sample of the same workload, and images/sec of
+every workload in both pipelines.
 """
 from __future__ import annotations
 
@@ -21,17 +22,32 @@ if ROOT not in sys.path:
 # MI355X published peaks
 PEAK = {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0, "mfma_fp64_TFLOPs": 78.6, "valu_fp64_TFLOPs": 78.6}
 
-# Bytes per launch that crossed the L2 <-> memory-fabric boundary, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# runs of this program (summary and commands: profiles/reduce_workload5_paper_hbm_counters.txt), each counter
-# scaled by its reading for a device copy of 2^30 bytes (FETCH_SIZE reads half the bytes: factor 2.0; WRITE_SIZE
-# factor 1.0).  Keyed by (workload, kernel); None where not collected.
-TRAFFIC = {
-    (5, "gemm_nt_dma_kernel<rownorm2>"): 4424852 * 1024 * 2.0 + 23040 * 1024 * 1.0,
-    (5, "activity_kernel"): 3686457 * 1024 * 2.0 + 1994 * 1024 * 1.0,
-    # whole calls of the vocabulary passes at 64 x 8 x 151,936 bf16 (profiles/verify_draft_s64_l8_v151936_hbm_counters.txt)
-    ("verify", "whole call"): 166599 * 1024 * 2.0 + 86 * 1024 * 1.0,
-    ("draft", "whole call"): 77174 * 1024 * 2.0 + 1264 * 1024 * 1.0,
-}
+PROFILES = os.path.join(ROOT, "profiles")
+COUNTER_FILES = {"reduce5": "reduce_workload5_paper_hbm_counters.txt", "vocab": "verify_draft_s64_l8_v151936_hbm_counters.txt"}
+
+
+def counter_traffic(which, kernels):
+    """Bytes per launch that crossed the L2 <-> memory-fabric boundary for the kernels named (summed), read from the
+    tracked rocprofv3 --pmc summary under profiles/ (FETCH_SIZE and WRITE_SIZE in KiB per launch, each scaled by the
+    factor the summary's calibration line states for a plain copy of known size).  `kernels` are the names as the
+    profiler prints them (matched as prefixes of a table row).  None when the file, the calibration or one of the
+    kernels is missing: a summary that no longer covers the kernel that runs gives no figure rather than a stale one."""
+    import re
+    try:
+        text = open(os.path.join(PROFILES, COUNTER_FILES[which])).read()
+    except OSError:
+        return None
+    cal = re.search(r"FETCH_SIZE\[KiB\] \* 1024 \* (\d+\.\d+).*?WRITE_SIZE\[KiB\] \* 1024 \* (\d+\.\d+)", text, re.S)
+    if not cal:
+        return None
+    f_fetch, f_write = float(cal.group(1)), float(cal.group(2))
+    total = 0.0
+    for k in kernels:
+        row = re.search(r"^" + re.escape(k) + r"[^\n]*?\s{2,}(\d+)\s+(\d+)\s+(\d+)\s", text, re.M)
+        if not row:
+            return None
+        total += int(row.group(2)) * 1024 * f_fetch + int(row.group(3)) * 1024 * f_write
+    return total
 
 
 def _params(C, w, rel, lr):
@@ -69,21 +85,29 @@ def _wname(w):
         w.cid, w.name, w.batch, w.n_tokens, w.d_model, w.n_query, w.n_heads, w.n_act_layers, w.keep_k, w.preselect_m, w.rank_r)
 
 
-def time_reduce(C, p, dev, ws, steps, warmup):
-    """Wall-clock ms per step of covspec_reduce, K steps bracketed by synchronisation."""
+def time_reduce(C, p, dev, ws, steps, warmup, both=False):
+    """ms per step of covspec_reduce over K steps bracketed by synchronisation: the median of the per-call times
+    between HIP events recorded on the work stream before every call and after the last.  With `both`, also the
+    wall-clock mean over the same K steps (returned second)."""
+    import statistics
     import torch
     k, _, _ = C.resolve(p)
     idx = torch.empty(p.batch, k, dtype=torch.int32, device="cuda")
     tok = torch.empty(p.batch, k, p.d_model, dtype=dev["X"].dtype, device="cuda")
     args = (p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     for _ in range(warmup):
         C.reduce(*args, workspace=ws, idx_out=idx, tokens_out=tok)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
+    for i in range(steps):
+        ev[i].record()
         C.reduce(*args, workspace=ws, idx_out=idx, tokens_out=tok)
+    ev[steps].record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / steps
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    med = statistics.median(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    return (med, wall) if both else med
 
 
 def stage_times(C, p, dev, ws, steps):
@@ -146,8 +170,11 @@ def roofline_for(w, p, p_modes, stages, probe_ms, C):
     dom = max(cand, key=lambda s: cand[s][5] * cand[s][6])
     kern, bound, peak, unit, work, launches, ms = cand[dom]
     achieved = work / (ms / 1e3)
+    # the counter summary covers workload 5 in the paper pipeline; names as the profiler prints them
+    prof_name = {"gemm_nt_dma_kernel<rownorm2>": "gemm_nt_dma_kernel<1>", "activity_kernel": "activity_kernel<"}.get(kern)
+    traffic = counter_traffic("reduce5", [prof_name]) if (w.cid == 5 and p_modes == (0, 0) and prof_name) else None
     return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-            "frac": round(achieved / peak, 5), "traffic": TRAFFIC.get((w.cid, kern)), "kernel": kern,
+            "frac": round(achieved / peak, 5), "traffic": traffic, "kernel": kern,
             "launches_per_step": launches, "avg_launch_ms": round(ms, 5),
             "ms_per_step_in_kernel": round(ms * launches, 4)}
 
@@ -216,7 +243,7 @@ def verify_bench(a):
             "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "verify S=%d L=%d V=%d" % (S, L, V), "entry_point": "covspec_verify"},
             "roofline": {"bound": "hbm", "achieved": round(alg / (ms * 1e-3) / 1e9, 1), "peak": PEAK["hbm_GBps"], "unit": "GB/s",
-                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": TRAFFIC[("verify", "whole call")],
+                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": counter_traffic("vocab", ["verify_stats_kernel", "verify_accept_kernel", "verify_rowpass64_kernel", "verify_sample_kernel"]),
                          "kernel": "whole call (verify_stats_kernel streams the logits)", "device_ms": round(ms, 4)}}
     if not a.no_cpu_baseline:
         from oracle import verify_oracle as VO
@@ -270,7 +297,7 @@ def draft_bench(a):
             "config": {"workload": "draft gate S=%d L=%d V=%d F0=%d rho=%g gamma=%g" % (S, L, V, F0, rho, gamma),
                        "entry_point": "covspec_draft_gate"},
             "roofline": {"bound": "hbm", "achieved": round(alg / (ms * 1e-3) / 1e9, 1), "peak": PEAK["hbm_GBps"], "unit": "GB/s",
-                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": TRAFFIC[("draft", "whole call")],
+                         "frac": round(alg / (ms * 1e-3) / 1e9 / PEAK["hbm_GBps"], 4), "traffic": counter_traffic("vocab", ["draft_scan_kernel", "draft_merge_kernel"]),
                          "kernel": "whole call (draft_scan_kernel streams the logits)", "device_ms": round(ms, 4)}}
     if not a.no_cpu_baseline:
         from oracle import draft_oracle as DO
@@ -482,7 +509,9 @@ def main():
     ap.add_argument("--workload", type=int, default=5, help="1..5 (default 5: the largest single-GPU workload)")
     ap.add_argument("--pipeline", choices=["paper", "variant"], default="paper")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all", action="store_true", help="also time the other workloads and pipeline (extra keys)")
+    ap.add_argument("--all", action="store_true", help="(default behaviour now) time every workload in both pipelines")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time only the chosen workload and pipeline (short runs under a profiler)")
     ap.add_argument("--verify", action="store_true", help="time the speculative verification step instead (own JSON line)")
     ap.add_argument("--draft", action="store_true", help="time the draft-side margin gate / candidate pass instead (own JSON line)")
     ap.add_argument("--ragged", action="store_true", help="time covspec_reduce_ragged on a dynamic-resolution batch (own JSON line)")
@@ -533,12 +562,13 @@ def main():
     dev = _upload(batch, w.dtype)
     p = _params(C, w, *modes)
     ws = C.alloc_workspace(p)
-    ms = time_reduce(C, p, dev, ws, a.steps, a.warmup)
+    ms, wall_ms = time_reduce(C, p, dev, ws, a.steps, a.warmup, both=True)
     stages, probe_ms = stage_times(C, p, dev, ws, min(a.steps, 10))
     line = {
         "metric": "images/sec for visual-token reduction (score+select+gather)",
         "value": round(w.batch / ms * 1e3, 3), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms, 4), "ms_per_step_wall_mean": round(wall_ms, 4), "timing": "median of per-call HIP event times",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == I.BF16 else "f64", "data": "synthetic",
         "config": {"workload": "%d:%s B=%d N=%d d=%d T=%d H=%d K=%d k=%d M=%d r=%d" % (
             w.cid, w.name, w.batch, w.n_tokens, w.d_model, w.n_query, w.n_heads, w.n_act_layers, w.keep_k,
@@ -553,14 +583,16 @@ def main():
     }
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, batch, *modes)
-    if a.all:
-        extra = {}
+    if not a.headline_only:
+        # every workload in both pipelines (images/s of covspec_reduce, whole batch per call, inputs generated once
+        # per workload): the other nine figures beside the headline one
+        table = {"%d:%s" % (w.cid, a.pipeline): round(w.batch / ms * 1e3, 2)}
         other = (1, 1) if modes == (0, 0) else (0, 0)
         p2 = _params(C, w, *other)
         ws2 = C.alloc_workspace(p2)
-        extra["%d:%s" % (w.cid, "variant" if other == (1, 1) else "paper")] = round(
-            w.batch / time_reduce(C, p2, dev, ws2, max(3, a.steps // 4), 2) * 1e3, 2)
-        del ws2, dev, ws
+        table["%d:%s" % (w.cid, "variant" if other == (1, 1) else "paper")] = round(
+            w.batch / time_reduce(C, p2, dev, ws2, max(5, a.steps // 2), 2) * 1e3, 2)
+        del ws2, dev, ws, batch
         for cid in sorted(I.WORKLOADS):
             if cid == w.cid:
                 continue
@@ -570,11 +602,11 @@ def main():
                 po = _params(C, wo, *m)
                 wso = C.alloc_workspace(po)
                 # small batches are latency-bound and their first calls see the clocks ramp up: more warm-up and steps
-                extra["%d:%s" % (cid, name)] = round(wo.batch / time_reduce(C, po, devo, wso, 10 if wo.batch <= 8 else 3, 3) * 1e3, 2)
+                table["%d:%s" % (cid, name)] = round(wo.batch / time_reduce(C, po, devo, wso, 20 if wo.batch <= 8 else 10, 5) * 1e3, 2)
                 del wso
             del devo
             torch.cuda.empty_cache()
-        line["other_images_per_s"] = extra
+        line["images_per_s_by_workload_and_pipeline"] = dict(sorted(table.items()))
     print(json.dumps(line), flush=True)
 
 
