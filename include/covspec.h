@@ -26,9 +26,10 @@
  *  - The eigen-solve and the greedy picks of covspec_select / covspec_reduce spread an image over
  *    several workgroups (at most 64) that wait for one another inside one launch, so such a launch
  *    needs that many workgroup slots of the device at the same time.  Alone on the device it always
- *    has them.  Every such wait is bounded (2 s of wall clock): if other work holds the device for
- *    longer, the call still ends, COVSPEC_OK has long been returned, and the image concerned comes back
- *    with NaN energies (or NaN residuals) and valid but meaningless kept indices.  Keep concurrent
+ *    has them.  Every such wait is bounded (2 s of wall clock unless covspec_set_wait_limit_us says
+ *    otherwise): if other work holds the device for longer, the call still ends, COVSPEC_OK has long been
+ *    returned, and the image concerned comes back with NaN energies (or NaN residuals) and valid but
+ *    meaningless kept indices; covspec_image_status reports which images these are.  Keep concurrent
  *    calls of these two entry points to COVSPEC_MAX_CONCURRENT_CALLS per device.
  *  - Ties in every ranking go to the lower index.  Ranking decisions are taken
  *    on the fp32 score values that the library returns.
@@ -272,6 +273,28 @@ int covspec_stream_step(const covspec_stream_params* p, int32_t n_keep, int32_t 
  */
 int covspec_lowrank_path(const covspec_params* p, const void* workspace, int32_t* path_out,
                          covspec_stream_t stream);
+
+/*
+ * Per-image outcome of the LAST covspec_select / covspec_reduce call with these parameters on this workspace:
+ * status_out (DEVICE int32 [B]) is 0 for an image whose result is valid and 1 for an image whose eigen-solve or
+ * greedy picks gave up because a workgroup waited for the others of its image beyond the wait limit (the device
+ * was held by other work).  For such an image the kept indices and gathered tokens are meaningless (energies and
+ * residuals are NaN) and the call should be repeated.  The status word is cleared at the start of every call and
+ * only ever set by the kernels that wait; modes without such kernels (SCORE_TOPK, RANDOM) always report 0.
+ * Enqueued on `stream` behind the call in question; reads the workspace, writes nothing else.  (The selection
+ * method itself, paper Sec. III-A.3, has no failure case: this reports a property of the execution.)
+ * covspec_reduce_ragged keeps one status word per run inside its workspace slices and has no such query.
+ */
+int covspec_image_status(const covspec_params* p, const void* workspace, int32_t* status_out,
+                         covspec_stream_t stream);
+
+/*
+ * Wait limit of the multi-workgroup kernels (see the conventions above), process-wide, in microseconds of wall
+ * clock; read when a call is enqueued.  Values <= 0 restore the default of 2 000 000.  A limit shorter than a
+ * workgroup's normal wait (tens of microseconds) makes images give up spuriously: tests of the give-up path use
+ * that, every kernel still runs to its end.
+ */
+void covspec_set_wait_limit_us(int64_t microseconds);
 
 /*
  * Description of the probed launch for these parameters: number of equal launches per call (0 when

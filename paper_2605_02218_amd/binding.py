@@ -25,7 +25,7 @@ EXPORTS = ("covspec_workspace_size", "covspec_resolve", "covspec_score", "covspe
            "covspec_reduce", "covspec_reduce_staged", "covspec_probe_launches", "covspec_status_string",
            "covspec_verify_workspace_size", "covspec_verify", "covspec_verify_static", "covspec_draft_fanout", "covspec_draft_workspace_size",
            "covspec_draft_gate", "covspec_last_error", "covspec_ragged_resolve", "covspec_ragged_workspace_size",
-           "covspec_reduce_ragged", "covspec_lowrank_path", "covspec_stream_workspace_size", "covspec_stream_step")
+           "covspec_reduce_ragged", "covspec_lowrank_path", "covspec_image_status", "covspec_set_wait_limit_us", "covspec_stream_workspace_size", "covspec_stream_step")
 
 
 class CovspecParams(ctypes.Structure):
@@ -117,6 +117,10 @@ def load_library() -> ctypes.CDLL:
     lib.covspec_reduce_ragged.argtypes = [pp, rp] + [vp] * 7 + [vp, ctypes.c_size_t, ctypes.POINTER(vp), ctypes.c_int32]
     lib.covspec_lowrank_path.restype = ctypes.c_int
     lib.covspec_lowrank_path.argtypes = [pp, vp, vp, vp]
+    lib.covspec_image_status.restype = ctypes.c_int
+    lib.covspec_image_status.argtypes = [pp, vp, vp, vp]
+    lib.covspec_set_wait_limit_us.restype = None
+    lib.covspec_set_wait_limit_us.argtypes = [ctypes.c_int64]
     spp = ctypes.POINTER(CovspecStreamParams)
     lib.covspec_stream_workspace_size.restype = ctypes.c_size_t
     lib.covspec_stream_workspace_size.argtypes = [spp]
@@ -472,6 +476,23 @@ def lowrank_path(p: Params, workspace):
     if st != OK:
         raise CovspecError(st, "covspec_lowrank_path")
     return out
+
+
+def image_status(p: Params, workspace):
+    """covspec_image_status: int32 [B] tensor, 0 = valid, 1 = the image's multi-workgroup kernels gave up waiting."""
+    import torch
+    out = torch.empty(p.batch, dtype=torch.int32, device=workspace.device)
+    wp, _ = _ws_args(workspace)
+    cs = p.c_struct()
+    st = load_library().covspec_image_status(ctypes.byref(cs), wp, _ptr(out), _stream())
+    if st != OK:
+        raise CovspecError(st, "covspec_image_status")
+    return out
+
+
+def set_wait_limit_us(microseconds: int) -> None:
+    """covspec_set_wait_limit_us: wait limit of the multi-workgroup kernels (<= 0 restores the default)."""
+    load_library().covspec_set_wait_limit_us(int(microseconds))
 
 
 @dataclass

@@ -84,9 +84,9 @@ struct ImageBarrier {
   unsigned int arrived;
   int failed;
 };
-constexpr long long kBarrierLimitTicks = 200000000LL;   // 2 s
+constexpr long long kBarrierLimitTicks = 200000000LL;   // 2 s, the default of `limit_ticks`
 
-__device__ __forceinline__ bool image_barrier_wait(ImageBarrier* bar, unsigned int target, int* s_flag) {
+__device__ __forceinline__ bool image_barrier_wait(ImageBarrier* bar, unsigned int target, int* s_flag, long long limit_ticks) {
   // Every wave first waits until its own stores have been acknowledged by the L2 (vmcnt counts loads and
   // stores on this architecture); the cache maintenance itself acts on the CU's L1 and the XCD's L2, not on a
   // wave, so one thread issues it for the workgroup: write-back before the arrival, invalidate after the wait.
@@ -99,7 +99,7 @@ __device__ __forceinline__ bool image_barrier_wait(ImageBarrier* bar, unsigned i
     const long long t0 = wall_clock64();
     while (__hip_atomic_load(&bar->arrived, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
       if (__hip_atomic_load(&bar->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
-          wall_clock64() - t0 > kBarrierLimitTicks) {
+          wall_clock64() - t0 > limit_ticks) {
         ok = 0;
         break;
       }

@@ -33,7 +33,7 @@ struct Plan {
   int nP;         // Gram pitch (padded order of the eigen-solve)
   // workspace offsets (bytes)
   size_t wqT, wkT, Eq, qn2, Eq3, G3raw, G3, vn2p, logits, Ev, S, stats, smean, sq, sa, sf;
-  size_t idxm, Awork, ctl, lam, c, Lt, order, resid, gscr, sub, ok;
+  size_t idxm, Awork, ctl, lam, c, Lt, order, resid, gscr, sub, ok, status;
   int P;          // block size of the subspace iteration (0: full Jacobi solve)
   size_t total;
 };
@@ -114,6 +114,7 @@ int make_plan(const covspec_params* p, Plan* pl) {
   q.sa = take(BN * 4);
   q.sf = take(BN * 4);
   q.idxm = take(B * M * 4);
+  q.status = take(B * 4);       // per image: 1 when the bounded wait of a multi-workgroup kernel gave up
   q.Awork = q.ctl = q.lam = q.c = q.sub = q.ok = 0;
   q.P = 0;
   if (lowrank) {
@@ -315,6 +316,8 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
                int32_t* pick_order_out, float* resid_out, void* ws, hipStream_t st, StageMarks& marks) {
   const long N = q.N, d = q.d;
   marks.mark(COVSPEC_STAGE_PRESELECT);
+  int* img_status = at<int>(ws, q.status);
+  HIPCHK(launch_fill_int(img_status, q.B, 0, st));
   if (q.lr == COVSPEC_LR_SCORE_TOPK || q.lr == COVSPEC_LR_RANDOM) {
     // selector ablations (Table II; Sec. III-A.3, first sentence): one ranking, no low-rank stage
     const float* rank_by = s_fused;
@@ -370,15 +373,15 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
       int* ok = at<int>(ws, q.ok);
       const double* Ut = nullptr;
       HIPCHK(launch_subspace_eigen(A, q.B, q.M, q.nP, q.r, q.P, kSubspaceIters, kSubspaceMoreIters, at<void>(ws, q.sub), at<void>(ws, q.ctl),
-                                   at<double>(ws, q.lam), ok, &Ut, marks.ev ? marks.ev[COVSPEC_PROBE_BEGIN] : nullptr,
+                                   at<double>(ws, q.lam), ok, &Ut, img_status, marks.ev ? marks.ev[COVSPEC_PROBE_BEGIN] : nullptr,
                                    marks.ev ? marks.ev[COVSPEC_PROBE_END] : nullptr, st));
       probed = true;
-      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, img_status, st));
       marks.mark(COVSPEC_STAGE_KEEP);
       HIPCHK(launch_subspace_energy(Ut, q.B, q.P, q.M, q.nP, (long)q.P * q.nP, q.r, at<double>(ws, q.lam), c, ok, 1, st));
       HIPCHK(launch_subspace_energy(A, q.B, q.M, q.M, q.nP, (long)q.nP * q.nP, q.r, at<double>(ws, q.lam), c, ok, 0, st));
     } else {
-      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, img_status, st));
       marks.mark(COVSPEC_STAGE_KEEP);
       HIPCHK(launch_subspace_energy(A, q.B, q.M, q.M, q.nP, (long)q.nP * q.nP, q.r, at<double>(ws, q.lam), c, nullptr, 0, st));
     }
@@ -387,7 +390,7 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
     int32_t* order = at<int32_t>(ws, q.order);
     float* resid = resid_out ? resid_out : at<float>(ws, q.resid);
     marks.mark(COVSPEC_STAGE_LOWRANK);
-    HIPCHK(launch_greedy(A, q.B, q.M, q.nP, q.k, at<double>(ws, q.Lt), order, resid, at<void>(ws, q.gscr), st));
+    HIPCHK(launch_greedy(A, q.B, q.M, q.nP, q.k, at<double>(ws, q.Lt), order, resid, at<void>(ws, q.gscr), img_status, st));
     marks.mark(COVSPEC_STAGE_KEEP);
     HIPCHK(launch_greedy_finish(order, idxm, q.B, q.M, q.k, idx_out, pick_order_out, st));
   }
@@ -617,6 +620,21 @@ int covspec_lowrank_path(const covspec_params* p, const void* workspace, int32_t
   return COVSPEC_OK;
 }
 
+int covspec_image_status(const covspec_params* p, const void* workspace, int32_t* status_out, covspec_stream_t stream) {
+  Plan pl;
+  const int st = make_plan(p, &pl);
+  if (st != COVSPEC_OK) return st;
+  if (!workspace || !status_out || ((uintptr_t)workspace & 255u)) return COVSPEC_INVALID_ARG;
+  discard_pending_error();
+  HIPCHK(hipMemcpyAsync(status_out, (const char*)workspace + pl.status, (size_t)pl.B * sizeof(int32_t), hipMemcpyDeviceToDevice,
+                        (hipStream_t)stream));
+  return COVSPEC_OK;
+}
+
+void covspec_set_wait_limit_us(int64_t microseconds) {
+  set_barrier_limit_ticks(microseconds > 0 ? microseconds * 100 : 0);   // 100 ticks of the wall clock per microsecond
+}
+
 int covspec_probe_launches(const covspec_params* p, int32_t* rows, int32_t* cols, int32_t* inner) {
   Plan pl;
   if (make_plan(p, &pl) != COVSPEC_OK) return 0;
@@ -830,12 +848,12 @@ int covspec_stream_step(const covspec_stream_params* p, int32_t n_keep, int32_t 
       int* ok = at<int>(ws, q.ok);
       const double* Ut = nullptr;
       HIPCHK(launch_subspace_eigen(A, q.B, nC, q.nP, q.r, P, kSubspaceIters, kSubspaceMoreIters, at<void>(ws, q.sub), at<void>(ws, q.ctl),
-                                   at<double>(ws, q.lam), ok, &Ut, nullptr, nullptr, st));
-      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, st));
+                                   at<double>(ws, q.lam), ok, &Ut, nullptr, nullptr, nullptr, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, nullptr, st));
       HIPCHK(launch_subspace_energy(Ut, q.B, P, nC, q.nP, (long)P * q.nP, q.r, at<double>(ws, q.lam), c, ok, 1, st));
       HIPCHK(launch_subspace_energy(A, q.B, nC, nC, q.nP, gstride, q.r, at<double>(ws, q.lam), c, ok, 0, st));
     } else {
-      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, nullptr, st));
       HIPCHK(launch_subspace_energy(A, q.B, nC, nC, q.nP, gstride, q.r, at<double>(ws, q.lam), c, nullptr, 0, st));
     }
     int32_t* selw = at<int32_t>(ws, q.sel);

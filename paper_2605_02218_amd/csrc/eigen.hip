@@ -27,6 +27,7 @@
 // fp64 MFMA layouts (checked on the device): operand lane l holds (row|col = l%16,
 // k = l/16); result lane l, register v holds (row 4v + l/16, col l%16).
 #include "common.h"
+#include "host_cache.h"
 #include "kernels.h"
 
 namespace covspec {
@@ -321,7 +322,8 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
 // The whole solve of all images: workgroup (image b, slot pr) visits the pair `pr` of every tournament round
 // of every sweep; after a sweep, slot 0 decides convergence and re-measures which rows are the r longest.
 // A and len2 are written and re-read by different workgroups between barriers, hence no __restrict__.
-__global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, int nP, int nsb, int r, JacobiCtl* ctl, double* len2) {
+__global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, int nP, int nsb, int r, JacobiCtl* ctl, double* len2,
+                                                              int* img_status, long long limit_ticks) {
   const int npairs = nsb >> 1;
   const int tid = threadIdx.x;
   if (tid == 0) s_flag = (int)atomicAdd(&ctl[0].ticket, 1u);
@@ -347,7 +349,7 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
       const double meas = jacobi_visit(Ab, len2b, nP, I, J, round == 0, floor2, long2);
       if (tid == 0 && meas > 0.0) atomicMax(&cb->maxoff[sweep], (unsigned long long)__double_as_longlong(sqrt(meas)));
       target += npairs;
-      alive = image_barrier_wait(&cb->bar, target, &s_flag);
+      alive = image_barrier_wait(&cb->bar, target, &s_flag, limit_ticks);
     }
     if (!alive) break;
     // ---- end of the sweep: slot 0 decides convergence and finds the squared length of the r-th longest row
@@ -371,13 +373,14 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
       }
     }
     target += npairs;
-    alive = image_barrier_wait(&cb->bar, target, &s_flag);
+    alive = image_barrier_wait(&cb->bar, target, &s_flag, limit_ticks);
     if (alive && __hip_atomic_load(&cb->done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
   }
   if (!alive) {
     // a wait ran out: poison this slot's share of the rows so that nothing downstream passes for a result
     const double qnan = __longlong_as_double(0x7ff8000000000000LL);
     for (long e = tid; e < (long)PR * nP; e += 256) Ab[(long)pr * PR * nP + e] = qnan;
+    if (img_status && tid == 0) img_status[b] = 1;
   }
 }
 
@@ -435,26 +438,27 @@ __global__ __launch_bounds__(256) void energy_kernel(const double* __restrict__ 
 size_t jacobi_ctl_bytes(int B) { return sizeof(JacobiCtl) * (size_t)B; }
 int jacobi_pitch(int n) { return (n + PR - 1) / PR * PR; }
 
+namespace {
+std::atomic<long long> g_barrier_limit{kBarrierLimitTicks};
+}
+void set_barrier_limit_ticks(long long ticks) { g_barrier_limit.store(ticks > 0 ? ticks : kBarrierLimitTicks); }
+long long barrier_limit_ticks() { return g_barrier_limit.load(); }
+
 hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl_, double* len2, const int* preset_done,
-                               hipStream_t st) {
+                               int* img_status, hipStream_t st) {
   if (nP % 64 != 0 || n > nP || n > 4096 || r < 1 || r > n) return hipErrorInvalidValue;
   JacobiCtl* ctl = (JacobiCtl*)ctl_;
   const int nsb = nP / SB;  // even, since nP % 64 == 0
   const int npairs = nsb / 2;
   // the workgroups of one image wait for one another, so one image has to fit the device
-  static int capacity = 0;
-  if (capacity == 0) {
-    int dev = 0, per_cu = 0, cus = 0;
-    hipError_t e;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, jacobi_solve_kernel, 256, 0)) != hipSuccess) return e;
-    if (per_cu < 1 || cus < 1) return hipErrorInvalidValue;
-    capacity = per_cu * cus;
-  }
+  static PerDeviceInt cache;
+  int capacity = 0;
+  const hipError_t ec = resident_workgroups(cache, jacobi_solve_kernel, 256, 0, &capacity);
+  if (ec != hipSuccess) return ec;
   if (npairs > capacity) return hipErrorInvalidValue;
   hipLaunchKernelGGL(jacobi_init_kernel, dim3(B), dim3(256), 0, st, A, n, nP, ctl, preset_done);
-  hipLaunchKernelGGL(jacobi_solve_kernel, dim3((unsigned)(B * npairs)), dim3(256), 0, st, A, n, nP, nsb, r, ctl, len2);
+  hipLaunchKernelGGL(jacobi_solve_kernel, dim3((unsigned)(B * npairs)), dim3(256), 0, st, A, n, nP, nsb, r, ctl, len2,
+                     img_status, barrier_limit_ticks());
   return hipGetLastError();
 }
 

@@ -18,6 +18,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "host_cache.h"
 #include "kernels.h"
 
 namespace covspec {
@@ -475,7 +476,8 @@ hipError_t launch_dma(const GemmArgs& g, hipStream_t stream) {
   const long nblocks = (long)tiles_m * tiles_n * g.batch;
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
   auto kern = gemm_nt_dma_kernel<EPI>;
-  static hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  static PerDeviceInt raised;   // per instantiation
+  const hipError_t attr = ensure_dynamic_lds(raised, (const void*)kern, LDS);
   if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(THREADS), LDS, stream, g, tiles_m, tiles_n);
   return hipGetLastError();
@@ -490,7 +492,8 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
   if (nblocks <= 0) return hipSuccess;
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
   auto kern = gemm_nt_kernel<In, EPI, GATHER, TW>;
-  static hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  static PerDeviceInt raised;   // per instantiation
+  const hipError_t attr = ensure_dynamic_lds(raised, (const void*)kern, LDS);
   if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(THREADS), LDS, stream, g, tiles_m, tiles_n);
   return hipGetLastError();

@@ -16,6 +16,7 @@
 // holds (row 4v + l/16, col l%16).
 #include <type_traits>
 #include "common.h"
+#include "host_cache.h"
 #include "kernels.h"
 
 namespace covspec {
@@ -229,12 +230,9 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
   const size_t lds = (size_t)2 * (TM + TN) * PITCH * sizeof(double);
   auto kern = gemm64_kernel<TA, TB, EPI, GATHER, TRANSB, MI, NJ>;
   if (lds > 64 * 1024) {
-    static bool raised = false;   // per instantiation
-    if (!raised) {
-      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-      raised = true;
-    }
+    static PerDeviceInt raised;   // per instantiation
+    const hipError_t e = ensure_dynamic_lds(raised, (const void*)kern, lds);
+    if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(256), lds, stream, g, tiles_m, tiles_n);
   return hipGetLastError();

@@ -20,6 +20,7 @@
 // Workgroups take (image, slot) from a ticket counter, so the resident ones always form
 // whole images plus one partial image that is next in the dispatch order.
 #include "common.h"
+#include "host_cache.h"
 #include "kernels.h"
 
 namespace covspec {
@@ -43,7 +44,8 @@ __global__ void greedy_init_kernel(GreedyCtl* ctl, int B) {
 
 // posts: per image [2][W] keys (u64) then [2][W] rho (fp64), double-buffered by step parity
 __global__ __launch_bounds__(GT) void greedy_kernel(const double* __restrict__ G, int n, int nP, int k, double* Lt, int32_t* __restrict__ order,
-                                                     float* __restrict__ resid, GreedyCtl* ctl, unsigned long long* posts) {
+                                                     float* __restrict__ resid, GreedyCtl* ctl, unsigned long long* posts,
+                                                     int* img_status, long long limit_ticks) {
   __shared__ double Lp[4096];
   __shared__ double part[4][GR];
   __shared__ unsigned long long sh_key;
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(GT) void greedy_kernel(const double* __restrict__ G
       if (best == 0ull && lane == 0) keys[(t & 1) * W + slot] = 0ull;
     }
     target += (unsigned int)W;
-    alive = image_barrier_wait(&cb->bar, target, &s_flag);
+    alive = image_barrier_wait(&cb->bar, target, &s_flag, limit_ticks);
     if (!alive) break;
     // ---- global argmax over the posts
     if (w == 0) {
@@ -143,6 +145,7 @@ __global__ __launch_bounds__(GT) void greedy_kernel(const double* __restrict__ G
     // a wait ran out: leave valid (distinct) positions and poisoned residuals behind
     const float qnan = __uint_as_float(0x7fc00000u);
     for (int t = tid; t < k; t += GT) { order[(long)b * k + t] = t; resid[(long)b * k + t] = qnan; }
+    if (img_status && tid == 0) img_status[b] = 1;
   }
 }
 
@@ -278,7 +281,8 @@ __device__ __forceinline__ unsigned long long wave_max_key(unsigned long long v)
 
 template <int BK, int NR>
 __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int nP, int k, int W, int32_t* __restrict__ order,
-                                                            float* __restrict__ resid, GreedyCtl* ctl) {
+                                                            float* __restrict__ resid, GreedyCtl* ctl, int* img_status,
+                                                            long long limit_ticks) {
   extern __shared__ double Lblk[];        // [BK][nP]
   __shared__ unsigned long long red[2][16];   // per wave: its best key and that row's residual, double-buffered by
   __shared__ double red_rho[2][16];           // step parity so that a step needs one barrier only
@@ -381,7 +385,7 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
       // every workgroup of the image has read its last row of the old R (the wait starts with a barrier of
       // the workgroup, behind which the block's columns are complete in LDS)
       target += (unsigned int)W;
-      alive = image_barrier_wait(&cb->bar, target, &s_flag);
+      alive = image_barrier_wait(&cb->bar, target, &s_flag, limit_ticks);
       if (!alive) break;
       // ---- R -= Lblk^T Lblk on this workgroup's bands (band ti belongs to slot ti % W); a wave takes four
       //      neighbouring 16 x 16 tiles per trip and requests their 16 values of R before the first MFMA
@@ -419,7 +423,7 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
       }
       // every band is up to date before any workgroup reads a row of R again
       target += (unsigned int)W;
-      alive = image_barrier_wait(&cb->bar, target, &s_flag);
+      alive = image_barrier_wait(&cb->bar, target, &s_flag, limit_ticks);
       if (!alive) break;
       for (int e = tid; e < BK * nP; e += TPB) Lblk[e] = 0.0;
       __syncthreads();
@@ -429,6 +433,7 @@ __global__ __launch_bounds__(TPB) void greedy_panel_kernel(double* G, int n, int
     // a wait ran out: leave valid (distinct) positions and poisoned residuals behind
     const float qnan = __uint_as_float(0x7fc00000u);
     for (int t = tid; t < k; t += TPB) { order[(long)b * k + t] = t; resid[(long)b * k + t] = qnan; }
+    if (img_status && tid == 0) img_status[b] = 1;
   }
 }
 
@@ -466,28 +471,26 @@ size_t greedy_scratch_bytes(int B, int nP) {
 
 template <int BK, int NR>
 static hipError_t launch_panel(double* G, int B, int n, int nP, int k, int W, int32_t* order, float* resid, GreedyCtl* ctl,
-                               hipStream_t st) {
+                               int* img_status, hipStream_t st) {
   const size_t lds = (size_t)BK * nP * sizeof(double);
-  static size_t raised = 0;
-  if (lds > raised) {
-    hipError_t e = hipFuncSetAttribute((const void*)greedy_panel_kernel<BK, NR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    raised = lds;
-  }
-  // the workgroups of one image wait for one another, so one image has to fit the device
-  int dev = 0, per_cu = 0, cus = 0;
-  hipError_t e;
-  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-  if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-  if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (greedy_panel_kernel<BK, NR>), TPB, lds)) != hipSuccess) return e;
-  if (per_cu < 1 || cus < 1 || W > per_cu * cus) return hipErrorInvalidValue;
+  constexpr size_t kLdsMost = 159 * 1024;   // launch_greedy picks BK so that the block's columns stay below this
+  if (lds > kLdsMost) return hipErrorInvalidValue;
+  static PerDeviceInt raised, cache;   // per instantiation
+  hipError_t e = ensure_dynamic_lds(raised, (const void*)greedy_panel_kernel<BK, NR>, kLdsMost);
+  if (e != hipSuccess) return e;
+  // the workgroups of one image wait for one another, so one image has to fit the device; counted once per device
+  // for the largest LDS request, which never overstates what a smaller one gets
+  int capacity = 0;
+  if ((e = resident_workgroups(cache, greedy_panel_kernel<BK, NR>, TPB, kLdsMost, &capacity)) != hipSuccess) return e;
+  if (W > capacity) return hipErrorInvalidValue;
   hipLaunchKernelGGL(greedy_init_kernel, dim3((B + 255) / 256), dim3(256), 0, st, ctl, B);
-  hipLaunchKernelGGL((greedy_panel_kernel<BK, NR>), dim3((unsigned)(B * W)), dim3(TPB), lds, st, G, n, nP, k, W, order, resid, ctl);
+  hipLaunchKernelGGL((greedy_panel_kernel<BK, NR>), dim3((unsigned)(B * W)), dim3(TPB), lds, st, G, n, nP, k, W, order, resid, ctl,
+                     img_status, barrier_limit_ticks());
   return hipGetLastError();
 }
 
 hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
-                         hipStream_t st) {
+                         int* img_status, hipStream_t st) {
   if (nP % GR != 0 || n > nP || n > 4096 || k > n || k > 4096) return hipErrorInvalidValue;
   GreedyCtl* ctl = (GreedyCtl*)scratch;
   // the largest block of picks (a multiple of the MFMA's depth of 4) whose columns fit LDS beside the kernel's few
@@ -505,12 +508,12 @@ hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int
     Wp = Wp < 1 ? 1 : Wp > 32 ? 32 : Wp;
     Wp = Wp > nt ? nt : Wp;
     // rows per thread: at most 1216 rows with blocks of 16, 1664 with 12, 2496 with 8
-    if (BK == 16) return n <= TPB ? launch_panel<16, 1>(G, B, n, nP, k, Wp, order, resid, ctl, st)
-                                  : launch_panel<16, 2>(G, B, n, nP, k, Wp, order, resid, ctl, st);
-    if (BK == 12) return launch_panel<12, 2>(G, B, n, nP, k, Wp, order, resid, ctl, st);
-    if (BK == 8) return n <= 2 * TPB ? launch_panel<8, 2>(G, B, n, nP, k, Wp, order, resid, ctl, st)
-                                     : launch_panel<8, 4>(G, B, n, nP, k, Wp, order, resid, ctl, st);
-    return launch_panel<4, 4>(G, B, n, nP, k, Wp, order, resid, ctl, st);
+    if (BK == 16) return n <= TPB ? launch_panel<16, 1>(G, B, n, nP, k, Wp, order, resid, ctl, img_status, st)
+                                  : launch_panel<16, 2>(G, B, n, nP, k, Wp, order, resid, ctl, img_status, st);
+    if (BK == 12) return launch_panel<12, 2>(G, B, n, nP, k, Wp, order, resid, ctl, img_status, st);
+    if (BK == 8) return n <= 2 * TPB ? launch_panel<8, 2>(G, B, n, nP, k, Wp, order, resid, ctl, img_status, st)
+                                     : launch_panel<8, 4>(G, B, n, nP, k, Wp, order, resid, ctl, img_status, st);
+    return launch_panel<4, 4>(G, B, n, nP, k, Wp, order, resid, ctl, img_status, st);
   }
   const int W = nP / GR;
   // Left-looking: spreading an image over W workgroups costs a device-scope barrier per step; it pays while the
@@ -520,20 +523,15 @@ hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int
     return hipGetLastError();
   }
   // the workgroups of one image wait for one another, so one image has to fit the device
-  static int capacity = 0;
-  if (capacity == 0) {
-    int dev = 0, per_cu = 0, cus = 0;
-    hipError_t e;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, greedy_kernel, GT, 0)) != hipSuccess) return e;
-    if (per_cu < 1 || cus < 1) return hipErrorInvalidValue;
-    capacity = per_cu * cus;
-  }
+  static PerDeviceInt cache;
+  int capacity = 0;
+  const hipError_t ec = resident_workgroups(cache, greedy_kernel, GT, 0, &capacity);
+  if (ec != hipSuccess) return ec;
   if (W > capacity) return hipErrorInvalidValue;
   unsigned long long* posts = (unsigned long long*)((char*)scratch + (((size_t)B * sizeof(GreedyCtl) + 255) / 256) * 256);
   hipLaunchKernelGGL(greedy_init_kernel, dim3((B + 255) / 256), dim3(256), 0, st, ctl, B);
-  hipLaunchKernelGGL(greedy_kernel, dim3((unsigned)(B * W)), dim3(GT), 0, st, G, n, nP, k, Lt, order, resid, ctl, posts);
+  hipLaunchKernelGGL(greedy_kernel, dim3((unsigned)(B * W)), dim3(GT), 0, st, G, n, nP, k, Lt, order, resid, ctl, posts,
+                     img_status, barrier_limit_ticks());
   return hipGetLastError();
 }
 

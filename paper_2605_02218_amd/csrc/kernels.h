@@ -113,14 +113,21 @@ hipError_t launch_random_scores(float* out, int B, int N, uint32_t seed, int ima
 hipError_t launch_select_top(const float* scores, int B, int n, int m, const int32_t* map, int32_t* out,
                              hipStream_t stream);
 
+// Bound of every wait of one workgroup for the others of its image (eigen-solve, greedy picks), in ticks of the
+// 100 MHz wall clock; process-wide, read at launch.  ticks <= 0 restores the default of 2 s.
+void set_barrier_limit_ticks(long long ticks);
+long long barrier_limit_ticks();
+
 // ---------------------------------------------------------------- eigen.hip
 // One-sided block Jacobi on the rows of the symmetric PSD matrices A[b] (fp64, pitch nP = jacobi_pitch(n),
 // rows/cols >= n zero).  On return the r longest rows k of A[b] are lambda_k v_k^T (shorter rows only span the rest).  `ctl` is scratch of jacobi_ctl_bytes(B), `len2` scratch of B*nP doubles.
 size_t jacobi_ctl_bytes(int B);
 int jacobi_pitch(int n);      // row pitch (and padded order) the solver needs: n rounded up to 64
 // preset_done (optional, [B]): images whose entry is non-zero are left untouched.
+// img_status (optional, [B]): set to 1 for an image whose workgroups gave up waiting for one another (its rows
+// are then NaN); never cleared here.
 hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl, double* len2, const int* preset_done,
-                               hipStream_t stream);
+                               int* img_status, hipStream_t stream);
 hipError_t launch_row_lengths(const double* A, int B, int rows, int pitch, long img_stride, double* lam, hipStream_t stream);
 // Subspace energy (paper energy equation) from rows of the form lambda_k v_k^T: c[b,i] = sum over the r
 // longest of the `rows` rows of A[b] of A[k][i]^2 / |row k|, i < n.  A[b] starts at b*img_stride, rows have
@@ -140,8 +147,8 @@ size_t subspace_workspace_bytes(int B, int n, int nP, int P);
 // equal launches of the product Yt G (P x nP x nP per image).
 int subspace_product_launches(int iters);
 hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, int more_iters, void* ws, void* jacobi_ctl,
-                                 double* jacobi_len2, int* ok, const double** ut, hipEvent_t probe_begin, hipEvent_t probe_end,
-                                 hipStream_t stream);
+                                 double* jacobi_len2, int* ok, const double** ut, int* img_status, hipEvent_t probe_begin,
+                                 hipEvent_t probe_end, hipStream_t stream);
 
 // ---------------------------------------------------------------- greedy.hip
 // Greedy residual picks (variant): pivoted Cholesky of G[b] (fp64, pitch nP; G may be overwritten with the residual
@@ -149,8 +156,10 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
 // order[b,t] = local position picked at step t, resid[b,t] = residual squared norm at that pick.
 // nP % 64 == 0; `scratch` holds greedy_scratch_bytes(B, nP) bytes (barrier counters and per-step posts).
 size_t greedy_scratch_bytes(int B, int nP);
+// img_status (optional, [B]): set to 1 for an image whose workgroups gave up waiting for one another (order[b] is
+// then 0..k-1 and its residuals NaN); never cleared here.
 hipError_t launch_greedy(double* G, int B, int n, int nP, int k, double* Lt, int32_t* order, float* resid, void* scratch,
-                         hipStream_t stream);
+                         int* img_status, hipStream_t stream);
 // idx_out[b,:] = sort ascending of idx_m[b, order[b,:]];  pick_out[b,t] = idx_m[b, order[b,t]] (optional).
 hipError_t launch_greedy_finish(const int32_t* order, const int32_t* idx_m, int B, int M, int k, int32_t* idx_out,
                                 int32_t* pick_out, hipStream_t stream);

@@ -16,6 +16,7 @@
 // After the Ritz step the residuals |G u - theta u| of the r dominant Ritz pairs are checked; images
 // that fail (slow decay, P too small) fall back to the full block Jacobi solve of G.
 #include "common.h"
+#include "host_cache.h"
 #include "kernels.h"
 
 namespace covspec {
@@ -411,19 +412,14 @@ size_t subspace_workspace_bytes(int B, int n, int nP, int P) {
 int subspace_product_launches(int iters) { return iters + 2; }   // start block, one per iteration, residuals
 
 hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, int more_iters, void* ws_, void* jacobi_ctl,
-                                 double* jacobi_len2, int* ok, const double** ut, hipEvent_t probe_begin, hipEvent_t probe_end,
-                                 hipStream_t st) {
+                                 double* jacobi_len2, int* ok, const double** ut, int* img_status, hipEvent_t probe_begin,
+                                 hipEvent_t probe_end, hipStream_t st) {
   hipError_t e0;
   if (P <= 0 || P % NB != 0 || P > n || P > 4096 || nP % NB != 0) return hipErrorInvalidValue;
   if (iters < 2 || more_iters < 2 || (iters & 1) || (more_iters & 1)) return hipErrorInvalidValue;   // the two blocks swap roles per step
   {
-    static bool raised = false;
-    if (!raised) {
-      if ((e0 = hipFuncSetAttribute((const void*)chol_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)(kCholLdsFixed + 4096 * sizeof(double)))) != hipSuccess)
-        return e0;
-      raised = true;
-    }
+    static PerDeviceInt raised;
+    if ((e0 = ensure_dynamic_lds(raised, (const void*)chol_kernel, kCholLdsFixed + 4096 * sizeof(double))) != hipSuccess) return e0;
   }
   char* ws = (char*)ws_;
   const size_t blk = (size_t)B * P * nP * 8;
@@ -494,7 +490,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
       mask(g);
       if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
     }
-    if ((e = launch_jacobi_eigen(H, B, P, P, r, jacobi_ctl, jacobi_len2, masked ? (const int*)ok : nullptr, st)) != hipSuccess) return e;
+    if ((e = launch_jacobi_eigen(H, B, P, P, r, jacobi_ctl, jacobi_len2, masked ? (const int*)ok : nullptr, img_status, st)) != hipSuccess) return e;
     // rows of H are now theta_k w_k^T; Ut = H Q^T has rows theta_k u_k^T
     {
       GemmArgs g;

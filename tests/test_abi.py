@@ -94,6 +94,21 @@ def test_entry_points_reject_null_pointers_and_small_workspaces_before_any_launc
     assert lib.covspec_score(None, fake, None, fake, None, None, None, None, None, fake, 1 << 40, None) == Bd.INVALID_ARG
 
 
+def test_image_status_query_validates_on_the_host():
+    lib = C.load_library()
+    p = C.Params(batch=2, n_tokens=256, d_model=64, n_query=4, keep_k=16, preselect_m=32, rank_r=4)
+    cs = p.c_struct()
+    fake = 4096
+    assert lib.covspec_image_status(ctypes.byref(cs), None, fake, None) == Bd.INVALID_ARG
+    assert lib.covspec_image_status(ctypes.byref(cs), fake, None, None) == Bd.INVALID_ARG
+    assert lib.covspec_image_status(ctypes.byref(cs), fake + 8, fake, None) == Bd.INVALID_ARG      # workspace alignment
+    assert lib.covspec_image_status(None, fake, fake, None) == Bd.INVALID_ARG
+    bad = C.Params(batch=2, n_tokens=256, d_model=64, n_query=4, keep_k=64, preselect_m=32).c_struct()
+    assert lib.covspec_image_status(ctypes.byref(bad), fake, fake, None) == Bd.INVALID_ARG
+    lib.covspec_set_wait_limit_us(5)      # host-side setting only; restored to the default right away
+    lib.covspec_set_wait_limit_us(0)
+
+
 def test_status_strings():
     assert C.status_string(0) == "ok"
     assert "workspace" in C.status_string(2)
