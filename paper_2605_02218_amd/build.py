@@ -31,14 +31,16 @@ def _run(cmd):
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every source and link the shared library; always rebuilds."""
+    """Compile every source and link the shared library; always rebuilds.  COVSPEC_HIPCC_FLAGS (optional, space
+    separated) adds compiler flags, e.g. a -D that selects a kernel variant for a measurement."""
     os.makedirs(OBJDIR, exist_ok=True)
     hipcc = _hipcc()
+    flags = FLAGS + os.environ.get("COVSPEC_HIPCC_FLAGS", "").split()
     objs = [os.path.join(OBJDIR, s.replace(".hip", ".o")) for s in SOURCES]
 
     def one(pair):
         src, obj = pair
-        return _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        return _run([hipcc, *flags, "-c", os.path.join(CSRC, src), "-o", obj])
 
     with ThreadPoolExecutor(max_workers=min(10, len(SOURCES))) as ex:
         outs = list(ex.map(one, zip(SOURCES, objs)))

@@ -25,6 +25,9 @@ namespace covspec {
 
 namespace {
 
+#ifndef COVSPEC_DMA_STAGES
+#define COVSPEC_DMA_STAGES 4
+#endif
 constexpr int ROWB = 128;  // bytes per LDS row (one k-tile of a tile row)
 constexpr int THREADS = 256;
 
@@ -293,9 +296,9 @@ __device__ __forceinline__ int swz64(int row, int chunk) {
   return row * 64 + ((chunk ^ f) << 4);
 }
 
-template <int EPI>
+template <int EPI, int NST>
 __global__ __launch_bounds__(THREADS) void gemm_nt_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
-  constexpr int BT = 256, WT = 128, TW = 4, BK = 32, NST = 4;
+  constexpr int BT = 256, WT = 128, TW = 4, BK = 32;
   constexpr int STAGE = 2 * BT * 64;  // bytes: A tile then B tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_dma_kernel(GemmArgs g, int ti
     gb[j] = B + (long)rb * g.ldb + c * 8;
   }
   auto issue = [&](int kt) {
-    unsigned char* sa = smem + (kt & (NST - 1)) * STAGE + wave * 4096;
+    unsigned char* sa = smem + (kt % NST) * STAGE + wave * 4096;
     unsigned char* sb = sa + BT * 64;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -378,13 +381,14 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_dma_kernel(GemmArgs g, int ti
   // after the barrier the stage they came from may be overwritten.
   // The loop body is branch-free (the number of k-tiles is even): past the end, `issue` re-loads the
   // last tile into a stage nobody reads any more and `frags` reads a stage whose values are never used.
-  auto stage_ptr = [&](int kt) -> const unsigned char* { return smem + (kt & (NST - 1)) * STAGE; };
+  auto stage_ptr = [&](int kt) -> const unsigned char* { return smem + (kt % NST) * STAGE; };
   bf16x8_t a0[2][TW], b0[2][TW], a1[2][TW], b1[2][TW];   // [k-step][32-row group], two sets
   issue(0);
-  issue(min(1, nk - 1));
-  issue(min(2, nk - 1));
-  issue(min(3, nk - 1));
-  __builtin_amdgcn_s_waitcnt(0x4078);   // vmcnt(24) lgkmcnt(0): tile 0 has landed
+#pragma unroll
+  for (int q = 1; q < NST; ++q) issue(min(q, nk - 1));
+  // tile 0 has landed: at most the 8 (NST - 1) loads of the later tiles are outstanding
+  if (NST == 4) __builtin_amdgcn_s_waitcnt(0x4078);   // vmcnt(24) lgkmcnt(0)
+  else __builtin_amdgcn_s_waitcnt(0x8070);            // vmcnt(32) lgkmcnt(0)
   __builtin_amdgcn_s_barrier();
   frags(stage_ptr(0), 0, a0[0], b0[0]);
   frags(stage_ptr(0), 1, a0[1], b0[1]);
@@ -406,23 +410,25 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_dma_kernel(GemmArgs g, int ti
   };
   for (int kt = 0; kt < nk; kt += 2) {
     // even tile: set 0 feeds the MFMAs, set 1 is filled from tile kt+1
-    __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0): all but the two newest tiles have landed
+    if (NST == 4) __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0): all but the NST - 2 newest tiles have landed
+    else __builtin_amdgcn_s_waitcnt(0x4078);            // vmcnt(24)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     frags(stage_ptr(kt + 1), 0, a1[0], b1[0]);
     frags(stage_ptr(kt + 1), 1, a1[1], b1[1]);
-    issue(min(kt + 4, nk - 1));
+    issue(min(kt + NST, nk - 1));
     mma(a0[0], b0[0]);
     mma(a0[1], b0[1]);
     order();
     __builtin_amdgcn_sched_barrier(0);
     // odd tile: set 1 feeds the MFMAs, set 0 is filled from tile kt+2
-    __builtin_amdgcn_s_waitcnt(0x4070);
+    if (NST == 4) __builtin_amdgcn_s_waitcnt(0x4070);
+    else __builtin_amdgcn_s_waitcnt(0x4078);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     frags(stage_ptr(kt + 2), 0, a0[0], b0[0]);
     frags(stage_ptr(kt + 2), 1, a0[1], b0[1]);
-    issue(min(kt + 5, nk - 1));
+    issue(min(kt + NST + 1, nk - 1));
     mma(a1[0], b1[0]);
     mma(a1[1], b1[1]);
     order();
@@ -471,11 +477,12 @@ __global__ __launch_bounds__(THREADS) void gemm_nt_dma_kernel(GemmArgs g, int ti
 
 template <int EPI>
 hipError_t launch_dma(const GemmArgs& g, hipStream_t stream) {
-  constexpr int BT = 256, LDS = 4 * 2 * BT * 64;
+  constexpr int NST = COVSPEC_DMA_STAGES;
+  constexpr int BT = 256, LDS = NST * 2 * BT * 64;
   const int tiles_m = (g.M + BT - 1) / BT, tiles_n = (g.N + BT - 1) / BT;
   const long nblocks = (long)tiles_m * tiles_n * g.batch;
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
-  auto kern = gemm_nt_dma_kernel<EPI>;
+  auto kern = gemm_nt_dma_kernel<EPI, NST>;
   static PerDeviceInt raised;   // per instantiation
   const hipError_t attr = ensure_dynamic_lds(raised, (const void*)kern, LDS);
   if (attr != hipSuccess) return attr;
