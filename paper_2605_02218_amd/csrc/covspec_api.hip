@@ -376,12 +376,12 @@ int run_select(const Plan& q, const void* X, const float* s_fused, int32_t* idx_
                                    at<double>(ws, q.lam), ok, &Ut, img_status, marks.ev ? marks.ev[COVSPEC_PROBE_BEGIN] : nullptr,
                                    marks.ev ? marks.ev[COVSPEC_PROBE_END] : nullptr, st));
       probed = true;
-      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, img_status, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, nullptr, img_status, st));
       marks.mark(COVSPEC_STAGE_KEEP);
       HIPCHK(launch_subspace_energy(Ut, q.B, q.P, q.M, q.nP, (long)q.P * q.nP, q.r, at<double>(ws, q.lam), c, ok, 1, st));
       HIPCHK(launch_subspace_energy(A, q.B, q.M, q.M, q.nP, (long)q.nP * q.nP, q.r, at<double>(ws, q.lam), c, ok, 0, st));
     } else {
-      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, img_status, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, q.M, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, nullptr, img_status, st));
       marks.mark(COVSPEC_STAGE_KEEP);
       HIPCHK(launch_subspace_energy(A, q.B, q.M, q.M, q.nP, (long)q.nP * q.nP, q.r, at<double>(ws, q.lam), c, nullptr, 0, st));
     }
@@ -849,11 +849,11 @@ int covspec_stream_step(const covspec_stream_params* p, int32_t n_keep, int32_t 
       const double* Ut = nullptr;
       HIPCHK(launch_subspace_eigen(A, q.B, nC, q.nP, q.r, P, kSubspaceIters, kSubspaceMoreIters, at<void>(ws, q.sub), at<void>(ws, q.ctl),
                                    at<double>(ws, q.lam), ok, &Ut, nullptr, nullptr, nullptr, st));
-      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, nullptr, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), ok, nullptr, nullptr, st));
       HIPCHK(launch_subspace_energy(Ut, q.B, P, nC, q.nP, (long)P * q.nP, q.r, at<double>(ws, q.lam), c, ok, 1, st));
       HIPCHK(launch_subspace_energy(A, q.B, nC, nC, q.nP, gstride, q.r, at<double>(ws, q.lam), c, ok, 0, st));
     } else {
-      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, nullptr, st));
+      HIPCHK(launch_jacobi_eigen(A, q.B, nC, q.nP, q.r, at<void>(ws, q.ctl), at<double>(ws, q.lam), nullptr, nullptr, nullptr, st));
       HIPCHK(launch_subspace_energy(A, q.B, nC, nC, q.nP, gstride, q.r, at<double>(ws, q.lam), c, nullptr, 0, st));
     }
     int32_t* selw = at<int32_t>(ws, q.sel);

@@ -57,6 +57,7 @@ struct JacobiCtl {
 // measures it also reduces it, so 3e-7 leaves the energies converged to well below their last bit.
 constexpr double kRotEps = 1e-15;   // rotations below this relative size are skipped
 constexpr double kConvTol = 3e-7;
+constexpr double kBandSwitch = 1e-2;   // banded sweeps while the previous sweep's largest weight is above this
 
 __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restrict__ A, int n, int nP, JacobiCtl* ctl,
                                                              const int* __restrict__ preset_done) {
@@ -86,6 +87,27 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restri
 __device__ __forceinline__ void tournament_pair(int np, int rd, int m, int& p, int& q) {
   if (m == 0) { p = np - 1; q = rd; }
   else { p = (rd + m) % (np - 1); q = (rd - m + (np - 1)) % (np - 1); }
+}
+
+// Banded schedule.  When the matrix is the Rayleigh-Ritz projection of a block iteration, its rows are ordered
+// like the eigenvalues and row p only couples to rows whose eigenvalues are near its own: super-blocks more than
+// a few apart are orthogonal from the start and stay so (a rotation mixes two rows, so what it feeds into a far
+// pair is the product of two small couplings).  A sweep then only visits the pairs (I, I + d), d = 1..dmax, as
+// rounds (d, parity): the pairs with (I / d) even, then those with (I / d) odd, each a set of disjoint pairs.
+// That is 2 dmax rounds instead of nsb - 1, nearest first, and the sweeps converge at the tournament's rate (CPU
+// model on the workloads' matrices).  What the band leaves out is small but not nothing: a short row of the wanted
+// set that keeps an admixture delta of a long, far row shows a residual of delta * (long / short), so the banded
+// sweeps only do the bulk of the work (while the largest weight seen stays above kBandSwitch) and the solve ends
+// with tournament sweeps over all pairs, which also are the ones that decide convergence.
+// Pair `m` of round (d, parity); false if there is none.
+__device__ __forceinline__ bool band_pair(int nsb, int dist, int parity, int m, int& p, int& q) {
+  int seen = 0;
+  for (int i = 0; i + dist < nsb; ++i) {
+    if (((i / dist) & 1) != parity) continue;
+    if (seen == m) { p = i; q = i + dist; return true; }
+    ++seen;
+  }
+  return false;
 }
 
 constexpr int SB = 32;        // rows per super-block
@@ -323,7 +345,7 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
 // of every sweep; after a sweep, slot 0 decides convergence and re-measures which rows are the r longest.
 // A and len2 are written and re-read by different workgroups between barriers, hence no __restrict__.
 __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, int nP, int nsb, int r, JacobiCtl* ctl, double* len2,
-                                                              int* img_status, long long limit_ticks) {
+                                                              const int* __restrict__ band, int* img_status, long long limit_ticks) {
   const int npairs = nsb >> 1;
   const int tid = threadIdx.x;
   if (tid == 0) s_flag = (int)atomicAdd(&ctl[0].ticket, 1u);
@@ -338,16 +360,35 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
   const double floor2 = cb->floor2;   // written by the init kernel
   unsigned int target = 0;
   bool alive = true;
+  // largest super-block distance that is visited (written before the launch); the banded schedule is taken when it
+  // has fewer rounds than the tournament
+  const int dmax = band ? band[b] : 0;
+  const bool may_band = dmax >= 1 && 2 * dmax < nsb - 1;
 
 #pragma unroll 1
   for (int sweep = 0; sweep < kMaxSweeps && alive; ++sweep) {
     const double long2 = __hip_atomic_load(&cb->long2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the previous sweep's largest weight: complete behind the barrier that closed that sweep, the same in every workgroup
+    const double prev = sweep == 0 ? 1.0
+                                   : __longlong_as_double((long long)__hip_atomic_load(&cb->maxoff[sweep - 1], __ATOMIC_RELAXED,
+                                                                                        __HIP_MEMORY_SCOPE_AGENT));
+    const bool banded = may_band && prev > kBandSwitch;
+    const int nrounds = banded ? 2 * dmax : nsb - 1;
 #pragma unroll 1
-    for (int round = 0; round < nsb - 1 && alive; ++round) {
-      int I, J;
-      tournament_pair(nsb, round, pr, I, J);
-      const double meas = jacobi_visit(Ab, len2b, nP, I, J, round == 0, floor2, long2);
-      if (tid == 0 && meas > 0.0) atomicMax(&cb->maxoff[sweep], (unsigned long long)__double_as_longlong(sqrt(meas)));
+    for (int round = 0; round < nrounds && alive; ++round) {
+      int I = 0, J = 0;
+      bool have = true;
+      if (banded) {
+        if (!band_pair(nsb, (round >> 1) + 1, round & 1, 0, I, J)) continue;   // a round without pairs (the same for every workgroup)
+        have = band_pair(nsb, (round >> 1) + 1, round & 1, pr, I, J);
+      } else {
+        tournament_pair(nsb, round, pr, I, J);
+      }
+      if (have) {
+        // the rows inside a super-block are paired in the first round of a sweep, in which every super-block takes part
+        const double meas = jacobi_visit(Ab, len2b, nP, I, J, round == 0, floor2, long2);
+        if (tid == 0 && meas > 0.0) atomicMax(&cb->maxoff[sweep], (unsigned long long)__double_as_longlong(sqrt(meas)));
+      }
       target += npairs;
       alive = image_barrier_wait(&cb->bar, target, &s_flag, limit_ticks);
     }
@@ -382,6 +423,33 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
     for (long e = tid; e < (long)PR * nP; e += 256) Ab[(long)pr * PR * nP + e] = qnan;
     if (img_status && tid == 0) img_status[b] = 1;
   }
+}
+
+// dmax[b] = the largest super-block distance d at which two rows of the symmetric matrix H[b] still couple: S[b] = H[b]^2
+// is the Gram matrix of the rows of H[b] (the rows the solve rotates), and a pair (p, q) couples with the weight the
+// solve measures, |S_pq| sqrt(min(S_pp, S_qq)) / max(S_pp, S_qq)^1.5.  Distances whose largest weight is below `tol`
+// are left out (at least 1 is returned).  One workgroup per image; n x n, pitch n, only the lower triangle of S is read.
+__global__ __launch_bounds__(1024) void band_limit_kernel(const double* __restrict__ S, int n, double tol, int* __restrict__ dmax) {
+  __shared__ double diag[4096];
+  __shared__ int far;
+  const int b = blockIdx.x;
+  const double* Sb = S + (long)b * n * n;
+  for (int k = threadIdx.x; k < n; k += 1024) diag[k] = Sb[(long)k * n + k];
+  if (threadIdx.x == 0) far = 1;
+  __syncthreads();
+  int mine = 1;
+  for (long e = threadIdx.x; e < (long)n * n; e += 1024) {
+    const int p = (int)(e / n), q = (int)(e - (long)p * n);
+    const int dist = p / SB - q / SB;
+    if (dist <= mine) continue;          // also skips the upper triangle and what is already known to couple
+    const double a = diag[p], c = diag[q], hi = fmax(a, c), lo = fmin(a, c);
+    if (!(lo > 0.0)) continue;
+    const double w = fabs(Sb[e]) * sqrt(lo) / (hi * sqrt(hi));
+    if (!(w < tol)) mine = dist;         // NaN counts as coupled
+  }
+  if (mine > 1) atomicMax(&far, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) dmax[b] = far;
 }
 
 // lam[b*rows + k] = |row k of A[b]| (A[b] starts at b*img_stride and has `rows` rows of `pitch`), one wave per row
@@ -445,7 +513,7 @@ void set_barrier_limit_ticks(long long ticks) { g_barrier_limit.store(ticks > 0 
 long long barrier_limit_ticks() { return g_barrier_limit.load(); }
 
 hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl_, double* len2, const int* preset_done,
-                               int* img_status, hipStream_t st) {
+                               const int* band, int* img_status, hipStream_t st) {
   if (nP % 64 != 0 || n > nP || n > 4096 || r < 1 || r > n) return hipErrorInvalidValue;
   JacobiCtl* ctl = (JacobiCtl*)ctl_;
   const int nsb = nP / SB;  // even, since nP % 64 == 0
@@ -458,7 +526,13 @@ hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl
   if (npairs > capacity) return hipErrorInvalidValue;
   hipLaunchKernelGGL(jacobi_init_kernel, dim3(B), dim3(256), 0, st, A, n, nP, ctl, preset_done);
   hipLaunchKernelGGL(jacobi_solve_kernel, dim3((unsigned)(B * npairs)), dim3(256), 0, st, A, n, nP, nsb, r, ctl, len2,
-                     img_status, barrier_limit_ticks());
+                     band, img_status, barrier_limit_ticks());
+  return hipGetLastError();
+}
+
+hipError_t launch_band_limit(const double* S, int B, int n, double tol, int* dmax, hipStream_t st) {
+  if (n > 4096 || n % SB != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(band_limit_kernel, dim3(B), dim3(1024), 0, st, S, n, tol, dmax);
   return hipGetLastError();
 }
 

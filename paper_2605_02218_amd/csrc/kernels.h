@@ -126,8 +126,13 @@ int jacobi_pitch(int n);      // row pitch (and padded order) the solver needs: 
 // preset_done (optional, [B]): images whose entry is non-zero are left untouched.
 // img_status (optional, [B]): set to 1 for an image whose workgroups gave up waiting for one another (its rows
 // are then NaN); never cleared here.
+// band (optional, [B]): largest super-block distance (32 rows each) whose pairs are visited, for matrices whose rows
+// only couple to near neighbours (see launch_band_limit); nullptr or an entry that saves no rounds: every pair.
 hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl, double* len2, const int* preset_done,
-                               int* img_status, hipStream_t stream);
+                               const int* band, int* img_status, hipStream_t stream);
+// dmax[b] = largest distance between 32-row super-blocks at which rows of the symmetric n x n matrix H[b] couple with a
+// weight of at least tol, given S[b] = H[b]^2 (pitch n, lower triangle read); n % 32 == 0.
+hipError_t launch_band_limit(const double* S, int B, int n, double tol, int* dmax, hipStream_t stream);
 hipError_t launch_row_lengths(const double* A, int B, int rows, int pitch, long img_stride, double* lam, hipStream_t stream);
 // Subspace energy (paper energy equation) from rows of the form lambda_k v_k^T: c[b,i] = sum over the r
 // longest of the `rows` rows of A[b] of A[k][i]^2 / |row k|, i < n.  A[b] starts at b*img_stride, rows have

@@ -35,6 +35,9 @@ constexpr double kPivotNear = 0.25;   // smallest scaled pivot above this: rows 
 constexpr double kPivotFar = 1e-3;    // above this: blocks of two steps
 constexpr double kGradeDigits = 14.0; // decimal digits a block's grading (lambda_1 / lambda_P)^steps may use up
 constexpr int kMaxBlockSteps = 3;
+// Couplings between rows of the projected matrix below this weight are left out of the first, banded sweeps of the
+// Ritz solve (its last sweeps visit every pair).
+constexpr double kBandTol = 1e-9;
 constexpr double kPivotOnePass = 0.01; // final step: above this one Cholesky-QR pass leaves the rows orthonormal to ~1e-14
 constexpr size_t kCholLdsFixed = (size_t)(2 * NB * NBP) * sizeof(double);   // plus P doubles: the diagonal of S
 
@@ -87,7 +90,7 @@ __device__ __noinline__ void potrf_wave(const double* a, double* fac, double flo
 // produce NaNs (the residual check afterwards decides whether the result is usable).
 // Dynamic LDS: 2 * 64 * 65 doubles.
 __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, int* skip_until, int* last_orth, int step,
-                                                   int last_free_step, int max_block) {
+                                                   int last_free_step, int next_weight) {
   extern __shared__ double lds[];
   double* a = lds;                  // [64][65] diagonal block, later the inverse of its factor
   double* fac = lds + NB * NBP;     // [64][65] the factor (lower triangle) and scratch (upper triangle)
@@ -257,8 +260,10 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
       const double digits_per_step = log10(fmax(dmax / dmin, 10.0)) / (double)(closed < 1 ? 1 : closed);
       const int by_grade = (int)(kGradeDigits / digits_per_step);
       const int by_pivot = pmin > kPivotNear ? kMaxBlockSteps : (pmin > kPivotFar ? 2 : 1);
-      m = by_pivot < by_grade ? by_pivot : by_grade;
-      if (m > max_block) m = max_block;     // a step with the squared matrix is two steps of this count already
+      // by_pivot counts products with G; the products that follow multiply by G^next_weight.  by_grade is in
+      // products of the block just closed, whose weight is never below that of the next ones.
+      const int by_pivot_products = by_pivot / next_weight;
+      m = by_pivot_products < by_grade ? by_pivot_products : by_grade;
       if (m < 1) m = 1;
     }
     int next = step + m;                      // the next step that orthonormalises
@@ -405,21 +410,23 @@ size_t subspace_workspace_bytes(int B, int n, int nP, int P) {
   if (P <= 0) return 0;
   const size_t blk = (size_t)B * P * nP * 8;
   return 2 * blk + (size_t)P * nP * 8 + 2 * (size_t)B * P * P * 8 + (size_t)B * P * NB * 8 + (size_t)B * P * 8 + 1024 + (size_t)B * 4 +
-         (size_t)B * 4 + 256 + (size_t)B * nP * nP * 8 /* G^2 */ + 256;
+         (size_t)B * 4 + (size_t)B * 4 /* band limits */ + 256 + (size_t)B * nP * nP * 8 /* G^2 */ + 256;
 }
 
 // Runs the iteration on G[b] (n x n, pitch nP, untouched).  On return, for images with ok[b] = 1, rows
 // k of (*ut)[b] (P rows, pitch nP, inside ws) are theta_k u_k^T with the r longest rows converged.
-// start block, one per product of the first pass (iters / 2: all but the last multiply by G^2), residuals
-int subspace_product_launches(int iters) { return iters / 2 + 2; }
+// The first pass makes iters steps of the iteration as iters / 3 products with G^2 followed by iters / 3 with G.
+// Launches of the probed shape: start block, the products of the first pass, residuals.
+int subspace_product_launches(int iters) { return 2 * (iters / 3) + 2; }
 
 hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, int P, int iters, int more_iters, void* ws_, void* jacobi_ctl,
                                  double* jacobi_len2, int* ok, const double** ut, int* img_status, hipEvent_t probe_begin,
                                  hipEvent_t probe_end, hipStream_t st) {
   hipError_t e0;
   if (P <= 0 || P % NB != 0 || P > n || P > 4096 || nP % NB != 0) return hipErrorInvalidValue;
-  // the two blocks swap roles per product: an even number of products per pass (the first pass makes iters / 2)
-  if (iters < 4 || more_iters < 2 || (iters & 3) || (more_iters & 1)) return hipErrorInvalidValue;
+  // every pass makes an even number of products, so that the rows of the images that passed the first check are
+  // in the block that is returned (the two blocks swap roles per product)
+  if (iters < 3 || iters % 3 != 0 || more_iters < 2 || (more_iters & 1)) return hipErrorInvalidValue;
   {
     static PerDeviceInt raised;
     if ((e0 = ensure_dynamic_lds(raised, (const void*)chol_kernel, kCholLdsFixed + 4096 * sizeof(double))) != hipSuccess) return e0;
@@ -435,7 +442,8 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   double* lam = D + (size_t)B * P * NB;
   int* skip_until = (int*)(((uintptr_t)(lam + (size_t)B * P) + 255) & ~(uintptr_t)255);   // [B] next step that orthonormalises
   int* last_orth = skip_until + B;                                                          // [B] step of the last one
-  double* G2 = (double*)(((uintptr_t)(last_orth + B) + 255) & ~(uintptr_t)255);             // [B][nP][nP] G squared
+  int* band = last_orth + B;                                                                // [B] see launch_band_limit
+  double* G2 = (double*)(((uintptr_t)(band + B) + 255) & ~(uintptr_t)255);                  // [B][nP][nP] G squared
   const int nblk = P / NB;
   hipError_t e;
 
@@ -456,7 +464,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   // X <- L^-1 X with X X^T = L L^T.  Images with skip_until[b] > step leave X alone, and the factorisation decides
   // how many steps the image takes before the next one (never beyond last_free_step).
   const size_t chol_lds = kCholLdsFixed + (size_t)P * sizeof(double);
-  auto cholqr = [&](double* X, int step, int last_free_step, int max_block) -> hipError_t {
+  auto cholqr = [&](double* X, int step, int last_free_step, int next_weight) -> hipError_t {
     GemmArgs g;
     g.A = X; g.B = X; g.C = S; g.M = P; g.N = P; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = P;
     g.batch = B; g.strideA = (long)P * nP; g.strideB = (long)P * nP; g.strideC = (long)P * P;
@@ -466,7 +474,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     g.skip_if = step;
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
     hipLaunchKernelGGL(chol_kernel, dim3((unsigned)B), dim3(512), chol_lds, st, S, D, P, skip_until, last_orth, step, last_free_step,
-                       max_block);
+                       next_weight);
     hipLaunchKernelGGL(trsm_kernel, dim3((unsigned)(B * (nP / NB))), dim3(256), 0, st, X, (const double*)S, (const double*)D, P, nP,
                        nP / NB, (const int*)last_orth, step);
     return hipGetLastError();
@@ -475,16 +483,21 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
   double* oth = Zt;
   // `steps` products from the block in `cur` (each preceded by an orthonormalisation where the image's schedule
   // asks for one), then Rayleigh-Ritz and the residual check.  steps is even, so `cur` is the same buffer after it.
-  // `squared`: every product but the last multiplies by G^2, i.e. takes two steps of the iteration at the cost of
-  // one (the same subspace as two products with G and an orthonormalisation between them); such a product is
-  // always followed by an orthonormalisation.  The last product is with G itself: it feeds the Rayleigh-Ritz step.
-  auto pass = [&](int steps, bool squared) -> hipError_t {
+  // The first n_sq products multiply by G^2: two steps of the iteration at the cost of one (the same subspace as
+  // two products with G and an orthonormalisation between them).  G^2 as formed is off by about 1e-16 |G|^2, which
+  // is a fixed perturbation of the operator of relative size 1e-16 (lambda_1 / lambda_r)^2 at the r-th eigenvalue
+  // (1e-8 for a spectrum that falls by 1e4 down to r); the products with G itself that follow contract that error
+  // like any other, and a CPU model of the workloads' matrices needs three to four of them.  The last product
+  // feeds the Rayleigh-Ritz step and is with G in any case.
+  auto pass = [&](int n_sq, int n_plain) -> hipError_t {
+    const int steps = n_sq + n_plain;
     for (int it = 0; it < steps; ++it) {
       // the block of step 0 is not (orthonormal) x G, so its factor says nothing about the next step (the kernel
       // takes one step after it); the last step always orthonormalises, twice where its pivots ask for it
-      if ((e = cholqr(cur, it, steps - 1, squared ? 1 : kMaxBlockSteps)) != hipSuccess) return e;
+      const int w = it < n_sq ? 2 : 1;
+      if ((e = cholqr(cur, it, steps - 1, w)) != hipSuccess) return e;
       if (it + 1 == steps && (e = cholqr(cur, it + 1, steps - 1, 1)) != hipSuccess) return e;
-      if ((e = gemm_yt_g(cur, oth, (squared && it + 1 < steps) ? G2 : G)) != hipSuccess) return e;   // last: oth = Q^T G
+      if ((e = gemm_yt_g(cur, oth, w == 2 ? G2 : G)) != hipSuccess) return e;   // last: oth = Q^T G
       double* t = cur; cur = oth; oth = t;
     }
     // now oth = Q^T (orthonormal rows), cur = Q^T G.  Rayleigh-Ritz: H = (Q^T G) Q
@@ -498,7 +511,19 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
       mask(g);
       if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
     }
-    if ((e = launch_jacobi_eigen(H, B, P, P, r, jacobi_ctl, jacobi_len2, masked ? (const int*)ok : nullptr, img_status, st)) != hipSuccess) return e;
+    // The rows of the block are ordered like the eigenvalues, so H only couples neighbouring rows: measure how far
+    // (on H^2, the Gram matrix of the rows the solve rotates; S is free by now) and let the solve leave the rest out
+    {
+      GemmArgs g;
+      g.A = H; g.B = H; g.C = S; g.M = P; g.N = P; g.K = P; g.lda = P; g.ldb = P; g.ldc = P;
+      g.batch = B; g.strideA = (long)P * P; g.strideB = (long)P * P; g.strideC = (long)P * P;
+      g.epilogue = EPI_STORE_F64;
+      g.lower_only = true;
+      mask(g);
+      if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
+      if ((e = launch_band_limit(S, B, P, kBandTol, band, st)) != hipSuccess) return e;
+    }
+    if ((e = launch_jacobi_eigen(H, B, P, P, r, jacobi_ctl, jacobi_len2, masked ? (const int*)ok : nullptr, band, img_status, st)) != hipSuccess) return e;
     // rows of H are now theta_k w_k^T; Ut = H Q^T has rows theta_k u_k^T
     {
       GemmArgs g;
@@ -525,24 +550,24 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
     g.mirror = true;
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
   }
-  // start block: Omega G^2
+  // start block: Omega G
   hipLaunchKernelGGL(omega_kernel, dim3((unsigned)(((long)P * nP + 255) / 256)), dim3(256), 0, st, Om, P, n, nP);
   if (probe_begin && (e = hipEventRecord(probe_begin, st)) != hipSuccess) return e;
   {
     GemmArgs g;
-    g.A = Om; g.B = G2; g.C = Yt; g.M = P; g.N = nP; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = nP;
+    g.A = Om; g.B = G; g.C = Yt; g.M = P; g.N = nP; g.K = nP; g.lda = nP; g.ldb = nP; g.ldc = nP;
     g.batch = B; g.strideA = 0; g.strideB = (long)nP * nP; g.strideC = (long)P * nP;
     g.epilogue = EPI_STORE_F64;
     if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
   }
   if (probe_end && (e = hipEventRecord(probe_end, st)) != hipSuccess) return e;
   if ((e = launch_fill_int(skip_until, 2 * B, -1, st)) != hipSuccess) return e;
-  if ((e = pass(iters / 2, true)) != hipSuccess) return e;
+  if ((e = pass(iters / 3, iters / 3)) != hipSuccess) return e;
   // images whose Ritz pairs are not there yet (slower spectral decay than the first pass allows for) go on from
   // their Ritz vectors for a few more steps; for the others every kernel of this pass returns at once
   masked = true;
   hipLaunchKernelGGL(mask_passed_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, (const int*)ok, skip_until, last_orth, B);
-  if ((e = pass(more_iters, false)) != hipSuccess) return e;
+  if ((e = pass(0, more_iters)) != hipSuccess) return e;
   *ut = cur;
   return hipGetLastError();
 }
