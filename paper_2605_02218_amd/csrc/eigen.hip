@@ -429,10 +429,12 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
 // is the Gram matrix of the rows of H[b] (the rows the solve rotates), and a pair (p, q) couples with the weight the
 // solve measures, |S_pq| sqrt(min(S_pp, S_qq)) / max(S_pp, S_qq)^1.5.  Distances whose largest weight is below `tol`
 // are left out (at least 1 is returned).  One workgroup per image; n x n, pitch n, only the lower triangle of S is read.
-__global__ __launch_bounds__(1024) void band_limit_kernel(const double* __restrict__ S, int n, double tol, int* __restrict__ dmax) {
+__global__ __launch_bounds__(1024) void band_limit_kernel(const double* __restrict__ S, int n, double tol, int* __restrict__ dmax,
+                                                          const int* __restrict__ skip) {
   __shared__ double diag[4096];
   __shared__ int far;
   const int b = blockIdx.x;
+  if (skip && skip[b]) return;     // the solve leaves this image alone
   const double* Sb = S + (long)b * n * n;
   for (int k = threadIdx.x; k < n; k += 1024) diag[k] = Sb[(long)k * n + k];
   if (threadIdx.x == 0) far = 1;
@@ -530,9 +532,9 @@ hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl
   return hipGetLastError();
 }
 
-hipError_t launch_band_limit(const double* S, int B, int n, double tol, int* dmax, hipStream_t st) {
+hipError_t launch_band_limit(const double* S, int B, int n, double tol, int* dmax, const int* skip, hipStream_t st) {
   if (n > 4096 || n % SB != 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(band_limit_kernel, dim3(B), dim3(1024), 0, st, S, n, tol, dmax);
+  hipLaunchKernelGGL(band_limit_kernel, dim3(B), dim3(1024), 0, st, S, n, tol, dmax, skip);
   return hipGetLastError();
 }
 

@@ -132,7 +132,8 @@ hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl
                                const int* band, int* img_status, hipStream_t stream);
 // dmax[b] = largest distance between 32-row super-blocks at which rows of the symmetric n x n matrix H[b] couple with a
 // weight of at least tol, given S[b] = H[b]^2 (pitch n, lower triangle read); n % 32 == 0.
-hipError_t launch_band_limit(const double* S, int B, int n, double tol, int* dmax, hipStream_t stream);
+// skip (optional, [B]): images with a non-zero entry are left out.
+hipError_t launch_band_limit(const double* S, int B, int n, double tol, int* dmax, const int* skip, hipStream_t stream);
 hipError_t launch_row_lengths(const double* A, int B, int rows, int pitch, long img_stride, double* lam, hipStream_t stream);
 // Subspace energy (paper energy equation) from rows of the form lambda_k v_k^T: c[b,i] = sum over the r
 // longest of the `rows` rows of A[b] of A[k][i]^2 / |row k|, i < n.  A[b] starts at b*img_stride, rows have

@@ -104,25 +104,27 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
   double floor_ = 0.0;
   for (int k = tid; k < P; k += 512) diag0[k] = Sb[(long)k * P + k];
 
+  // The diagonal block of the first panel: factored by ONE wave, row i of the block in the registers of lane i (no
+  // barrier and no LDS traffic per column; with the whole workgroup a column cost a barrier and a round trip through
+  // LDS, and the factorisation is a chain of 64 dependent columns).  Column k: pivot from lane k, scaled column
+  // l_ik = a_ik / sqrt(a_kk), then a_ij -= l_ik l_jk with l_jk read from lane j.  Lanes also carry the (unused)
+  // entries above the diagonal; they stay finite and never feed an entry below it.
+  for (int e = tid; e < NB * NB; e += 512) {
+    const int i = e >> 6, j = e & 63;
+    a[i * NBP + j] = (j <= i) ? Sb[(long)i * P + j] : 0.0;
+  }
+  __syncthreads();
+  {
+    double tr = 0.0;
+    for (int i = 0; i < NB; ++i) tr += a[i * NBP + i];   // same value in every thread
+    floor_ = 1e-300 + 1e-28 * tr;
+  }
+  if (w == 0) potrf_wave(a, fac, floor_);
+  __syncthreads();
+
   for (int J = 0; J < nblk; ++J) {
     const int j0 = J * NB;
-    for (int e = tid; e < NB * NB; e += 512) {
-      const int i = e >> 6, j = e & 63;
-      a[i * NBP + j] = (j <= i) ? Sb[(long)(j0 + i) * P + j0 + j] : 0.0;
-    }
-    __syncthreads();
-    if (J == 0) {
-      double tr = 0.0;
-      for (int i = 0; i < NB; ++i) tr += a[i * NBP + i];   // same value in every thread
-      floor_ = 1e-300 + 1e-28 * tr;
-    }
-    // ---- factor the diagonal block in ONE wave, row i of the block in the registers of lane i: no barrier and
-    //      no LDS traffic per column (with the whole workgroup a column cost a barrier and a round trip through
-    //      LDS, and the factorisation is a chain of 64 dependent columns).  Column k: pivot from lane k, scaled
-    //      column l_ik = a_ik / sqrt(a_kk), then a_ij -= l_ik l_jk with l_jk read from lane j.  Lanes also carry
-    //      the (unused) entries above the diagonal; they stay finite and never feed an entry below it.
-    if (w == 0) potrf_wave(a, fac, floor_);
-    __syncthreads();
+    // here `fac` holds the factor of diagonal block J (for J > 0 wave 0 formed it during the trailing update of panel J - 1)
     if (tid == 0)
       for (int k = 0; k < NB; ++k) {
         const double d = fac[k * NBP + k];
@@ -191,14 +193,19 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
 #pragma unroll
         for (int v = 0; v < 4; ++v) Sb[(rb + 4 * v + kq) * P + j0 + 16 * y + i16] = out[y][v];
     }
-    __syncthreads();
-    // ---- trailing update, unit = 16 rows of block I x the 64 columns of block I' <= I.  Every wave takes a
-    //      contiguous range of units, so consecutive units mostly share I' and its fragments stay in registers;
-    //      all loads of a unit are issued before its MFMAs.
+    __syncthreads();     // the panel is complete in global memory and `a`, `fac` are free
+    if (below == 0) break;
+    // ---- trailing update, unit = 16 rows of block I x the 64 columns of block I' <= I.  The four units of the
+    //      next diagonal block go to wave 0, which writes them to LDS instead of global memory and factors the
+    //      block at once (look-ahead: the chain of 64 dependent columns runs beside the rest of the update instead
+    //      of after it); the other waves share the remaining units in contiguous ranges, so that consecutive units
+    //      mostly share I' and its fragments stay in registers.  All loads of a unit are issued before its MFMAs.
     {
       const int nb = below / NB;
-      const int units = 2 * nb * (nb + 1);            // 4 * nb (nb + 1) / 2
-      const int u0 = (int)((long)units * w / 8), u1 = (int)((long)units * (w + 1) / 8);
+      const int units = 2 * nb * (nb + 1);            // 4 * nb (nb + 1) / 2; units 0..3 are the next diagonal block
+      int u0, u1;
+      if (w == 0) { u0 = 0; u1 = 4; }
+      else { u0 = 4 + (int)((long)(units - 4) * (w - 1) / 7); u1 = 4 + (int)((long)(units - 4) * w / 7); }
       // unit u -> pair index u / 4 -> (I, I2) with I (I + 1) / 2 + I2 = pair index
       int I = 0, I2 = 0;
       {
@@ -235,13 +242,27 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
         for (int y = 0; y < 4; ++y)
 #pragma unroll
           for (int v = 0; v < 4; ++v) cc[y][v] = Sb[(ra + 4 * v + kq) * P + rc + 16 * y + i16];
+        if (w == 0) {
+          // the next diagonal block (every entry of it is kept up to date, above the diagonal too): into LDS
 #pragma unroll
-        for (int y = 0; y < 4; ++y)
+          for (int y = 0; y < 4; ++y)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) Sb[(ra + 4 * v + kq) * P + rc + 16 * y + i16] = cc[y][v] - acc[y][v];
+            for (int v = 0; v < 4; ++v) a[(16 * q + 4 * v + kq) * NBP + 16 * y + i16] = cc[y][v] - acc[y][v];
+        } else {
+#pragma unroll
+          for (int y = 0; y < 4; ++y)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Sb[(ra + 4 * v + kq) * P + rc + 16 * y + i16] = cc[y][v] - acc[y][v];
+        }
         if (q == 3) {   // next pair
           if (I2 == I) { ++I; I2 = 0; } else ++I2;
         }
+      }
+      if (w == 0) {
+        // one wave wrote the block and one wave reads it: its LDS writes are complete once the counter says so
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+        __builtin_amdgcn_wave_barrier();
+        potrf_wave(a, fac, floor_);
       }
     }
     __syncthreads();
@@ -521,7 +542,7 @@ hipError_t launch_subspace_eigen(const double* G, int B, int n, int nP, int r, i
       g.lower_only = true;
       mask(g);
       if ((e = launch_gemm64_nt(g, true, true, st)) != hipSuccess) return e;
-      if ((e = launch_band_limit(S, B, P, kBandTol, band, st)) != hipSuccess) return e;
+      if ((e = launch_band_limit(S, B, P, kBandTol, band, masked ? (const int*)ok : nullptr, st)) != hipSuccess) return e;
     }
     if ((e = launch_jacobi_eigen(H, B, P, P, r, jacobi_ctl, jacobi_len2, masked ? (const int*)ok : nullptr, band, img_status, st)) != hipSuccess) return e;
     // rows of H are now theta_k w_k^T; Ut = H Q^T has rows theta_k u_k^T
