@@ -490,6 +490,157 @@ hipError_t launch_dma(const GemmArgs& g, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// ---- bf16 products into fp64 with optional row gathers (the Gram matrix of the pre-selected tokens and the rows a
+// streaming step adds to it): 128x128 block tile, wave tile 64x64 (2x2 MFMA tiles), k-tile 32, four LDS stages of
+// 16 KB filled by direct global -> LDS loads whose lanes take their row from the gather list, fp32 partial sums
+// flushed into fp64 accumulators every 256 k, tiles above the diagonal skipped and mirrored on request.  Same
+// pipeline as gemm_nt_dma_kernel (one barrier per k-tile, fragments of the next k-tile read while the current one
+// is multiplied); two workgroups fit a compute unit, so one's waits are the other's MFMAs.  Rows beyond M / N are
+// clamped when loading and masked in the epilogue; requires K % 32 == 0.
+__global__ __launch_bounds__(THREADS, 2) void gemm_gram_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  constexpr int BT = 128, WT = 64, TW = 2, BK = 32, NST = 4;
+  constexpr int STAGE = 2 * BT * 64;  // bytes: A tile then B tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const TileMap tmap = map_block(blockIdx.x, gridDim.x, tiles_m, tiles_n);
+  if (g.lower_only && tmap.tn > tmap.tm) return;      // square tiles: entirely above the diagonal (uniform)
+  const int row0 = tmap.tm * BT, col0 = tmap.tn * BT;
+  const int bo = tmap.b / g.batch_inner, bi = tmap.b - bo * g.batch_inner;
+  const bf16_t* __restrict__ A = (const bf16_t*)g.A + (long)bo * g.strideA + (long)bi * g.strideA2;
+  const bf16_t* __restrict__ B = (const bf16_t*)g.B + (long)bo * g.strideB + (long)bi * g.strideB2;
+  const long coff = (long)bo * g.strideC + (long)bi * g.strideC2;
+
+  // wave w issues loads j = 0, 1 per operand and stage; load j fills tile rows 16*(2w+j) .. +15:
+  // lane l -> row 16*(2w+j) + l/4, physical chunk l%4
+  const bf16_t* ga[2];
+  const bf16_t* gb[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int r = 16 * (2 * wave + j) + (lane >> 2);
+    const int f = ((r >> 2) & 1) | ((((r >> 1) ^ (r >> 3)) & 1) << 1);
+    const int c = (lane & 3) ^ f;  // logical chunk that belongs at this physical slot
+    long ra = min(row0 + r, g.M - 1), rb = min(col0 + r, g.N - 1);
+    if (g.gatherA) ra = g.gatherA[(long)bo * g.gstrideA + ra];
+    if (g.gatherB) rb = g.gatherB[(long)bo * g.gstrideB + rb];
+    ga[j] = A + ra * g.lda + c * 8;
+    gb[j] = B + rb * g.ldb + c * 8;
+  }
+  auto issue = [&](int kt) {
+    unsigned char* sa = smem + (kt & (NST - 1)) * STAGE + wave * 2048;
+    unsigned char* sb = sa + BT * 64;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ga[j] + kt * BK),
+                                       (__attribute__((address_space(3))) void*)(sa + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gb[j] + kt * BK),
+                                       (__attribute__((address_space(3))) void*)(sb + j * 1024), 16, 0, 0);
+    }
+  };
+
+  f32x16_t acc[TW][TW];
+  double acc64[TW * TW * 16];
+#pragma unroll
+  for (int i = 0; i < TW; ++i)
+#pragma unroll
+    for (int j = 0; j < TW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { acc[i][j][v] = 0.f; acc64[(i * TW + j) * 16 + v] = 0.0; }
+
+  const int nk = g.K / BK;
+  const int li = lane & 31, lh = lane >> 5;
+  int offA[2][TW], offB[2][TW];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+    for (int i = 0; i < TW; ++i) {
+      offA[ks][i] = swz64(wm * WT + i * 32 + li, 2 * ks + lh);
+      offB[ks][i] = BT * 64 + swz64(wn * WT + i * 32 + li, 2 * ks + lh);
+    }
+  auto frags = [&](const unsigned char* st, int ks, bf16x8_t (&af)[TW], bf16x8_t (&bfr)[TW]) {
+#pragma unroll
+    for (int i = 0; i < TW; ++i) {
+      af[i] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(st + offA[ks][i]));
+      bfr[i] = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(st + offB[ks][i]));
+    }
+  };
+  auto mma = [&](const bf16x8_t (&af)[TW], const bf16x8_t (&bfr)[TW]) {
+#pragma unroll
+    for (int i = 0; i < TW; ++i)
+#pragma unroll
+      for (int j = 0; j < TW; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+  };
+  auto flush = [&]() {
+#pragma unroll
+    for (int i = 0; i < TW; ++i)
+#pragma unroll
+      for (int j = 0; j < TW; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          acc64[(i * TW + j) * 16 + v] += (double)acc[i][j][v];
+          acc[i][j][v] = 0.f;
+        }
+  };
+  auto stage_ptr = [&](int kt) -> const unsigned char* { return smem + (kt & (NST - 1)) * STAGE; };
+
+  // Per k-tile kt: wait until tile kt+1 has landed (only the four loads of tile kt+2 may be outstanding), barrier,
+  // start the loads of tile kt+3 into the stage that held tile kt-1 (every wave has read it: its LDS reads are
+  // complete before it arrives at the barrier).  The fragments are prefetched one k-step ahead, in two register
+  // sets: the second k-step of tile kt is read while the first one feeds the MFMAs, the first k-step of tile
+  // kt+1 while the second one does.  Past the end, `issue` re-loads the last tile and `frags` reads a stage whose
+  // values are never used.
+  bf16x8_t a0[TW], b0[TW], a1[TW], b1[TW];
+  issue(0);
+  issue(min(1, nk - 1));
+  issue(min(2, nk - 1));
+  __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0): tile 0 has landed
+  __builtin_amdgcn_s_barrier();
+  frags(stage_ptr(0), 0, a0, b0);
+  for (int kt = 0; kt < nk; ++kt) {
+    __builtin_amdgcn_s_waitcnt(0x0074);   // vmcnt(4) lgkmcnt(0): all but the newest tile have landed
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    frags(stage_ptr(kt), 1, a1, b1);
+    issue(min(kt + 3, nk - 1));
+    mma(a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    frags(stage_ptr(kt + 1), 0, a0, b0);
+    mma(a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    // the fp32 partial sums go into fp64 every 256 contraction steps (8 k-tiles) and at the end
+    if ((kt & 7) == 7 || kt + 1 == nk) flush();
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);
+
+#pragma unroll
+  for (int i = 0; i < TW; ++i)
+#pragma unroll
+    for (int j = 0; j < TW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = row0 + wm * WT + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+        const int c = col0 + wn * WT + j * 32 + li;
+        if (r < g.M && c < g.N) {
+          const double x = acc64[(i * TW + j) * 16 + v];
+          ((double*)g.C)[coff + (long)r * g.ldc + c] = x;
+          // symmetric product: the tile below the diagonal is also stored transposed (v & 3 walks four
+          // consecutive rows r, so each thread writes 32 contiguous bytes of row c)
+          if (g.mirror && tmap.tn != tmap.tm) ((double*)g.C)[coff + (long)c * g.ldc + r] = x;
+        }
+      }
+}
+
+inline hipError_t launch_gram_dma(const GemmArgs& g, hipStream_t stream) {
+  constexpr int BT = 128, LDS = 4 * 2 * BT * 64;
+  const int tiles_m = (g.M + BT - 1) / BT, tiles_n = (g.N + BT - 1) / BT;
+  const long nblocks = (long)tiles_m * tiles_n * g.batch;
+  if (nblocks <= 0) return hipSuccess;
+  if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gemm_gram_dma_kernel, dim3((unsigned)nblocks), dim3(THREADS), LDS, stream, g, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
 template <typename In, int EPI, bool GATHER, int TW>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream) {
   constexpr int BT = 64 * TW;
@@ -515,6 +666,13 @@ inline bool use_big_tiles(const GemmArgs& g) {
 
 template <typename In, int EPI>
 hipError_t launch_t(const GemmArgs& g, hipStream_t stream) {
+  if constexpr (std::is_same<In, bf16_t>::value && EPI == EPI_STORE_F64) {
+    // fp64 results from bf16 rows (gathered or not): the direct-to-LDS kernel when the shape allows it
+    const bool aligned = g.lda % 8 == 0 && g.ldb % 8 == 0 && (((uintptr_t)g.A | (uintptr_t)g.B) & 15) == 0 && g.strideA % 8 == 0 &&
+                         g.strideB % 8 == 0 && g.strideA2 % 8 == 0 && g.strideB2 % 8 == 0;
+    if (aligned && g.K % 32 == 0 && g.K >= 32 && g.M >= 1 && g.N >= 1 && (long)g.M * g.N * g.batch >= 128L * 128 * 64)
+      return launch_gram_dma(g, stream);
+  }
   if (g.gatherA || g.gatherB) return launch_cfg<In, EPI, true, 2>(g, stream);
   if constexpr (std::is_same<In, bf16_t>::value && EPI != EPI_STORE_F64) {
     if (use_big_tiles(g)) {
