@@ -9,7 +9,7 @@
 // |row k| = lambda_k and c_i = sum over the r longest rows of A_ki^2 / |row k|.
 //
 // Parallel form: rows are grouped in super-blocks of 32; a round-robin tournament pairs the
-// super-blocks, one 256-thread workgroup per pair and image.  The whole solve is ONE launch: the
+// super-blocks, one 512-thread workgroup per pair and image.  The whole solve is ONE launch: the
 // workgroups of an image meet at a barrier in global memory after every tournament round.  A
 // workgroup takes its (image, slot) from a ticket counter when it starts, so the workgroups that are
 // resident always hold the lowest tickets, i.e. whole images plus at most one partial image whose
@@ -113,6 +113,12 @@ __device__ __forceinline__ bool band_pair(int nsb, int dist, int parity, int m, 
 constexpr int SB = 32;        // rows per super-block
 constexpr int PR = 2 * SB;    // rows per workgroup
 constexpr int HP = PR + 1;    // LDS pitch (doubles)
+#ifndef COVSPEC_JACOBI_THREADS
+#define COVSPEC_JACOBI_THREADS 512
+#endif
+constexpr int JT = COVSPEC_JACOBI_THREADS;   // threads per workgroup of the solve: 256 or 512
+constexpr int JW = JT / 64;                  // waves
+static_assert(JT == 256 || JT == 512, "the visit's index mappings are written for 4 or 8 waves");
 
 // LDS of the solve kernel (file scope: shared by the kernel and the visit function below).
 __shared__ double Hs[PR * HP];
@@ -130,8 +136,10 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
   const int nchunks = nP >> 4;
   auto grow = [&](int i) -> int { return (i < SB) ? I * SB + i : J * SB + (i - SB); };   // nP <= 4096: offsets fit an int
 
-  // ---- 1. H = P P^T : wave w takes column chunks w, w+4, ...; upper tiles only
-  for (int e = tid; e < PR * HP; e += 256) { Hs[e] = 0.0; Ws[e] = 0.0; }
+  // ---- 1. H = P P^T : wave w takes column chunks w, w + JW, ...; upper tiles only.  The waves' partial tiles are
+  //         added in a fixed order (the result must not depend on which wave comes first): the waves of the lower
+  //         half one after the other into Hs, those of the upper half likewise into Ws at the same time, then Hs += Ws.
+  for (int e = tid; e < PR * HP; e += JT) { Hs[e] = 0.0; Ws[e] = 0.0; }
   if (tid == 0) any_rot = 0;
   {
     f64x4_t acc[10];
@@ -151,10 +159,10 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
 #pragma unroll
     for (int x = 0; x < 4; ++x) f0[x] = f1[x] = f2[x] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
     fetch(f0, w);
-    fetch(f1, w + 4);
+    fetch(f1, w + JW);
 #pragma unroll 1
-    for (int c = w; c < nchunks; c += 4) {
-      fetch(f2, c + 8);
+    for (int c = w; c < nchunks; c += JW) {
+      fetch(f2, c + 2 * JW);
       int t = 0;
 #pragma unroll
       for (int x = 0; x < 4; ++x)
@@ -168,22 +176,28 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
       for (int x = 0; x < 4; ++x) { f0[x] = f1[x]; f1[x] = f2[x]; }
     }
     __syncthreads();  // zero fill visible
-    for (int ww = 0; ww < 4; ++ww) {
-      if (w == ww) {
+    double* part = (w < JW / 2) ? Hs : Ws;
+    for (int ww = 0; ww < JW / 2; ++ww) {
+      if ((w % (JW / 2)) == ww) {
         int t = 0;
 #pragma unroll
         for (int x = 0; x < 4; ++x)
 #pragma unroll
           for (int y = x; y < 4; ++y) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Hs[(16 * x + 4 * v + kq) * HP + 16 * y + i16] += acc[t][v];
+            for (int v = 0; v < 4; ++v) part[(16 * x + 4 * v + kq) * HP + 16 * y + i16] += acc[t][v];
             ++t;
           }
       }
       __syncthreads();
     }
+    for (int e = tid; e < PR * PR; e += JT) {
+      const int r = e >> 6, c = e & 63;
+      if ((r >> 4) <= (c >> 4)) Hs[r * HP + c] += Ws[r * HP + c];
+    }
+    __syncthreads();
     // mirror the strictly-upper tiles, identity into W
-    for (int e = tid; e < PR * PR; e += 256) {
+    for (int e = tid; e < PR * PR; e += JT) {
       const int r = e >> 6, c = e & 63;
       if ((r >> 4) > (c >> 4)) Hs[r * HP + c] = Hs[c * HP + r];
       Ws[r * HP + c] = (r == c) ? 1.0 : 0.0;
@@ -198,16 +212,19 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
   // (floor2, long2: read at the top of the round)
   const int nrounds = full ? PR - 1 : SB;
   double meas2 = 0.0;   // largest squared admixture weight seen by this thread
-  // This thread's share of a step: column pair b2 (of H and W), H row pairs a0 + 8k, W rows a0 + 8k.
+  // This thread's share of a step: column pair b2 (of H and W), H row pairs a0 + NA*k, W rows a0 + NA*k.
   // The (p, q) of a pair is carried from step to step: circle method (p, q advance by one mod 63; pair 0
   // keeps p = 63) when all 64 rows meet, else p = pair id and q walks cyclically over the second super-block.
+  constexpr int NA = JT / 32;        // row-pair groups: thread (b2, a0) takes the row pairs a0, a0 + NA, ...
+  constexpr int HB = 32 / NA;        // H blocks per thread and step
+  constexpr int WR = 64 / NA;        // W rows per thread and step
   const int b2 = tid & 31, a0 = tid >> 5;
   int pb = full ? (b2 == 0 ? PR - 1 : b2) : b2;
   int qb = full ? (b2 == 0 ? 0 : PR - 1 - b2) : SB + b2;
-  int pa[4], qa[4];
+  int pa[HB], qa[HB];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int m = a0 + 8 * k;
+  for (int k = 0; k < HB; ++k) {
+    const int m = a0 + NA * k;
     pa[k] = full ? (m == 0 ? PR - 1 : m) : m;
     qa[k] = full ? (m == 0 ? 0 : PR - 1 - m) : SB + m;
   }
@@ -259,23 +276,23 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
       // all loads first, then the arithmetic, then all stores: the blocks are disjoint, which the compiler
       // cannot know, and it would otherwise wait out one LDS round trip per block
       const double cb = cs_c[b2], sb = cs_s[b2];
-      double ca[4], sa[4], h00[4], h01[4], h10[4], h11[4], wp[8], wq[8];
+      double ca[HB], sa[HB], h00[HB], h01[HB], h10[HB], h11[HB], wp[WR], wq[WR];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        ca[k] = cs_c[a0 + 8 * k];
-        sa[k] = cs_s[a0 + 8 * k];
+      for (int k = 0; k < HB; ++k) {
+        ca[k] = cs_c[a0 + NA * k];
+        sa[k] = cs_s[a0 + NA * k];
         h00[k] = Hs[pa[k] * HP + pb];
         h01[k] = Hs[pa[k] * HP + qb];
         h10[k] = Hs[qa[k] * HP + pb];
         h11[k] = Hs[qa[k] * HP + qb];
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        wp[k] = Ws[(a0 + 8 * k) * HP + pb];
-        wq[k] = Ws[(a0 + 8 * k) * HP + qb];
+      for (int k = 0; k < WR; ++k) {
+        wp[k] = Ws[(a0 + NA * k) * HP + pb];
+        wq[k] = Ws[(a0 + NA * k) * HP + qb];
       }
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {   // H block (a0 + 8k, b2) <- R_a^T H R_b
+      for (int k = 0; k < HB; ++k) {   // H block (a0 + NA k, b2) <- R_a^T H R_b
         const double t00 = ca[k] * h00[k] - sa[k] * h10[k], t01 = ca[k] * h01[k] - sa[k] * h11[k];
         const double t10 = sa[k] * h00[k] + ca[k] * h10[k], t11 = sa[k] * h01[k] + ca[k] * h11[k];
         h00[k] = cb * t00 - sb * t01;
@@ -284,27 +301,27 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
         h11[k] = sb * t10 + cb * t11;
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {   // W columns (pb, qb), row a0 + 8k
+      for (int k = 0; k < WR; ++k) {   // W columns (pb, qb), row a0 + NA k
         const double x0 = cb * wp[k] - sb * wq[k];
         wq[k] = sb * wp[k] + cb * wq[k];
         wp[k] = x0;
       }
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < HB; ++k) {
         Hs[pa[k] * HP + pb] = h00[k];
         Hs[pa[k] * HP + qb] = h01[k];
         Hs[qa[k] * HP + pb] = h10[k];
         Hs[qa[k] * HP + qb] = h11[k];
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        Ws[(a0 + 8 * k) * HP + pb] = wp[k];
-        Ws[(a0 + 8 * k) * HP + qb] = wq[k];
+      for (int k = 0; k < WR; ++k) {
+        Ws[(a0 + NA * k) * HP + pb] = wp[k];
+        Ws[(a0 + NA * k) * HP + qb] = wq[k];
       }
     }
     advance(b2, pb, qb);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) advance(a0 + 8 * k, pa[k], qa[k]);
+    for (int k = 0; k < HB; ++k) advance(a0 + NA * k, pa[k], qa[k]);
     __syncthreads();
   }
   // squared row lengths after this visit (the diagonal of the rotated Gram block)
@@ -320,7 +337,7 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
     int roff[16];
 #pragma unroll
     for (int t = 0; t < 16; ++t) roff[t] = grow(4 * t + kq) * nP + i16;
-    for (int c = w; c < nchunks; c += 4) {
+    for (int c = w; c < nchunks; c += JW) {
       double pb[16];
 #pragma unroll
       for (int t = 0; t < 16; ++t) pb[t] = Ab[roff[t] + 16 * c];
@@ -344,7 +361,7 @@ __device__ __noinline__ double jacobi_visit(double* Ab, double* len2b, int nP, i
 // The whole solve of all images: workgroup (image b, slot pr) visits the pair `pr` of every tournament round
 // of every sweep; after a sweep, slot 0 decides convergence and re-measures which rows are the r longest.
 // A and len2 are written and re-read by different workgroups between barriers, hence no __restrict__.
-__global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, int nP, int nsb, int r, JacobiCtl* ctl, double* len2,
+__global__ __launch_bounds__(JT) void jacobi_solve_kernel(double* A, int n, int nP, int nsb, int r, JacobiCtl* ctl, double* len2,
                                                               const int* __restrict__ band, int* img_status, long long limit_ticks) {
   const int npairs = nsb >> 1;
   const int tid = threadIdx.x;
@@ -396,9 +413,9 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
     // ---- end of the sweep: slot 0 decides convergence and finds the squared length of the r-th longest row
     if (pr == 0) {
       double* l2 = Hs;   // 4096 doubles fit
-      for (int k = tid; k < n; k += 256) l2[k] = len2b[k];
+      for (int k = tid; k < n; k += JT) l2[k] = len2b[k];
       __syncthreads();
-      for (int k = tid; k < n; k += 256) {
+      for (int k = tid; k < n; k += JT) {
         const double v = l2[k];
         int rank = 0;
         for (int j = 0; j < n; ++j) {
@@ -420,7 +437,7 @@ __global__ __launch_bounds__(256, 2) void jacobi_solve_kernel(double* A, int n, 
   if (!alive) {
     // a wait ran out: poison this slot's share of the rows so that nothing downstream passes for a result
     const double qnan = __longlong_as_double(0x7ff8000000000000LL);
-    for (long e = tid; e < (long)PR * nP; e += 256) Ab[(long)pr * PR * nP + e] = qnan;
+    for (long e = tid; e < (long)PR * nP; e += JT) Ab[(long)pr * PR * nP + e] = qnan;
     if (img_status && tid == 0) img_status[b] = 1;
   }
 }
@@ -523,11 +540,11 @@ hipError_t launch_jacobi_eigen(double* A, int B, int n, int nP, int r, void* ctl
   // the workgroups of one image wait for one another, so one image has to fit the device
   static PerDeviceInt cache;
   int capacity = 0;
-  const hipError_t ec = resident_workgroups(cache, jacobi_solve_kernel, 256, 0, &capacity);
+  const hipError_t ec = resident_workgroups(cache, jacobi_solve_kernel, JT, 0, &capacity);
   if (ec != hipSuccess) return ec;
   if (npairs > capacity) return hipErrorInvalidValue;
   hipLaunchKernelGGL(jacobi_init_kernel, dim3(B), dim3(256), 0, st, A, n, nP, ctl, preset_done);
-  hipLaunchKernelGGL(jacobi_solve_kernel, dim3((unsigned)(B * npairs)), dim3(256), 0, st, A, n, nP, nsb, r, ctl, len2,
+  hipLaunchKernelGGL(jacobi_solve_kernel, dim3((unsigned)(B * npairs)), dim3(JT), 0, st, A, n, nP, nsb, r, ctl, len2,
                      band, img_status, barrier_limit_ticks());
   return hipGetLastError();
 }

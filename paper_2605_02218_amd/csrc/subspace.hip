@@ -39,7 +39,7 @@ constexpr int kMaxBlockSteps = 3;
 // Ritz solve (its last sweeps visit every pair).
 constexpr double kBandTol = 1e-9;
 constexpr double kPivotOnePass = 0.01; // final step: above this one Cholesky-QR pass leaves the rows orthonormal to ~1e-14
-constexpr size_t kCholLdsFixed = (size_t)(2 * NB * NBP) * sizeof(double);   // plus P doubles: the diagonal of S
+constexpr size_t kCholLdsFixed = (size_t)(2 * NB * NBP + NB) * sizeof(double);   // plus P doubles: the diagonal of S
 
 __global__ void omega_kernel(double* __restrict__ om, int P, int n, int nP) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -58,9 +58,13 @@ __device__ __forceinline__ double lane_value(double v, int l) {
 }
 
 // Factors the 64 x 64 block `a` (LDS, pitch NBP, lower triangle) in one wave: lane i holds row i.  The factor
-// goes to `fac` (lower triangle, zeros above).  Pivots are floored at `floor_`.  Not inlined, so that the 64
-// row registers do not compete with the caller's.
-__device__ __noinline__ void potrf_wave(const double* a, double* fac, double floor_) {
+// goes to `fac` (lower triangle, zeros above).  Pivots are floored at `floor_`.  Column k: pivot from lane k, scaled
+// column l_ik = a_ik / sqrt(a_kk) (lane i), then a_ij -= l_ik l_jk.  The l_jk of the other lanes come through
+// `col` (64 doubles of LDS): every lane posts its l_ik and reads the column back as broadcast loads, two values
+// per load (a wave's LDS accesses complete in order, so no barrier is needed; reading them lane by lane with
+// v_readlane took two such instructions and their wait states per value and ran at twice the time).  Not inlined,
+// so that the 64 row registers do not compete with the caller's.
+__device__ __noinline__ void potrf_wave(const double* a, double* fac, double* col, double floor_) {
   const int lane = threadIdx.x & 63;
   double row[NB];
 #pragma unroll
@@ -73,8 +77,11 @@ __device__ __noinline__ void potrf_wave(const double* a, double* fac, double flo
     rs = rs * fma(-0.5 * akk, rs * rs, 1.5);
     const double lk = (lane == k) ? akk * rs : row[k] * rs;
     row[k] = lk;
+    if (k + 1 < NB) {
+      col[lane] = lk;
 #pragma unroll
-    for (int j = k + 1; j < NB; ++j) row[j] = fma(-lk, lane_value(lk, j), row[j]);
+      for (int j = k + 1; j < NB; ++j) row[j] = fma(-lk, col[j], row[j]);
+    }
   }
 #pragma unroll
   for (int k = 0; k < NB; ++k) fac[lane * NBP + k] = (k <= lane) ? row[k] : 0.0;
@@ -88,13 +95,14 @@ __device__ __noinline__ void potrf_wave(const double* a, double* fac, double flo
 // On return the strictly-lower blocks of S hold L; its diagonal blocks are represented by their inverses.
 // Pivots are floored at 1e-28 * trace(first block) so that a numerically rank-deficient block cannot
 // produce NaNs (the residual check afterwards decides whether the result is usable).
-// Dynamic LDS: 2 * 64 * 65 doubles.
+// Dynamic LDS: 2 * 64 * 65 + 64 + P doubles.
 __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict__ Dinv, int P, int* skip_until, int* last_orth, int step,
                                                    int last_free_step, int next_weight) {
   extern __shared__ double lds[];
   double* a = lds;                  // [64][65] diagonal block, later the inverse of its factor
   double* fac = lds + NB * NBP;     // [64][65] the factor (lower triangle) and scratch (upper triangle)
-  double* diag0 = lds + 2 * NB * NBP;   // [P] the diagonal of S before any update: squared row lengths
+  double* col = lds + 2 * NB * NBP;     // [64] column exchange of the one-wave factorisation
+  double* diag0 = col + NB;             // [P] the diagonal of S before any update: squared row lengths
   const int b = blockIdx.x;
   if (skip_until && skip_until[b] > step) return;   // this image does not orthonormalise at this step
   double* Sb = S + (long)b * P * P;
@@ -119,7 +127,7 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
     for (int i = 0; i < NB; ++i) tr += a[i * NBP + i];   // same value in every thread
     floor_ = 1e-300 + 1e-28 * tr;
   }
-  if (w == 0) potrf_wave(a, fac, floor_);
+  if (w == 0) potrf_wave(a, fac, col, floor_);
   __syncthreads();
 
   for (int J = 0; J < nblk; ++J) {
@@ -262,7 +270,7 @@ __global__ __launch_bounds__(512) void chol_kernel(double* S, double* __restrict
         // one wave wrote the block and one wave reads it: its LDS writes are complete once the counter says so
         __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
         __builtin_amdgcn_wave_barrier();
-        potrf_wave(a, fac, floor_);
+        potrf_wave(a, fac, col, floor_);
       }
     }
     __syncthreads();
