@@ -134,6 +134,31 @@ def stage_times(C, p, dev, ws, steps):
     return out, probe
 
 
+def gram_flops(B, M, d, tile):
+    """Flops the Gram kernel executes: square tiles on and below the diagonal only (the rest is mirrored)."""
+    t = (M + tile - 1) // tile
+    return 2.0 * B * (t * (t + 1) // 2) * tile * tile * d
+
+
+def contraction_fractions(w, modes, stages):
+    """Fraction of the MFMA peak of the stages that are contractions, from the stage times of the same run: executed
+    flops (the three bf16 planes of the folded query matrix counted three times, Gram tiles on and below the diagonal
+    only) over the stage's time, which also holds that stage's small non-MFMA kernels."""
+    import covspec_inputs as I
+    B, N, d, T = w.batch, w.n_tokens, w.d_model, w.n_query
+    if w.dtype != I.BF16 or modes != (0, 0):
+        return None
+    peak = PEAK["mfma_bf16_TFLOPs"] * 1e12
+    planes = 3
+    work = {"token_projection": 2.0 * B * N * d * d,
+            "query_side (e(q), folded query matrix in 3 planes)": 2.0 * B * T * d * d * (1 + planes),
+            "relevance (token x folded query products in 3 planes)": 2.0 * B * N * d * T * planes,
+            "gram (tiles on and below the diagonal)": gram_flops(B, w.preselect_m, d, 128)}
+    key = {"token_projection": "token_projection", "query_side (e(q), folded query matrix in 3 planes)": "query_side",
+           "relevance (token x folded query products in 3 planes)": "relevance", "gram (tiles on and below the diagonal)": "gram"}
+    return {k: round(v / (stages[key[k]] * 1e-3) / peak, 4) for k, v in work.items() if stages[key[k]] > 0}
+
+
 def roofline_for(w, p, p_modes, stages, probe_ms, C):
     """Roofline object of the kernel the step spends most of its time in.
 
@@ -156,9 +181,10 @@ def roofline_for(w, p, p_modes, stages, probe_ms, C):
                      stages["activity"]),
         "gather": ("gather_rows_kernel", "hbm", PEAK["hbm_GBps"], "GB/s", 2.0 * B * k * d * e / 1e9, 1,
                    stages["gather"]),
-        "gram": ("gemm_nt_kernel<bf16,gather,f64>" if (bf and p_modes[1] == 0) else "gemm64_kernel<gather>",
+        # the Gram matrix is symmetric: only the tiles on and below the diagonal are computed, and only those are counted
+        "gram": ("gemm_gram_dma_kernel (tiles on and below the diagonal)" if (bf and p_modes[1] == 0) else "gemm64_kernel<gather> (tiles on and below the diagonal)",
                  "mfma", PEAK["mfma_bf16_TFLOPs"] if (bf and p_modes[1] == 0) else PEAK["mfma_fp64_TFLOPs"],
-                 "TFLOP/s", 2.0 * B * M * M * d / 1e12, 1, stages["gram"]),
+                 "TFLOP/s", gram_flops(B, M, d, 128 if (bf and p_modes[1] == 0) else 64) / 1e12, 1, stages["gram"]),
     }
     n_probe, pr, pc, pk = C.probe_launches(p)
     if n_probe > 0 and probe_ms > 0:
@@ -171,7 +197,7 @@ def roofline_for(w, p, p_modes, stages, probe_ms, C):
     kern, bound, peak, unit, work, launches, ms = cand[dom]
     achieved = work / (ms / 1e3)
     # the counter summary covers workload 5 in the paper pipeline; names as the profiler prints them
-    prof_name = {"gemm_nt_dma_kernel<rownorm2>": "gemm_nt_dma_kernel<1>", "activity_kernel": "activity_kernel<"}.get(kern)
+    prof_name = {"gemm_nt_dma_kernel<rownorm2>": "gemm_nt_dma_kernel<1, 4>", "activity_kernel": "activity_kernel<"}.get(kern)
     traffic = counter_traffic("reduce5", [prof_name]) if (w.cid == 5 and p_modes == (0, 0) and prof_name) else None
     return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
             "frac": round(achieved / peak, 5), "traffic": traffic, "kernel": kern,
@@ -576,6 +602,7 @@ def main():
             else "variant: attention-softmax relevance + greedy residual picks", "entry_point": "covspec_reduce"},
         "roofline": roofline_for(w, p, modes, stages, probe_ms, C),
         "stages_ms": {k: round(v, 4) for k, v in stages.items()},
+        "mfma_peak_fraction_by_stage": contraction_fractions(w, modes, stages),
         # the stages grouped by the entry point that runs them on its own
         "entry_points_ms": {"covspec_score": round(sum(stages[k] for k in ("query_side", "token_projection", "relevance", "activity", "fuse")), 4),
                             "covspec_select": round(sum(stages[k] for k in ("preselect", "gram", "lowrank", "keep")), 4),
