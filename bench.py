@@ -173,8 +173,8 @@ def roofline_for(w, p, p_modes, stages, probe_ms, C):
     bf = e == 2
     # name -> (kernel, bound, peak, unit, algorithmic work per launch, launches per step, ms per launch)
     cand = {
-        "token_projection": ("gemm_nt_dma_kernel<rownorm2>" if (bf and p_modes[0] == 0) else
-                             "gemm_nt_dma_kernel<store>" if bf else "gemm64_kernel<f32>",
+        "token_projection": ("gemm_nt_ring_kernel<rownorm2>" if (bf and p_modes[0] == 0) else
+                             "gemm_nt_ring_kernel<store>" if bf else "gemm64_kernel<f32>",
                              "mfma", PEAK["mfma_bf16_TFLOPs"] if bf else PEAK["mfma_fp64_TFLOPs"], "TFLOP/s",
                              2.0 * B * N * d * d / 1e12, 1, stages["token_projection"]),
         "activity": ("activity_kernel", "hbm", PEAK["hbm_GBps"], "GB/s", (K + 1) * B * N * d * e / 1e9, 1,
@@ -197,7 +197,7 @@ def roofline_for(w, p, p_modes, stages, probe_ms, C):
     kern, bound, peak, unit, work, launches, ms = cand[dom]
     achieved = work / (ms / 1e3)
     # the counter summary covers workload 5 in the paper pipeline; names as the profiler prints them
-    prof_name = {"gemm_nt_dma_kernel<rownorm2>": "gemm_nt_dma_kernel<1, 4>", "activity_kernel": "activity_kernel<"}.get(kern)
+    prof_name = {"gemm_nt_ring_kernel<rownorm2>": "gemm_nt_ring_kernel<1>", "activity_kernel": "activity_kernel<"}.get(kern)
     traffic = counter_traffic("reduce5", [prof_name]) if (w.cid == 5 and p_modes == (0, 0) and prof_name) else None
     return {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
             "frac": round(achieved / peak, 5), "traffic": traffic, "kernel": kern,
