@@ -57,6 +57,25 @@ def test_score_matches_oracle(C, name, rel_mode):
             assert abs(float(sq[b].astype(np.float64).sum()) - 1.0) < 1e-4
 
 
+def test_large_product_path_with_an_odd_number_of_k_tiles_and_ragged_edges(C):
+    """The 256x256-tile kernel of the large bf16 products (taken from 512 tiles up) on a shape none of the five
+    workloads has: K = 320 is five 64-wide k-tiles (an odd count), 300 token rows and 320 / 270 output columns end inside
+    a tile in both directions (rows beyond the end load zeros), with the row-norm epilogue (projection) and the store
+    epilogue (token x folded-query products)."""
+    w = I.small_workload(cid=15, name="ring-edges", batch=128, n_tokens=300, d_model=320, dtype=I.BF16, n_query=90,
+                         n_heads=4, keep_k=40, preselect_m=80, rank_r=16, factor_rank=64, n_act_layers=1)
+    batch = U.gen_batch(w)
+    dev = U.upload(batch, w.dtype)
+    p = U.lib_params(C, w, w.batch)
+    sq, sa, sf = C.score(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    sq, sf = _cpu(sq), _cpu(sf)
+    op = U.oracle_params(w)
+    for b in range(w.batch):
+        ref = U.oracle_image(w, batch, b, op)
+        U.assert_scores_close(sq[b], ref["s_query"], w.dtype, "ring-edges s_query[%d]" % b)
+        U.assert_scores_close(sf[b], ref["s_fused"], w.dtype, "ring-edges s_fused[%d]" % b)
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 def test_score_without_weights_or_hidden(C, name):
     w = SMALL[name]
