@@ -131,22 +131,52 @@ __device__ __forceinline__ float sum_planes(const float* src, int planes, long p
   return v;
 }
 
-__global__ void sum_split3_kernel(const float* __restrict__ src, int planes, long plane_stride, long rows, int d,
-                                  long rpg, bf16_t* __restrict__ out) {
-  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+// V elements of a row per thread (V = 4 when d % 4 == 0 and the planes and the output start on 16- / 8-byte boundaries:
+// one 16-byte load per plane and one 8-byte store per output plane; else V = 1).  The sum over the planes is taken in
+// plane order per element, the same in both widths.
+template <int V>
+__global__ __launch_bounds__(256) void sum_split3_kernel(const float* __restrict__ src, int planes, long plane_stride, long rows, int d,
+                                                         long rpg, bf16_t* __restrict__ out) {
+  const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * V;
   if (i >= rows * d) return;
-  long r = i / d;
-  int c = (int)(i - r * d);
-  float v = sum_planes(src, planes, plane_stride, i);
-  bf16_t hi = f32_to_bf16_rne(v);
-  float r1 = v - bf16_to_f32(hi);  // exact
-  bf16_t mid = f32_to_bf16_rne(r1);
-  float r2 = r1 - bf16_to_f32(mid);  // exact
-  bf16_t lo = f32_to_bf16_rne(r2);
-  long g = r / rpg, j = r - g * rpg;
-  out[((g * 3 + 0) * rpg + j) * d + c] = hi;
-  out[((g * 3 + 1) * rpg + j) * d + c] = mid;
-  out[((g * 3 + 2) * rpg + j) * d + c] = lo;
+  const long r = i / d;
+  const int c = (int)(i - r * d);
+  float v[V];
+  if (V == 4) {
+    const f32x4_t x = *(const f32x4_t*)(src + i);
+#pragma unroll
+    for (int e = 0; e < V; ++e) v[e] = x[e];
+    for (int p = 1; p < planes; ++p) {
+      const f32x4_t y = *(const f32x4_t*)(src + p * plane_stride + i);
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[e] += y[e];
+    }
+  } else {
+    v[0] = sum_planes(src, planes, plane_stride, i);
+  }
+  bf16_t hi[V], mid[V], lo[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    hi[e] = f32_to_bf16_rne(v[e]);
+    const float r1 = v[e] - bf16_to_f32(hi[e]);  // exact
+    mid[e] = f32_to_bf16_rne(r1);
+    const float r2 = r1 - bf16_to_f32(mid[e]);   // exact
+    lo[e] = f32_to_bf16_rne(r2);
+  }
+  const long g = r / rpg, j = r - g * rpg;
+  bf16_t* o0 = out + ((g * 3 + 0) * rpg + j) * d + c;
+  bf16_t* o1 = out + ((g * 3 + 1) * rpg + j) * d + c;
+  bf16_t* o2 = out + ((g * 3 + 2) * rpg + j) * d + c;
+  if (V == 4) {
+    typedef unsigned short u16x4_t __attribute__((ext_vector_type(4)));
+    *(u16x4_t*)o0 = (u16x4_t){hi[0], hi[1], hi[2], hi[3]};
+    *(u16x4_t*)o1 = (u16x4_t){mid[0], mid[1], mid[2], mid[3]};
+    *(u16x4_t*)o2 = (u16x4_t){lo[0], lo[1], lo[2], lo[3]};
+  } else {
+    *o0 = hi[0];
+    *o1 = mid[0];
+    *o2 = lo[0];
+  }
 }
 
 // ---------------------------------------------------------------- cosine-max epilogue (paper Sec. III-A.1)
@@ -412,8 +442,10 @@ hipError_t launch_convert(const void* src, int in_type, void* dst, bool out_f64,
 
 hipError_t launch_sum_split3(const float* src, int planes, long plane_stride, long rows, int d, long rows_per_group,
                              unsigned short* out, hipStream_t st) {
-  dim3 grid(blocks_for(rows * d, 256)), block(256);
-  hipLaunchKernelGGL(sum_split3_kernel, grid, block, 0, st, src, planes, plane_stride, rows, d, rows_per_group, out);
+  const bool wide = d % 4 == 0 && plane_stride % 4 == 0 && ((uintptr_t)src & 15) == 0 && ((uintptr_t)out & 7) == 0;
+  dim3 block(256);
+  if (wide) hipLaunchKernelGGL(sum_split3_kernel<4>, dim3(blocks_for(rows * d / 4, 256)), block, 0, st, src, planes, plane_stride, rows, d, rows_per_group, out);
+  else hipLaunchKernelGGL(sum_split3_kernel<1>, dim3(blocks_for(rows * d, 256)), block, 0, st, src, planes, plane_stride, rows, d, rows_per_group, out);
   return hipGetLastError();
 }
 
