@@ -180,33 +180,75 @@ __global__ __launch_bounds__(256) void sum_split3_kernel(const float* __restrict
 }
 
 // ---------------------------------------------------------------- cosine-max epilogue (paper Sec. III-A.1)
-// One wave per token; lanes stride over the query keywords.  The scalar arithmetic is fp64 so that the only
-// error left in the score is that of the fp32-accumulated contractions feeding it.
+// s_query[token] = max_j dot_j / max(|e(v)| |e(q_j)|, 1e-30), dot_j = the sum of the logit planes of keyword j.  The
+// scalar arithmetic is fp64 so that the only error left in the score is that of the fp32-accumulated contractions
+// feeding it.  Four lanes per token, 64 tokens of one image per workgroup: the keywords' 1 / |e(q_j)| are formed once
+// per workgroup (LDS) and a token's |e(v)| once, so that a keyword costs a token one multiplication
+// (max_j dot_j / (|v| |q_j|) = (max_j dot_j / |q_j|) / |v|; a wave per token with a square root and a division per
+// keyword was bound by those: 156 us for workload 5 where its 283 MB of logits are 50 us of HBM time).  Where the
+// floor could bind (|v| |q_j| < 1e-30 for some keyword that is not a zero vector) the token takes the literal formula.
 template <typename F>
 __global__ __launch_bounds__(256) void cosine_max_kernel(const F* __restrict__ logits, int planes,
                                                           const F* __restrict__ vnorm2, int nparts,
                                                           const F* __restrict__ qnorm2, float* __restrict__ s_query,
-                                                          long tokens, int N, int T) {
-  const int lane = threadIdx.x & 63;
-  const long token = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (token >= tokens) return;
-  const long b = token / N;
-  // the partial sums of |e(v)|^2: one load per lane and a wave sum instead of nparts loads that every lane repeats
+                                                          int N, int T) {
+  extern __shared__ double cm_lds[];    // [T] 1 / |e(q_j)| (0 for a zero vector), then the smallest non-zero |e(q_j)|
+  double* rq = cm_lds;
+  double* minq = cm_lds + T;
+  const int tid = threadIdx.x, q = tid & 3;
+  const int b = blockIdx.y;
+  if (tid == 0) *minq = 1e300;
+  __syncthreads();
+  double mine = 1e300;
+  for (int j = tid; j < T; j += 256) {
+    const double sq = sqrt((double)qnorm2[(long)b * T + j]);
+    rq[j] = sq > 0.0 ? 1.0 / sq : 0.0;
+    if (sq > 0.0) mine = fmin(mine, sq);
+  }
+  mine = wave_min(mine);
+  if ((tid & 63) == 0 && mine < 1e300) atomicMin((unsigned long long*)minq, (unsigned long long)__double_as_longlong(mine));   // positive doubles order like their bits
+  __syncthreads();
+  const double smallest = *minq;
+  const int n = blockIdx.x * 64 + (tid >> 2);
+  if (n >= N) return;      // whole quads leave together
+  const long token = (long)b * N + n;
   double n2 = 0.0;
-  for (int t = lane; t < nparts; t += 64) n2 += (double)vnorm2[token * nparts + t];
-  n2 = wave_sum(n2);
+  for (int t = q; t < nparts; t += 4) n2 += (double)vnorm2[token * nparts + t];
+  n2 += __shfl_xor(n2, 1, 64);
+  n2 += __shfl_xor(n2, 2, 64);
   const double nv = sqrt(n2);
   const F* L = logits + token * (long)planes * T;
   double best = -INFINITY;
-  for (int j = lane; j < T; j += 64) {
-    double dot = (double)L[j];
-    for (int s = 1; s < planes; ++s) dot += (double)L[s * T + j];
-    double den = nv * sqrt((double)qnorm2[b * T + j]);
-    double c = dot / fmax(den, 1e-30);
-    best = fmax(best, c);
+  if (nv * smallest >= 1e-30) {
+    if (std::is_same<F, float>::value && (T & 3) == 0 && (((uintptr_t)logits) & 15) == 0) {
+      for (int j0 = 4 * q; j0 < T; j0 += 16) {
+        f32x4_t x = *(const f32x4_t*)((const float*)L + j0);
+        double d0 = x[0], d1 = x[1], d2 = x[2], d3 = x[3];
+        for (int s_ = 1; s_ < planes; ++s_) {
+          x = *(const f32x4_t*)((const float*)L + (long)s_ * T + j0);
+          d0 += x[0]; d1 += x[1]; d2 += x[2]; d3 += x[3];
+        }
+        best = fmax(best, fmax(fmax(d0 * rq[j0], d1 * rq[j0 + 1]), fmax(d2 * rq[j0 + 2], d3 * rq[j0 + 3])));
+      }
+    } else {
+      for (int j = q; j < T; j += 4) {
+        double dot = (double)L[j];
+        for (int s_ = 1; s_ < planes; ++s_) dot += (double)L[(long)s_ * T + j];
+        best = fmax(best, dot * rq[j]);
+      }
+    }
+    best = best / nv;     // nv > 0 here
+  } else {
+    for (int j = q; j < T; j += 4) {
+      double dot = (double)L[j];
+      for (int s_ = 1; s_ < planes; ++s_) dot += (double)L[(long)s_ * T + j];
+      const double den = nv * sqrt((double)qnorm2[(long)b * T + j]);
+      best = fmax(best, dot / fmax(den, 1e-30));
+    }
   }
-  best = wave_max(best);
-  if (lane == 0) s_query[token] = (float)best;
+  best = fmax(best, __shfl_xor(best, 1, 64));
+  best = fmax(best, __shfl_xor(best, 2, 64));
+  if (q == 0) s_query[token] = (float)best;
 }
 
 // ---------------------------------------------------------------- softmax relevance (variant)
@@ -451,10 +493,12 @@ hipError_t launch_sum_split3(const float* src, int planes, long plane_stride, lo
 
 hipError_t launch_cosine_max(const void* logits, int planes, const void* vnorm2, int nparts, const void* qnorm2, bool f64,
                              float* s_query, int B, int N, int T, hipStream_t st) {
-  long tokens = (long)B * N;
-  dim3 grid(blocks_for(tokens, 4)), block(256);
-  if (f64) hipLaunchKernelGGL((cosine_max_kernel<double>), grid, block, 0, st, (const double*)logits, planes, (const double*)vnorm2, nparts, (const double*)qnorm2, s_query, tokens, N, T);
-  else hipLaunchKernelGGL((cosine_max_kernel<float>), grid, block, 0, st, (const float*)logits, planes, (const float*)vnorm2, nparts, (const float*)qnorm2, s_query, tokens, N, T);
+  if (B <= 0 || N <= 0) return hipSuccess;
+  dim3 grid((unsigned)((N + 63) / 64), (unsigned)B), block(256);
+  const size_t lds = (size_t)(T + 1) * sizeof(double);
+  if (lds > 48 * 1024) return hipErrorInvalidValue;     // more than 6143 query keywords
+  if (f64) hipLaunchKernelGGL((cosine_max_kernel<double>), grid, block, lds, st, (const double*)logits, planes, (const double*)vnorm2, nparts, (const double*)qnorm2, s_query, N, T);
+  else hipLaunchKernelGGL((cosine_max_kernel<float>), grid, block, lds, st, (const float*)logits, planes, (const float*)vnorm2, nparts, (const float*)qnorm2, s_query, N, T);
   return hipGetLastError();
 }
 

@@ -76,6 +76,29 @@ def test_large_product_path_with_an_odd_number_of_k_tiles_and_ragged_edges(C):
         U.assert_scores_close(sf[b], ref["s_fused"], w.dtype, "ring-edges s_fused[%d]" % b)
 
 
+@pytest.mark.parametrize("name", ["fp32-ragged", "bf16-tiles"])
+def test_zero_tokens_and_zero_keywords_score_zero(C, name):
+    """A token or a query keyword that is the zero vector has no direction: its cosine is 0 (the denominator is
+    floored, Sec. III-A.1's score is undefined there).  One image gets two zero tokens and a zero keyword, another
+    only zero keywords but one."""
+    w = SMALL[name]
+    batch = {k: (v.copy() if hasattr(v, "copy") else v) for k, v in U.gen_batch(w).items()}
+    batch["X"][0, 3] = 0
+    batch["X"][0, w.n_tokens - 1] = 0
+    batch["Q"][0, 1] = 0
+    batch["Q"][1, 1:] = 0
+    dev = U.upload(batch, w.dtype)
+    p = U.lib_params(C, w, w.batch)
+    sq, _, sf = C.score(p, dev["X"], dev["hidden"], dev["Q"], dev["Wq"], dev["Wk"])
+    sq, sf = _cpu(sq), _cpu(sf)
+    assert np.isfinite(sq).all() and np.isfinite(sf).all()
+    assert sq[0, 3] == 0.0 and sq[0, w.n_tokens - 1] == 0.0
+    for b in range(w.batch):
+        ref = U.oracle_image(w, batch, b, U.oracle_params(w))
+        U.assert_scores_close(sq[b], ref["s_query"], w.dtype, "%s zero vectors s_query[%d]" % (name, b))
+        U.assert_scores_close(sf[b], ref["s_fused"], w.dtype, "%s zero vectors s_fused[%d]" % (name, b))
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 def test_score_without_weights_or_hidden(C, name):
     w = SMALL[name]
