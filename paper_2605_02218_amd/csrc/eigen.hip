@@ -57,6 +57,12 @@ struct JacobiCtl {
 // measures it also reduces it, so 3e-7 leaves the energies converged to well below their last bit.
 constexpr double kRotEps = 1e-15;   // rotations below this relative size are skipped
 constexpr double kConvTol = 3e-7;
+// A sweep over ALL pairs that measures a small largest weight w leaves weights of a few w^2 behind (the quadratic
+// convergence of the cyclic method; 1 to 4 w^2 on the workloads), so when such a sweep measures less than kEarlyTol
+// the sweep after it could only confirm: the solve ends there.  What it leaves in the Ritz residual, 2 to 4 w^2 <=
+// 1e-10, is a tenth of what the residual check accepts (with 2e-5 one image of 64 failed that check and paid for a
+// second pass).  Banded sweeps do not qualify: they leave the far pairs alone.
+constexpr double kEarlyTol = 5e-6;
 constexpr double kBandSwitch = 1e-2;   // banded sweeps while the previous sweep's largest weight is above this
 
 __global__ __launch_bounds__(256) void jacobi_init_kernel(const double* __restrict__ A, int n, int nP, JacobiCtl* ctl,
@@ -427,7 +433,8 @@ __global__ __launch_bounds__(JT) void jacobi_solve_kernel(double* A, int n, int 
       if (tid == 0) {
         cb->sweeps = sweep + 1;
         const unsigned long long m = __hip_atomic_load(&cb->maxoff[sweep], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (__longlong_as_double((long long)m) < kConvTol) __hip_atomic_store(&cb->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const double mw = __longlong_as_double((long long)m);
+        if (mw < kConvTol || (!banded && mw < kEarlyTol)) __hip_atomic_store(&cb->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
     target += npairs;
